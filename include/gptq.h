@@ -1,0 +1,146 @@
+/*
+ * gptq.h -- C ABI of the MI355X (gfx950) GPTQ per-layer quantization solver.
+ *
+ * The calls follow the steps of the GPTQ algorithm (Frantar et al., arXiv 2210.17323):
+ *   1. gptq_hessian_accumulate      H += 2 X X^T over chunks of calibration tokens  (Section 2; Alg. 1 caption)
+ *   2. gptq_damp_cholesky_inverse   U = Cholesky((H + lambda I)^-1)^T                (Section 3, Step 3; Alg. 1)
+ *   3. gptq_quantize_layer          the block / column loop with lazy batch updates  (Section 3, Step 2; Alg. 1)
+ *   4. gptq_pack                    dense 2/3/4-bit stream of the resulting codes    (Section 4, "Practical Speedups")
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer to memory owned by the caller, valid on the current
+ *     HIP device; the library never allocates or frees device memory.  Scratch space comes from a
+ *     caller-provided workspace whose size the matching *_workspace_bytes call returns.
+ *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues work on that stream and returns; it never synchronises.
+ *   - Return value: GPTQ_OK or an error code.  On error nothing has been enqueued and
+ *     gptq_last_error() (thread-local) describes the problem.  Arguments are validated on the host
+ *     before any launch; no C++ exception crosses this boundary.
+ *   - Not re-entrant on the same workspace: two calls sharing a workspace must be on the same stream.
+ */
+#ifndef GPTQ_MI355_H
+#define GPTQ_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GPTQ_API __attribute__((visibility("default")))
+
+enum {
+    GPTQ_OK = 0,
+    GPTQ_ERR_INVALID_ARG = 1,      /* null pointer, bad size, bad alignment, bad enum                   */
+    GPTQ_ERR_NOT_POSDEF = 2,       /* reported by gptq_check_info when a pivot was not positive          */
+    GPTQ_ERR_HIP = 3,              /* a HIP runtime call failed                                          */
+    GPTQ_ERR_UNSUPPORTED = 4,      /* valid request this build has no kernel for                         */
+    GPTQ_ERR_WORKSPACE = 5         /* workspace pointer null or smaller than *_workspace_bytes            */
+};
+
+enum { GPTQ_F16 = 0, GPTQ_BF16 = 1, GPTQ_F32 = 2 };          /* element types of X and W              */
+enum { GPTQ_GRID_MINMAX = 0, GPTQ_GRID_TERNARY = 1 };        /* quantization grids                    */
+
+GPTQ_API int gptq_version(void);
+GPTQ_API const char* gptq_last_error(void);
+
+/*
+ * Step 1 -- Hessian of the layer-wise objective, H = 2 X X^T (Section 2, text before Eq. 2; Alg. 1 caption).
+ *
+ *   H   [n x n] float32, ldh >= n.  Accumulated in place: H += 2 X X^T.  The caller zero-fills H
+ *       before the first chunk.  Only the UPPER triangle (column >= row) is defined afterwards;
+ *       entries below the diagonal hold unspecified partial values until gptq_hessian_symmetrize.
+ *   X   [n x t] one row per input channel, t tokens contiguous (ldx >= t), type xdtype
+ *       (GPTQ_F16 / GPTQ_BF16: products are exact in float32 and accumulated in float32 by the
+ *       matrix cores; GPTQ_F32: float32 matrix-core products).
+ *       X must be 16-byte aligned and ldx a multiple of 8 (f16/bf16) or 4 (f32) elements.
+ *   No normalisation by the token count is applied (the quantization result is invariant to the
+ *   scale of H).  n == 0 or t == 0 is a valid no-op.
+ */
+GPTQ_API int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int xdtype,
+                            int64_t n, int64_t t, int64_t ldx, void* stream);
+
+/* Copies the upper triangle of H onto the lower one (H[j][i] = H[i][j] for j > i). */
+GPTQ_API int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* stream);
+
+/*
+ * Step 2 -- dampening and the Cholesky factor of the inverse (Section 3, Step 3; Alg. 1, third statement).
+ *
+ *   lambda = percdamp * mean(diag H)  ("1% of the average diagonal value": percdamp = 0.01);
+ *   U = Cholesky((H + lambda I)^-1)^T, upper triangular with positive diagonal and
+ *   (H + lambda I)^-1 = U^T U.  Row j of U from the diagonal on is what Alg. 1 reads.
+ *
+ *   H_U       [n x n] float32, ld >= n.  In: only the upper triangle of H is read.  Out: U in the
+ *             upper triangle, zeros strictly below the diagonal.
+ *   ws        workspace of at least gptq_damp_cholesky_inverse_workspace_bytes(n) bytes, 256-byte aligned.
+ *   info_dev  device int.  Set to 0, or to the 1-based index of a column whose pivot was not
+ *             positive (then U is meaningless).  Read it after synchronising, e.g. through
+ *             gptq_check_info.  percdamp < 0 is invalid; percdamp == 0 is allowed.
+ *   Computed as a Cholesky factorisation taken from the last column backwards, H + lambda I = R R^T with R
+ *   upper triangular, followed by the triangular inverse U = R^-1 (the same matrix, by uniqueness of
+ *   the Cholesky factor), all in float32.
+ */
+GPTQ_API size_t gptq_damp_cholesky_inverse_workspace_bytes(int64_t n);
+GPTQ_API int gptq_damp_cholesky_inverse(float* H_U, int64_t ld, int64_t n, float percdamp,
+                               void* ws, size_t ws_bytes, int* info_dev, void* stream);
+
+/* Synchronises `stream`, reads *info_dev and returns GPTQ_OK or GPTQ_ERR_NOT_POSDEF
+ * (the failing 1-based column index is stored in *host_info if host_info is not NULL). */
+GPTQ_API int gptq_check_info(const int* info_dev, int* host_info, void* stream);
+
+/*
+ * Step 3 -- Algorithm 1: quantize W column by column in lazy blocks with error propagation.
+ *
+ *   W        [r x n] weights (rows = output features), type wdtype, ldw >= n.  Not modified: the
+ *            solver works on a float32 copy held in the workspace.
+ *   U        [n x n] float32 upper triangular factor from step 2, ldu >= n.
+ *   bits     2, 3 or 4 for GPTQ_GRID_MINMAX (codes in [0, 2^bits - 1]); ignored for
+ *            GPTQ_GRID_TERNARY (codes {0,1,2} = {-s, 0, +s}, zero point 1).
+ *   grid     GPTQ_GRID_MINMAX: uniform asymmetric min-max grid (Section 4, Setup), range widened to
+ *            contain 0: scale = (max(w,0) - min(w,0)) / maxq, zero = rint(-min(w,0)/scale), all-zero
+ *            input: scale 1, zero 0.  GPTQ_GRID_TERNARY: s = max|w| (1 if all zero).
+ *            code = clamp(rint(w/scale) + zero, 0, maxq), ties to even, evaluated in float32.
+ *   block    lazy-batch block size B (Section 3, Step 2).  This build supports B = 128.
+ *   group    0: one grid per row, fixed from the original W before the process.  g > 0: a new grid
+ *            for columns [j, j+g) whenever j % g == 0, taken from the current updated weights
+ *            (Section 4, "175 Billion Parameter Models").  Requires n % g == 0 and either
+ *            128 % g == 0 with g >= 8, or g % 128 == 0.
+ *   codes    [r x n] uint8 out, ldc >= n.
+ *   scales   [r x G] float32 out, zeros [r x G] int32 out, G = 1 (group == 0) or n / group; dense.
+ *   Wq       optional [r x n] float32 out (ldq >= n): the dequantised weights scale*(code - zero); may be NULL.
+ *   half_E2_rows  optional [r] float64 out: per row, (1/2) * sum over columns of E^2 where
+ *            E[:, j] = (W[:, j] - Q[:, j]) / U[j][j] at the time column j is quantized (Alg. 1).  Its
+ *            sum over rows equals (1/2) tr((W-Q)(H + lambda I)(W-Q)^T).  May be NULL.
+ *   ws       at least gptq_quantize_layer_workspace_bytes(r, n, block, group) bytes, 256-byte aligned.
+ *   r == 0 or n == 0 is a valid no-op.
+ */
+GPTQ_API size_t gptq_quantize_layer_workspace_bytes(int64_t r, int64_t n, int block, int64_t group);
+GPTQ_API int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
+                        const float* U, int64_t ldu,
+                        int bits, int grid, int block, int64_t group,
+                        uint8_t* codes, int64_t ldc, float* scales, int32_t* zeros,
+                        float* Wq, int64_t ldq, double* half_E2_rows,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Step 4 -- bit packing (the paper stores 3-bit weights densely, Section 4 "Practical Speedups",
+ * but prints no layout; this one is ours).
+ *
+ *   Per row, code k occupies bits [k*bits, (k+1)*bits) of a little-endian bit stream stored as
+ *   consecutive uint32 words; a code may straddle two words; the row is padded with zero bits to
+ *   a whole word: words_per_row = ceil(n * bits / 32).
+ *   codes [r x n] uint8 (ldc >= n), every code < 2^bits (higher bits are masked off);
+ *   out   [r x ld_out] uint32, ld_out >= words_per_row.  bits in {2, 3, 4}.
+ */
+GPTQ_API int gptq_pack(const uint8_t* codes, int64_t ldc, int64_t r, int64_t n, int bits,
+              uint32_t* out, int64_t ld_out, void* stream);
+/* Inverse of gptq_pack. */
+GPTQ_API int gptq_unpack(const uint32_t* words, int64_t ld_words, int64_t r, int64_t n, int bits,
+                uint8_t* codes, int64_t ldc, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPTQ_MI355_H */

@@ -1,0 +1,13 @@
+"""MI355X-native GPTQ layer solver: thin Python binding over the C-ABI library libgptq_mi355.so.
+
+All arithmetic runs in the hand-written HIP kernels under csrc/; PyTorch only provides device
+memory and streams.  There is no CPU fallback: loading fails loudly if the library is missing.
+"""
+from .binding import (  # noqa: F401
+    GptqError, lib, load_library, version, exported_symbols,
+    gptq_hessian_accumulate, gptq_hessian_symmetrize,
+    gptq_damp_cholesky_inverse, gptq_damp_cholesky_inverse_workspace_bytes, gptq_check_info,
+    gptq_quantize_layer, gptq_quantize_layer_workspace_bytes,
+    gptq_pack, gptq_unpack, packed_words_per_row,
+    GPTQ_GRID_MINMAX, GPTQ_GRID_TERNARY,
+)

@@ -1,0 +1,226 @@
+// Step 2: lambda = percdamp * mean(diag H); U = Cholesky((H + lambda I)^-1)^T
+// (Section 3, Step 3 and Alg. 1, third statement).
+//
+// Route: factor H + lambda I = R R^T with R upper triangular -- a Cholesky factorisation that starts at
+// the last column and moves backwards -- then invert the triangle, U = R^-1.  (H + lambda I)^-1 =
+// R^-T R^-1 = U^T U and the Cholesky factor with positive diagonal is unique, so this U is the
+// matrix Alg. 1 asks for, at half the flops of "Cholesky, invert, Cholesky again" and without ever
+// forming the explicit inverse.
+//
+// Blocked, right-looking, block size 128, everything in place in the upper triangle:
+//   for block b = last .. first:                       (columns [j0, j1))
+//     R_bb  = reverse-Cholesky of the 128x128 diagonal block (one workgroup, block in LDS),
+//             and its inverse R_bb^-1 kept in the workspace
+//     P     = H[0:j0, j0:j1] * R_bb^-T                  (GEMM; P is the panel of R above the block)
+//     H[0:j0, 0:j0] -= P P^T                            (GEMM, upper tiles only)
+//   for block b = first .. last:                        (in-place triangular inverse)
+//     R[b, right]    = -R_bb^-1 * R[b, right]
+//     R[above, right] += R[above, b] * R[b, right]      (the rank-128 update that carries the flops)
+//     R[above, b]    = R[above, b] * R_bb^-1
+//     R[b, b]        = R_bb^-1
+#include "common.h"
+
+namespace gptq {
+
+constexpr int NB = 128;
+constexpr int DP = NB + 1;      // LDS pitch of the diagonal-block kernels
+
+// One workgroup: mean of the diagonal in float64, lambda in float32, add it to the diagonal.
+__global__ __launch_bounds__(1024) void damp_kernel(float* H, int64_t ld, int64_t n, float percdamp, int* info) {
+    __shared__ double part[1024];
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) s += (double)H[i * ld + i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    const float lambda = percdamp * (float)(part[0] / (double)n);
+    for (int64_t i = threadIdx.x; i < n; i += 1024) H[i * ld + i] += lambda;
+    if (threadIdx.x == 0) *info = 0;
+}
+
+// Factor the diagonal block D = R R^T (R upper, processed from the last column backwards) and
+// invert R.  Rows/columns beyond nbk are padded with the identity.  One workgroup of 256 threads.
+//   H block  <- R (upper part; strictly lower part of the block zeroed)
+//   dinv     <- R^-1 as a dense 128 x 128 block (zeros below the diagonal)
+__global__ __launch_bounds__(256) void diag_block_kernel(float* Hblk, int64_t ld, int nbk, float* dinv, int* info, int col_base) {
+    extern __shared__ float sm[];
+    float* D = sm;                  // [NB][DP]
+    float* Xs = sm + NB * DP;       // [NB][DP]  inverse, Xs[k][c]
+    const int tid = threadIdx.x;
+    for (int q = tid; q < NB * NB; q += 256) {
+        const int i = q / NB, k = q % NB;
+        float v = (i == k) ? 1.f : 0.f;
+        if (i < nbk && k < nbk) v = (k >= i) ? Hblk[(int64_t)i * ld + k] : 0.f;
+        D[i * DP + k] = v;
+    }
+    __syncthreads();
+    for (int j = NB - 1; j >= 0; --j) {
+        float d = D[j * DP + j];
+        if (!(d > 0.f)) {
+            if (tid == 0) atomicCAS(info, 0, col_base + j + 1);
+            d = 1.f;
+        }
+        const float rjj = sqrtf(d);
+        __syncthreads();
+        if (tid < j) D[tid * DP + j] = D[tid * DP + j] / rjj;
+        if (tid == j) D[j * DP + j] = rjj;
+        __syncthreads();
+        // D[i][k] -= R[i][j] * R[k][j] for i <= k < j
+        for (int q = tid; q < j * j; q += 256) {
+            const int i = q / j, k = q % j;
+            if (i <= k) D[i * DP + k] -= D[i * DP + j] * D[k * DP + j];
+        }
+        // (the next iteration's reads are ordered by the barrier after the pivot read)
+        __syncthreads();
+    }
+    // inverse by back substitution, one column per thread: R x = e_c
+    if (tid < NB) {
+        const int c = tid;
+        for (int i = NB - 1; i > c; --i) Xs[i * DP + c] = 0.f;
+        Xs[c * DP + c] = 1.f / D[c * DP + c];
+        for (int i = c - 1; i >= 0; --i) {
+            float s = 0.f;
+            for (int k = i + 1; k <= c; ++k) s = fmaf(D[i * DP + k], Xs[k * DP + c], s);
+            Xs[i * DP + c] = -s / D[i * DP + i];
+        }
+    }
+    __syncthreads();
+    for (int q = tid; q < NB * NB; q += 256) {
+        const int i = q / NB, k = q % NB;
+        dinv[q] = Xs[i * DP + k];
+        if (i < nbk && k < nbk) Hblk[(int64_t)i * ld + k] = (k >= i) ? D[i * DP + k] : 0.f;
+    }
+}
+
+// dst[rows x cols] (ld_dst) = src[rows x cols] (ld_src), optionally only the upper triangle of a
+// square block (strictly lower part written as zero).
+__global__ __launch_bounds__(256) void copy_block_kernel(float* dst, int64_t ld_dst, const float* src, int64_t ld_src,
+                                                         int64_t rows, int cols, int upper_square) {
+    const int64_t total = rows * cols;
+    for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < total; q += (int64_t)gridDim.x * 256) {
+        const int64_t i = q / cols;
+        const int k = (int)(q % cols);
+        float v = src[i * ld_src + k];
+        if (upper_square && k < i) v = 0.f;
+        dst[i * ld_dst + k] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_lower_kernel(float* H, int64_t ld, int64_t n) {
+    const int64_t row = blockIdx.x;
+    for (int64_t k = threadIdx.x; k < row; k += 256) H[row * ld + k] = 0.f;
+}
+
+}  // namespace gptq
+
+using namespace gptq;
+
+extern "C" size_t gptq_damp_cholesky_inverse_workspace_bytes(int64_t n) {
+    if (n <= 0) return 256;
+    const size_t nblk = (size_t)ceil_div(n, NB);
+    const size_t dinv = nblk * NB * NB * sizeof(float);
+    const size_t panel = round_up((size_t)n * NB * sizeof(float), 256);
+    return dinv + panel + 256;
+}
+
+extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float percdamp,
+                                          void* ws, size_t ws_bytes, int* info_dev, void* stream) {
+    if (n < 0) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: negative size");
+    if (!info_dev) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: info_dev is null");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n == 0) return GPTQ_OK;
+    if (!H) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: H is null");
+    if (ld < n || ld % 4 || !aligned(H, 16))
+        return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: need ld >= n, ld %% 4 == 0 and a 16-byte aligned H");
+    if (!(percdamp >= 0.f)) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: percdamp must be >= 0");
+    if (!ws || !aligned(ws, 256) || ws_bytes < gptq_damp_cholesky_inverse_workspace_bytes(n))
+        return fail(GPTQ_ERR_WORKSPACE, "damp_cholesky_inverse: workspace missing, misaligned or too small");
+
+    const int64_t nblk = ceil_div(n, NB);
+    float* dinv = static_cast<float*>(ws);
+    float* P = dinv + nblk * NB * NB;
+    constexpr size_t diag_lds = 2 * NB * DP * sizeof(float);
+    GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(diag_block_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)diag_lds));
+
+    hipLaunchKernelGGL(damp_kernel, dim3(1), dim3(1024), 0, s, H, ld, n, percdamp, info_dev);
+    GPTQ_LAUNCH_CHECK();
+
+    // ---- H + lambda I = R R^T, from the last block backwards
+    for (int64_t b = nblk - 1; b >= 0; --b) {
+        const int64_t j0 = b * NB;
+        const int nbk = (int)std::min<int64_t>(NB, n - j0);
+        float* Dblk = H + j0 * ld + j0;
+        float* dinv_b = dinv + b * NB * NB;
+        hipLaunchKernelGGL(diag_block_kernel, dim3(1), dim3(256), diag_lds, s, Dblk, ld, nbk, dinv_b, info_dev, (int)j0);
+        GPTQ_LAUNCH_CHECK();
+        if (j0 == 0) break;
+        // P = H[0:j0, j0:j1] * R_bb^-T
+        GemmF32 g{};
+        g.A = H + j0; g.lda = ld; g.B = dinv_b; g.ldb = NB; g.C = P; g.ldc = NB;
+        g.M = j0; g.N = nbk; g.K = nbk; g.alpha = 1.f; g.b_is_nk = true; g.overwrite = true;
+        int rc = launch_gemm_f32(g, s);
+        if (rc) return rc;
+        const int cb = (int)std::min<int64_t>(ceil_div(j0 * nbk, 256), 4096);
+        hipLaunchKernelGGL(copy_block_kernel, dim3(cb), dim3(256), 0, s, H + j0, ld, (const float*)P, (int64_t)NB, j0, nbk, 0);
+        GPTQ_LAUNCH_CHECK();
+        // H[0:j0, 0:j0] -= P P^T (upper tiles)
+        GemmF32 u{};
+        u.A = P; u.lda = NB; u.B = P; u.ldb = NB; u.C = H; u.ldc = ld;
+        u.M = j0; u.N = j0; u.K = nbk; u.alpha = -1.f; u.b_is_nk = true; u.overwrite = false;
+        u.upper_only = true; u.crow0 = 0; u.ccol0 = 0;
+        rc = launch_gemm_f32(u, s);
+        if (rc) return rc;
+    }
+
+    // ---- U = R^-1 in place
+    for (int64_t b = 0; b < nblk; ++b) {
+        const int64_t j0 = b * NB;
+        const int nbk = (int)std::min<int64_t>(NB, n - j0);
+        const int64_t j1 = j0 + nbk;
+        const float* dinv_b = dinv + b * NB * NB;
+        if (j1 < n) {
+            // R[b, right] = -R_bb^-1 * R[b, right].  In place: a workgroup reads its own 128 columns of
+            // all (<= 128) rows through LDS before its epilogue writes them, and there is one row tile.
+            GemmF32 g{};
+            g.A = dinv_b; g.lda = NB; g.B = H + j0 * ld + j1; g.ldb = ld; g.C = H + j0 * ld + j1; g.ldc = ld;
+            g.M = nbk; g.N = n - j1; g.K = nbk; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = true;
+            int rc = launch_gemm_f32(g, s);
+            if (rc) return rc;
+            if (j0 > 0) {
+                GemmF32 u{};
+                u.A = H + j0; u.lda = ld; u.B = H + j0 * ld + j1; u.ldb = ld; u.C = H + j1; u.ldc = ld;
+                u.M = j0; u.N = n - j1; u.K = nbk; u.alpha = 1.f; u.b_is_nk = false; u.overwrite = false;
+                rc = launch_gemm_f32(u, s);
+                if (rc) return rc;
+            }
+        }
+        if (j0 > 0) {
+            // R[above, b] = R[above, b] * R_bb^-1.  In place: one column tile, each workgroup reads all
+            // of its own rows before writing them.
+            GemmF32 g{};
+            g.A = H + j0; g.lda = ld; g.B = dinv_b; g.ldb = NB; g.C = H + j0; g.ldc = ld;
+            g.M = j0; g.N = nbk; g.K = nbk; g.alpha = 1.f; g.b_is_nk = false; g.overwrite = true;
+            int rc = launch_gemm_f32(g, s);
+            if (rc) return rc;
+        }
+        hipLaunchKernelGGL(copy_block_kernel, dim3(64), dim3(256), 0, s, H + j0 * ld + j0, ld, dinv_b, (int64_t)NB, (int64_t)nbk, nbk, 1);
+        GPTQ_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}
+
+extern "C" int gptq_check_info(const int* info_dev, int* host_info, void* stream) {
+    if (!info_dev) return fail(GPTQ_ERR_INVALID_ARG, "check_info: info_dev is null");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int v = 0;
+    GPTQ_HIP_CHECK(hipMemcpyAsync(&v, info_dev, sizeof(int), hipMemcpyDeviceToHost, s));
+    GPTQ_HIP_CHECK(hipStreamSynchronize(s));
+    if (host_info) *host_info = v;
+    if (v != 0) return fail(GPTQ_ERR_NOT_POSDEF, "pivot of column %d (1-based) was not positive", v);
+    return GPTQ_OK;
+}

@@ -1,0 +1,58 @@
+// Shared host-side helpers of the GPTQ gfx950 library: status codes, error text, launch checks.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "../../include/gptq.h"
+
+namespace gptq {
+
+void set_error(const char* fmt, ...);
+
+inline int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+int fail_v(int code, const char* fmt, va_list ap);
+inline int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    int rc = fail_v(code, fmt, ap);
+    va_end(ap);
+    return rc;
+}
+
+#define GPTQ_HIP_CHECK(expr)                                                                      \
+    do {                                                                                          \
+        hipError_t _e = (expr);                                                                   \
+        if (_e != hipSuccess)                                                                     \
+            return ::gptq::fail(GPTQ_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e));     \
+    } while (0)
+
+#define GPTQ_LAUNCH_CHECK() GPTQ_HIP_CHECK(hipGetLastError())
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// ---- float32 matrix-core GEMM used by several steps (gemm_f32.hip) --------------------------
+// C[M x N] += alpha * A[M x K] * op(B), A row-major (K contiguous).
+//   b_is_nk = true : B is [N x K] row-major (K contiguous)  -> C += alpha * A * B^T
+//   b_is_nk = false: B is [K x N] row-major (N contiguous)  -> C += alpha * A * B
+//   overwrite: C = alpha * A * op(B) instead of accumulating.
+//   upper_only: skip 128x128 output tiles that lie entirely below the diagonal (row0 > col0 + 127),
+//               with (crow0, ccol0) the global offset of C's first element inside its parent matrix.
+// All pointers 16-byte aligned, leading dimensions multiples of 4.
+struct GemmF32 {
+    const float* A; int64_t lda;
+    const float* B; int64_t ldb;
+    float* C; int64_t ldc;
+    int64_t M, N, K;
+    float alpha;
+    bool b_is_nk;
+    bool overwrite;
+    bool upper_only;
+    int64_t crow0, ccol0;
+};
+int launch_gemm_f32(const GemmF32& g, hipStream_t s);
+
+}  // namespace gptq

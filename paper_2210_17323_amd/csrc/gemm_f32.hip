@@ -1,0 +1,174 @@
+// float32 matrix-core GEMM for gfx950, C (+)= alpha * A * op(B).
+//
+// Used by: the float32 Hessian path, the blocked Cholesky / triangular inverse, and the trailing
+// update of Alg. 1 (W[:, i+B:] -= E * Hinv[i:i+B, i+B:]).
+//
+// Tiling: one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 128 x 128 tile of C and walks K
+// in steps of 16.  Each wavefront owns 64 x 64 = 2 x 2 tiles of v_mfma_f32_32x32x2_f32 (16
+// accumulator registers each).  A and B tiles are staged through LDS k-major ([k][m] and [k][n],
+// row pitch 132 floats) so that the 32 lanes of a half-wavefront read 32 consecutive floats
+// (conflict free); the next K step is prefetched into registers while the current one is multiplied.
+#include "common.h"
+
+namespace gptq {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 128, TN = 128, TK = 16, PITCH = 132;
+
+struct GemmArgs {
+    const float* A; int64_t lda;
+    const float* B; int64_t ldb;
+    float* C; int64_t ldc;
+    int64_t M, N, K;
+    float alpha;
+    int overwrite, upper_only;
+    int64_t crow0, ccol0;
+    int tiles_n;
+};
+
+__device__ __forceinline__ float4 load4_guard(const float* p, int64_t valid) {
+    // valid = number of in-range elements starting at p (<= 0: none)
+    if (valid >= 4) return *reinterpret_cast<const float4*>(p);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (valid > 0) v.x = p[0];
+    if (valid > 1) v.y = p[1];
+    if (valid > 2) v.z = p[2];
+    return v;
+}
+
+template <bool B_IS_NK>
+__global__ __launch_bounds__(256, 2) void gemm_f32_kernel(GemmArgs g) {
+    __shared__ float As[2][TK][PITCH];
+    __shared__ float Bs[2][TK][PITCH];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t tile = blockIdx.x;
+    const int64_t m0 = (tile / g.tiles_n) * TM, n0 = (tile % g.tiles_n) * TN;
+    if (g.upper_only && g.crow0 + m0 > g.ccol0 + n0 + (TN - 1)) return;
+
+    // ---- global -> register staging: 2 float4 of A and 2 float4 of B per thread per K step
+    float4 ra[2], rb[2];
+    auto load_tiles = [&](int64_t k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int q = tid + 256 * i;
+            {
+                const int row = q >> 2, kc = (q & 3) * 4;
+                const int64_t gr = m0 + row;
+                ra[i] = (gr < g.M) ? load4_guard(g.A + gr * g.lda + k0 + kc, g.K - (k0 + kc))
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            if (B_IS_NK) {
+                const int row = q >> 2, kc = (q & 3) * 4;
+                const int64_t gn = n0 + row;
+                rb[i] = (gn < g.N) ? load4_guard(g.B + gn * g.ldb + k0 + kc, g.K - (k0 + kc))
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+                const int krow = q >> 5, nc = (q & 31) * 4;
+                const int64_t gk = k0 + krow;
+                rb[i] = (gk < g.K) ? load4_guard(g.B + gk * g.ldb + n0 + nc, g.N - (n0 + nc))
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int q = tid + 256 * i;
+            {
+                const int row = q >> 2, kc = (q & 3) * 4;
+                As[buf][kc + 0][row] = ra[i].x;
+                As[buf][kc + 1][row] = ra[i].y;
+                As[buf][kc + 2][row] = ra[i].z;
+                As[buf][kc + 3][row] = ra[i].w;
+            }
+            if (B_IS_NK) {
+                const int row = q >> 2, kc = (q & 3) * 4;
+                Bs[buf][kc + 0][row] = rb[i].x;
+                Bs[buf][kc + 1][row] = rb[i].y;
+                Bs[buf][kc + 2][row] = rb[i].z;
+                Bs[buf][kc + 3][row] = rb[i].w;
+            } else {
+                const int krow = q >> 5, nc = (q & 31) * 4;
+                *reinterpret_cast<float4*>(&Bs[buf][krow][nc]) = rb[i];
+            }
+        }
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[s][t][i] = 0.f;
+
+    const int64_t ksteps = (g.K + TK - 1) / TK;
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+
+    const int l32 = lane & 31, lhi = lane >> 5;
+    for (int64_t ks = 0; ks < ksteps; ++ks) {
+        const int buf = ks & 1;
+        if (ks + 1 < ksteps) load_tiles((ks + 1) * TK);
+#pragma unroll
+        for (int kk = 0; kk < TK / 2; ++kk) {
+            float a[2], b[2];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) a[s] = As[buf][2 * kk + lhi][wm * 64 + s * 32 + l32];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) b[t] = Bs[buf][2 * kk + lhi][wn * 64 + t * 32 + l32];
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    acc[s][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[t], acc[s][t], 0, 0, 0);
+        }
+        if (ks + 1 < ksteps) {
+            store_tiles(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: accumulator element i of a 32x32 tile is row 8*(i/4) + 4*(lane/32) + i%4, column lane%32
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int64_t col = n0 + wn * 64 + t * 32 + l32;
+            if (col >= g.N) continue;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int64_t row = m0 + wm * 64 + s * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
+                if (row < g.M) {
+                    float* c = g.C + row * g.ldc + col;
+                    const float v = g.alpha * acc[s][t][i];
+                    *c = g.overwrite ? v : (*c + v);
+                }
+            }
+        }
+}
+
+int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
+    if (p.M <= 0 || p.N <= 0) return GPTQ_OK;
+    if (!aligned(p.A, 16) || !aligned(p.B, 16) || (p.lda % 4) || (p.ldb % 4))
+        return fail(GPTQ_ERR_INVALID_ARG, "gemm_f32: operands must be 16-byte aligned with leading dimensions that are multiples of 4");
+    GemmArgs g;
+    g.A = p.A; g.lda = p.lda; g.B = p.B; g.ldb = p.ldb; g.C = p.C; g.ldc = p.ldc;
+    g.M = p.M; g.N = p.N; g.K = p.K < 0 ? 0 : p.K; g.alpha = p.alpha;
+    g.overwrite = p.overwrite; g.upper_only = p.upper_only; g.crow0 = p.crow0; g.ccol0 = p.ccol0;
+    const int64_t tm = ceil_div(p.M, TM), tn = ceil_div(p.N, TN);
+    if (tm * tn > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "gemm_f32: too many tiles");
+    g.tiles_n = (int)tn;
+    dim3 grid((unsigned)(tm * tn));
+    if (p.b_is_nk) hipLaunchKernelGGL(gemm_f32_kernel<true>, grid, dim3(256), 0, s, g);
+    else           hipLaunchKernelGGL(gemm_f32_kernel<false>, grid, dim3(256), 0, s, g);
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}
+
+}  // namespace gptq

@@ -1,0 +1,251 @@
+// Step 1: H += 2 X X^T  (Section 2, the Hessian of the layer-wise objective; Alg. 1 caption).
+//
+// X is [n x t] with tokens contiguous, so both operands of X X^T are K-contiguous.  Only tiles of
+// the upper triangle of H are computed.  fp16 / bf16 inputs go to v_mfma_f32_32x32x16_{f16,bf16}
+// (products exact in float32, float32 accumulation); float32 inputs use the float32 GEMM.
+//
+// Kernel layout (fp16/bf16): a workgroup owns a BT x BT tile of H and walks the token axis in steps
+// of 64.  Per step it stages BT x 64 halves of the row panel and of the column panel in LDS (row
+// pitch 128 bytes; the 16-byte chunk index is XOR-swizzled with the row so that both the
+// row-wise stores and the 32-rows-at-one-chunk MFMA operand reads are bank-conflict free), with
+// the next step prefetched into registers.  Tiles are enumerated in strips of 8 tile columns
+// walked top to bottom and each XCD gets a contiguous range of that order, so the 32 workgroups
+// resident on one XCD form a ~4 x 8 patch of tiles that shares its row and column panels in L2.
+#include "common.h"
+
+namespace gptq {
+
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int HK = 64;          // token step (halves)
+constexpr int STRIP = 8;        // tile columns per strip
+constexpr int NXCD = 8;
+
+struct SyrkArgs {
+    float* H; int64_t ldh;
+    const uint16_t* X; int64_t ldx;
+    int64_t n, t;
+    int nt;                     // tiles per side
+    int64_t total;              // enumerated tile slots (including skipped ones in diagonal patches)
+    int64_t per_xcd;
+};
+
+template <bool IS_BF16>
+__device__ __forceinline__ floatx16 mfma16(uint4 a, uint4 b, floatx16 c) {
+    if constexpr (IS_BF16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a), __builtin_bit_cast(halfx8, b), c, 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ uint4 load8h_guard(const uint16_t* p, int64_t valid) {
+    if (valid >= 8) return *reinterpret_cast<const uint4*>(p);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (valid <= 0) return v;
+    uint16_t h[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = (i < valid) ? p[i] : (uint16_t)0;
+    v.x = h[0] | ((uint32_t)h[1] << 16);
+    v.y = h[2] | ((uint32_t)h[3] << 16);
+    v.z = h[4] | ((uint32_t)h[5] << 16);
+    v.w = h[6] | ((uint32_t)h[7] << 16);
+    return v;
+}
+
+// BT: tile side; WM x WN wavefronts; each wavefront owns (BT/WM) x (BT/WN) outputs.
+template <bool IS_BF16, int BT, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int SM = BT / WM / 32, SN = BT / WN / 32;      // 32x32 MFMA tiles per wavefront
+    constexpr int CH = BT * 8 / NT;                          // 16-byte chunks per thread per panel
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // stage layout: [2][A panel BT*128 bytes | B panel BT*128 bytes]
+    constexpr int PANEL = BT * 128;
+
+    // ---- which tile: XCD-contiguous strip order
+    const int64_t w = blockIdx.x;
+    int64_t L = (w % NXCD) * g.per_xcd + (w / NXCD);
+    if (L >= g.total) return;
+    int bi, bj;
+    {
+        int s = 0;
+        for (;; ++s) {
+            const int cols = min(STRIP, g.nt - s * STRIP);
+            const int rows = min((s + 1) * STRIP, g.nt);
+            const int64_t cnt = (int64_t)cols * rows;
+            if (L < cnt) { bi = (int)(L / cols); bj = s * STRIP + (int)(L % cols); break; }
+            L -= cnt;
+        }
+    }
+    if (bi > bj) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int64_t r0 = (int64_t)bi * BT, c0 = (int64_t)bj * BT;
+
+    uint4 ra[CH], rb[CH];
+    auto load_panels = [&](int64_t k0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int q = tid + NT * i;
+            const int row = q >> 3, ch = q & 7;
+            const int64_t k = k0 + ch * 8;
+            const int64_t ga = r0 + row, gb = c0 + row;
+            ra[i] = (ga < g.n) ? load8h_guard(g.X + ga * g.ldx + k, g.t - k) : make_uint4(0, 0, 0, 0);
+            rb[i] = (gb < g.n) ? load8h_guard(g.X + gb * g.ldx + k, g.t - k) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_panels = [&](int buf) {
+        unsigned char* base = smem + buf * 2 * PANEL;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int q = tid + NT * i;
+            const int row = q >> 3, ch = q & 7;
+            const int off = row * 128 + ((ch ^ (row & 7)) << 4);
+            *reinterpret_cast<uint4*>(base + off) = ra[i];
+            *reinterpret_cast<uint4*>(base + PANEL + off) = rb[i];
+        }
+    };
+
+    floatx16 acc[SM][SN];
+#pragma unroll
+    for (int s = 0; s < SM; ++s)
+#pragma unroll
+        for (int u = 0; u < SN; ++u)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[s][u][i] = 0.f;
+
+    const int64_t ksteps = (g.t + HK - 1) / HK;
+    load_panels(0);
+    store_panels(0);
+    __syncthreads();
+
+    for (int64_t ks = 0; ks < ksteps; ++ks) {
+        const int buf = ks & 1;
+        if (ks + 1 < ksteps) load_panels((ks + 1) * HK);
+        const unsigned char* pa = smem + buf * 2 * PANEL;
+        const unsigned char* pb = pa + PANEL;
+#pragma unroll
+        for (int kk = 0; kk < HK / 16; ++kk) {
+            const int ch = kk * 2 + lhi;
+            uint4 fa[SM], fb[SN];
+#pragma unroll
+            for (int s = 0; s < SM; ++s) {
+                const int row = wm * (BT / WM) + s * 32 + l32;
+                fa[s] = *reinterpret_cast<const uint4*>(pa + row * 128 + ((ch ^ (row & 7)) << 4));
+            }
+#pragma unroll
+            for (int u = 0; u < SN; ++u) {
+                const int row = wn * (BT / WN) + u * 32 + l32;
+                fb[u] = *reinterpret_cast<const uint4*>(pb + row * 128 + ((ch ^ (row & 7)) << 4));
+            }
+#pragma unroll
+            for (int s = 0; s < SM; ++s)
+#pragma unroll
+                for (int u = 0; u < SN; ++u) acc[s][u] = mfma16<IS_BF16>(fa[s], fb[u], acc[s][u]);
+        }
+        if (ks + 1 < ksteps) {
+            store_panels(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- H += 2 * acc
+#pragma unroll
+    for (int s = 0; s < SM; ++s)
+#pragma unroll
+        for (int u = 0; u < SN; ++u) {
+            const int64_t col = c0 + wn * (BT / WN) + u * 32 + l32;
+            if (col >= g.n) continue;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int64_t row = r0 + wm * (BT / WM) + s * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
+                if (row < g.n) {
+                    float* h = g.H + row * g.ldh + col;
+                    *h += 2.0f * acc[s][u][i];
+                }
+            }
+        }
+}
+
+template <bool IS_BF16, int BT, int WM, int WN>
+static int launch_syrk(SyrkArgs g, hipStream_t s) {
+    g.nt = (int)ceil_div(g.n, BT);
+    int64_t total = 0;
+    for (int st = 0; st * STRIP < g.nt; ++st)
+        total += (int64_t)std::min(STRIP, g.nt - st * STRIP) * std::min((st + 1) * STRIP, g.nt);
+    g.total = total;
+    g.per_xcd = ceil_div(total, NXCD);
+    const int64_t blocks = g.per_xcd * NXCD;
+    if (blocks > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
+    constexpr size_t lds = 2 * 2 * BT * 128;
+    auto kern = syrk_f16_kernel<IS_BF16, BT, WM, WN>;
+    GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WM * WN), lds, s, g);
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}
+
+// ---- mirror the upper triangle onto the lower one, 32 x 32 tiles through LDS
+__global__ __launch_bounds__(256) void symmetrize_kernel(float* H, int64_t ld, int64_t n) {
+    __shared__ float tile[32][33];
+    const int64_t bi = blockIdx.y, bj = blockIdx.x;      // source tile (bi, bj) with bj >= bi
+    if (bj < bi) return;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int r = ty; r < 32; r += 8) {
+        const int64_t row = bi * 32 + r, col = bj * 32 + tx;
+        tile[r][tx] = (row < n && col < n) ? H[row * ld + col] : 0.f;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int64_t row = bj * 32 + r, col = bi * 32 + tx;   // destination (row, col) = source (col, row)
+        if (row < n && col < n && row > col) H[row * ld + col] = tile[tx][r];
+    }
+}
+
+}  // namespace gptq
+
+using namespace gptq;
+
+extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int xdtype,
+                                       int64_t n, int64_t t, int64_t ldx, void* stream) {
+    if (n < 0 || t < 0) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: negative size");
+    if (n == 0 || t == 0) return GPTQ_OK;
+    if (!H || !X) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: null pointer");
+    if (ldh < n || ldx < t) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: leading dimension smaller than the row length");
+    if (xdtype != GPTQ_F16 && xdtype != GPTQ_BF16 && xdtype != GPTQ_F32)
+        return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: unknown xdtype %d", xdtype);
+    if (!aligned(H, 4)) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: H misaligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (xdtype == GPTQ_F32) {
+        if (!aligned(X, 16) || ldx % 4) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: float32 X must be 16-byte aligned with ldx %% 4 == 0");
+        GemmF32 g{};
+        g.A = static_cast<const float*>(X); g.lda = ldx;
+        g.B = g.A; g.ldb = ldx;
+        g.C = H; g.ldc = ldh;
+        g.M = n; g.N = n; g.K = t; g.alpha = 2.0f;
+        g.b_is_nk = true; g.overwrite = false; g.upper_only = true; g.crow0 = 0; g.ccol0 = 0;
+        return launch_gemm_f32(g, s);
+    }
+    if (!aligned(X, 16) || ldx % 8) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: 16-bit X must be 16-byte aligned with ldx %% 8 == 0");
+    SyrkArgs g{};
+    g.H = H; g.ldh = ldh; g.X = static_cast<const uint16_t*>(X); g.ldx = ldx; g.n = n; g.t = t;
+    const bool big = n > 6144;      // 256-wide tiles only fill the chip when there are enough of them
+    if (xdtype == GPTQ_BF16) return big ? launch_syrk<true, 256, 2, 4>(g, s) : launch_syrk<true, 128, 2, 2>(g, s);
+    return big ? launch_syrk<false, 256, 2, 4>(g, s) : launch_syrk<false, 128, 2, 2>(g, s);
+}
+
+extern "C" int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* stream) {
+    if (n < 0) return fail(GPTQ_ERR_INVALID_ARG, "hessian_symmetrize: negative size");
+    if (n == 0) return GPTQ_OK;
+    if (!H || ldh < n) return fail(GPTQ_ERR_INVALID_ARG, "hessian_symmetrize: bad H / ldh");
+    const int64_t nb = ceil_div(n, 32);
+    if (nb > 65535) return fail(GPTQ_ERR_UNSUPPORTED, "hessian_symmetrize: n too large");
+    hipLaunchKernelGGL(symmetrize_kernel, dim3((unsigned)nb, (unsigned)nb), dim3(256), 0, static_cast<hipStream_t>(stream), H, ldh, n);
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}

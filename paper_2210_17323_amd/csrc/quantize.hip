@@ -1,0 +1,321 @@
+// Step 3: Algorithm 1 -- column-by-column quantization in lazy blocks of B = 128 with error
+// propagation (Section 3, Steps 1-3; Alg. 1), grids of Section 4 (Setup; grouping; "Extreme
+// Quantization").
+//
+// Per block of 128 columns:
+//   quant_block_kernel : one LANE per weight row.  The lane keeps its 128 working weights in
+//       registers and walks the columns in order: code = clamp(rint(w/scale) + zero), q = grid
+//       value, e = (w - q) / U[j][j], then w[k] -= e * U[j][k] for the later columns of the block.
+//       Rows are independent (the Hessian information U is shared by all rows), so there is no
+//       cross-lane traffic at all; the 128 x 128 block of U is the same for every lane and is read
+//       through uniform (scalar) loads.  The column loop is fully unrolled so every register index
+//       is static.  Outputs: codes, the block's error matrix E (r x 128), per-row sum of e^2.
+//   trailing update    : W[:, i+B:] -= E * U[i:i+B, i+B:], the float32 matrix-core GEMM.
+#include "common.h"
+
+namespace gptq {
+
+constexpr int QB = 128;
+
+// ---- W (f16 / bf16 / f32) -> float32 working copy; optionally the per-row grid from the original row.
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<_Float16>(_Float16 v) { return (float)v; }
+template <> __device__ __forceinline__ float to_f32<__bf16>(__bf16 v) { return (float)v; }
+
+__device__ __forceinline__ void grid_from_range(int grid, float maxq, float lo, float hi, float amax, float& scale, int& zero) {
+    if (grid == GPTQ_GRID_TERNARY) {
+        scale = (amax == 0.f) ? 1.f : amax;
+        zero = 1;
+    } else {
+        lo = fminf(lo, 0.f);
+        hi = fmaxf(hi, 0.f);
+        if (hi == lo) { scale = 1.f; zero = 0; }
+        else {
+            scale = (hi - lo) / maxq;
+            zero = (int)rintf(-lo / scale);
+        }
+    }
+}
+
+// One workgroup per row: convert the row and reduce min / max / max|.|.
+template <typename T>
+__global__ __launch_bounds__(256) void prepare_rows_kernel(const T* W, int64_t ldw, int64_t n, float* Wk, int64_t ldk,
+                                                           int want_grid, int grid, float maxq, float* scales, int32_t* zeros) {
+    const int64_t row = blockIdx.x;
+    float lo = INFINITY, hi = -INFINITY, am = 0.f;
+    for (int64_t k = threadIdx.x; k < n; k += 256) {
+        const float v = to_f32<T>(W[row * ldw + k]);
+        Wk[row * ldk + k] = v;
+        lo = fminf(lo, v); hi = fmaxf(hi, v); am = fmaxf(am, fabsf(v));
+    }
+    if (!want_grid) return;
+    __shared__ float slo[256], shi[256], sam[256];
+    slo[threadIdx.x] = lo; shi[threadIdx.x] = hi; sam[threadIdx.x] = am;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            slo[threadIdx.x] = fminf(slo[threadIdx.x], slo[threadIdx.x + w]);
+            shi[threadIdx.x] = fmaxf(shi[threadIdx.x], shi[threadIdx.x + w]);
+            sam[threadIdx.x] = fmaxf(sam[threadIdx.x], sam[threadIdx.x + w]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        float sc; int zr;
+        grid_from_range(grid, maxq, slo[0], shi[0], sam[0], sc, zr);
+        scales[row] = sc; zeros[row] = zr;
+    }
+}
+
+// Grid of one group that spans several blocks (group % 128 == 0): one wavefront per row over the
+// current working weights W[:, j : j+g].
+__global__ __launch_bounds__(64) void group_grid_kernel(const float* Wk, int64_t ldk, int64_t j, int64_t g, int grid, float maxq,
+                                                        float* scales, int32_t* zeros, int64_t ngroups, int64_t gidx) {
+    const int64_t row = blockIdx.x;
+    float lo = INFINITY, hi = -INFINITY, am = 0.f;
+    for (int64_t k = threadIdx.x; k < g; k += 64) {
+        const float v = Wk[row * ldk + j + k];
+        lo = fminf(lo, v); hi = fmaxf(hi, v); am = fmaxf(am, fabsf(v));
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off));
+        hi = fmaxf(hi, __shfl_xor(hi, off));
+        am = fmaxf(am, __shfl_xor(am, off));
+    }
+    if (threadIdx.x == 0) {
+        float sc; int zr;
+        grid_from_range(grid, maxq, lo, hi, am, sc, zr);
+        scales[row * ngroups + gidx] = sc; zeros[row * ngroups + gidx] = zr;
+    }
+}
+
+// Dense, padded copy of the diagonal block of U: Ub[j][k] = U[j0+j][j0+k], identity outside the matrix.
+__global__ __launch_bounds__(256) void copy_u_block_kernel(const float* U, int64_t ldu, int64_t n, int64_t j0, float* Ub) {
+    for (int q = threadIdx.x + blockIdx.x * 256; q < QB * QB; q += gridDim.x * 256) {
+        const int j = q / QB, k = q % QB;
+        float v = (j == k) ? 1.f : 0.f;
+        if (j0 + j < n && j0 + k < n) v = (k >= j) ? U[(j0 + j) * ldu + j0 + k] : 0.f;
+        Ub[q] = v;
+    }
+}
+
+struct QuantArgs {
+    float* Wk; int64_t ldk;         // working weights, points at column 0
+    const float* Ub;                // dense 128 x 128 block of U
+    int64_t r, j0; int nbk;
+    int grid; int maxq;
+    float* scales; int32_t* zeros; int64_t ngroups;   // [r x ngroups]
+    int64_t group;                  // 0 or the group size
+    uint8_t* codes; int64_t ldc;
+    float* E;                       // [r x 128]
+    double* half_e2;                // [r] or null
+    int first_block;
+};
+
+// G = 0: the grid of this block's columns is already in scales/zeros (per-row grid, or a group that
+//        is a multiple of 128).  G in {8,16,32,64,128}: groups inside the block, grid taken from the
+//        current register values at each group start.
+template <int G>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void quant_block_kernel(QuantArgs a) {
+    const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    const bool active = row < a.r;
+    const int64_t rr = active ? row : 0;
+    float w[QB];
+    {
+        const float* src = a.Wk + rr * a.ldk + a.j0;
+        if (a.nbk == QB) {
+#pragma unroll
+            for (int k = 0; k < QB; k += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(src + k);
+                w[k] = v.x; w[k + 1] = v.y; w[k + 2] = v.z; w[k + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < QB; ++k) w[k] = (k < a.nbk) ? src[k] : 0.f;
+        }
+    }
+    const float maxq = (float)a.maxq;
+    float scale = 1.f; int zero = 0;
+    if (G == 0) {
+        const int64_t gi = a.group ? (a.j0 / a.group) : 0;
+        scale = a.scales[rr * a.ngroups + gi];
+        zero = a.zeros[rr * a.ngroups + gi];
+    }
+    float zf = (float)zero;
+    uint32_t packed[QB / 4];
+    float e2 = 0.f;
+    const float* __restrict__ ub = a.Ub;
+#pragma unroll
+    for (int j = 0; j < QB; ++j) {
+        if (G > 0 && (j % (G > 0 ? G : 1)) == 0) {
+            float lo = w[j], hi = w[j], am = fabsf(w[j]);
+#pragma unroll
+            for (int k = 1; k < (G > 0 ? G : 1); ++k) {
+                lo = fminf(lo, w[j + k]); hi = fmaxf(hi, w[j + k]); am = fmaxf(am, fabsf(w[j + k]));
+            }
+            grid_from_range(a.grid, maxq, lo, hi, am, scale, zero);
+            zf = (float)zero;
+            if (active && j < a.nbk) {
+                const int64_t gi = (a.j0 + j) / (G > 0 ? G : 1);
+                a.scales[row * a.ngroups + gi] = scale;
+                a.zeros[row * a.ngroups + gi] = zero;
+            }
+        }
+        const float x = w[j] / scale;
+        float c = rintf(x) + zf;
+        c = fminf(fmaxf(c, 0.f), maxq);
+        const float q = __fmul_rn(scale, c - zf);          // the grid value, rounded on its own (never fused into w - q)
+        const float e = (w[j] - q) / ub[j * QB + j];
+        const uint32_t ci = (uint32_t)c;
+        if ((j & 3) == 0) packed[j >> 2] = ci; else packed[j >> 2] |= ci << (8 * (j & 3));
+        e2 = fmaf(e, e, e2);
+        w[j] = e;
+#pragma unroll
+        for (int k = j + 1; k < QB; ++k) w[k] = fmaf(-e, ub[j * QB + k], w[k]);
+    }
+    if (!active) return;
+    // ---- outputs: E row (the registers now hold e_j), codes, per-row error
+    float* edst = a.E + row * QB;
+#pragma unroll
+    for (int k = 0; k < QB; k += 4) *reinterpret_cast<float4*>(edst + k) = make_float4(w[k], w[k + 1], w[k + 2], w[k + 3]);
+    uint8_t* cdst = a.codes + row * a.ldc + a.j0;
+    if (a.nbk == QB && (reinterpret_cast<uintptr_t>(cdst) & 15) == 0) {
+#pragma unroll
+        for (int k = 0; k < QB / 4; k += 4)
+            *reinterpret_cast<uint4*>(cdst + 4 * k) = make_uint4(packed[k], packed[k + 1], packed[k + 2], packed[k + 3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < QB; ++k)
+            if (k < a.nbk) cdst[k] = (uint8_t)((packed[k >> 2] >> (8 * (k & 3))) & 0xff);
+    }
+    if (a.half_e2) {
+        const double prev = a.first_block ? 0.0 : a.half_e2[row];
+        a.half_e2[row] = prev + 0.5 * (double)e2;
+    }
+}
+
+// Wq = scale * (code - zero)
+__global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* codes, int64_t ldc, const float* scales, const int32_t* zeros,
+                                                      int64_t ngroups, int64_t gsize, int64_t n, float* Wq, int64_t ldq) {
+    const int64_t row = blockIdx.x;
+    for (int64_t k = threadIdx.x; k < n; k += 256) {
+        const int64_t gi = k / gsize;
+        const float sc = scales[row * ngroups + gi];
+        const float zf = (float)zeros[row * ngroups + gi];
+        Wq[row * ldq + k] = sc * ((float)codes[row * ldc + k] - zf);
+    }
+}
+
+static bool group_supported(int64_t group) {
+    if (group == 0) return true;
+    if (group < 0) return false;
+    if (group % QB == 0) return true;
+    return group == 8 || group == 16 || group == 32 || group == 64;
+}
+
+struct QuantWs { size_t wk, e, ub, total; int64_t ldk; };
+static QuantWs quant_ws_layout(int64_t r, int64_t n) {
+    QuantWs l;
+    l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
+    l.wk = 0;
+    size_t off = round_up((size_t)std::max<int64_t>(r, 1) * l.ldk * sizeof(float), 256);
+    l.e = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QB * sizeof(float), 256);
+    l.ub = off; off += QB * QB * sizeof(float);
+    l.total = off + 256;
+    return l;
+}
+
+}  // namespace gptq
+
+using namespace gptq;
+
+extern "C" size_t gptq_quantize_layer_workspace_bytes(int64_t r, int64_t n, int block, int64_t group) {
+    (void)block; (void)group;
+    if (r < 0 || n < 0) return 0;
+    return quant_ws_layout(r, n).total;
+}
+
+extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
+                                   const float* U, int64_t ldu,
+                                   int bits, int grid, int block, int64_t group,
+                                   uint8_t* codes, int64_t ldc, float* scales, int32_t* zeros,
+                                   float* Wq, int64_t ldq, double* half_E2_rows,
+                                   void* ws, size_t ws_bytes, void* stream) {
+    if (r < 0 || n < 0) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: negative size");
+    if (grid != GPTQ_GRID_MINMAX && grid != GPTQ_GRID_TERNARY) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: unknown grid %d", grid);
+    if (grid == GPTQ_GRID_MINMAX && (bits < 2 || bits > 4)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: bits must be 2, 3 or 4 (got %d)", bits);
+    if (wdtype != GPTQ_F16 && wdtype != GPTQ_BF16 && wdtype != GPTQ_F32) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: unknown wdtype %d", wdtype);
+    if (block <= 0) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: block must be positive");
+    if (block != QB) return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer: only block = 128 is built (got %d)", block);
+    if (group < 0) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: negative group");
+    if (group > 0 && n % group) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: n must be a multiple of the group size");
+    if (group > 0 && (QB % group) && (group % QB)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: a group must not straddle a block end (need 128 %% g == 0 or g %% 128 == 0)");
+    if (!group_supported(group)) return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer: group size %lld not built (8, 16, 32, 64 or a multiple of 128)", (long long)group);
+    if (r == 0 || n == 0) return GPTQ_OK;
+    if (!W || !U || !codes || !scales || !zeros) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: null pointer");
+    if (ldw < n || ldu < n || ldc < n || (Wq && ldq < n)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: leading dimension smaller than n");
+    if (!aligned(U, 16) || ldu % 4) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: U must be 16-byte aligned with ldu %% 4 == 0");
+    const QuantWs lay = quant_ws_layout(r, n);
+    if (!ws || !aligned(ws, 256) || ws_bytes < lay.total) return fail(GPTQ_ERR_WORKSPACE, "quantize_layer: workspace missing, misaligned or too small");
+    if (r > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer: too many rows");
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    float* Wk = reinterpret_cast<float*>(base + lay.wk);
+    float* E = reinterpret_cast<float*>(base + lay.e);
+    float* Ub = reinterpret_cast<float*>(base + lay.ub);
+    const int maxq = (grid == GPTQ_GRID_TERNARY) ? 2 : ((1 << bits) - 1);
+    const int64_t ngroups = group ? n / group : 1;
+    const int want_grid = group == 0;
+
+    switch (wdtype) {
+        case GPTQ_F16:
+            hipLaunchKernelGGL(prepare_rows_kernel<_Float16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const _Float16*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
+            break;
+        case GPTQ_BF16:
+            hipLaunchKernelGGL(prepare_rows_kernel<__bf16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const __bf16*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
+            break;
+        default:
+            hipLaunchKernelGGL(prepare_rows_kernel<float>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const float*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
+    }
+    GPTQ_LAUNCH_CHECK();
+
+    const unsigned qblocks = (unsigned)ceil_div(r, 64);
+    for (int64_t j0 = 0; j0 < n; j0 += QB) {
+        const int nbk = (int)std::min<int64_t>(QB, n - j0);
+        const int64_t j1 = j0 + nbk;
+        hipLaunchKernelGGL(copy_u_block_kernel, dim3(16), dim3(256), 0, s, U, ldu, n, j0, Ub);
+        GPTQ_LAUNCH_CHECK();
+        if (group >= QB && j0 % group == 0) {
+            hipLaunchKernelGGL(group_grid_kernel, dim3((unsigned)r), dim3(64), 0, s, (const float*)Wk, lay.ldk, j0, group, grid, (float)maxq, scales, zeros, ngroups, j0 / group);
+            GPTQ_LAUNCH_CHECK();
+        }
+        QuantArgs a{};
+        a.Wk = Wk; a.ldk = lay.ldk; a.Ub = Ub; a.r = r; a.j0 = j0; a.nbk = nbk; a.grid = grid; a.maxq = maxq;
+        a.scales = scales; a.zeros = zeros; a.ngroups = ngroups; a.group = group;
+        a.codes = codes; a.ldc = ldc; a.E = E; a.half_e2 = half_E2_rows; a.first_block = (j0 == 0);
+        const int G = (group > 0 && group < QB) ? (int)group : 0;
+        switch (G) {
+            case 0:  hipLaunchKernelGGL(quant_block_kernel<0>,  dim3(qblocks), dim3(64), 0, s, a); break;
+            case 8:  hipLaunchKernelGGL(quant_block_kernel<8>,  dim3(qblocks), dim3(64), 0, s, a); break;
+            case 16: hipLaunchKernelGGL(quant_block_kernel<16>, dim3(qblocks), dim3(64), 0, s, a); break;
+            case 32: hipLaunchKernelGGL(quant_block_kernel<32>, dim3(qblocks), dim3(64), 0, s, a); break;
+            default: hipLaunchKernelGGL(quant_block_kernel<64>, dim3(qblocks), dim3(64), 0, s, a); break;
+        }
+        GPTQ_LAUNCH_CHECK();
+        if (j1 < n) {
+            GemmF32 g{};
+            g.A = E; g.lda = QB; g.B = U + j0 * ldu + j1; g.ldb = ldu; g.C = Wk + j1; g.ldc = lay.ldk;
+            g.M = r; g.N = n - j1; g.K = nbk; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
+            const int rc = launch_gemm_f32(g, s);
+            if (rc) return rc;
+        }
+    }
+    if (Wq) {
+        hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)r), dim3(256), 0, s, (const uint8_t*)codes, ldc, (const float*)scales, (const int32_t*)zeros,
+                           ngroups, group ? group : n, n, Wq, ldq);
+        GPTQ_LAUNCH_CHECK();
+    }
+    return GPTQ_OK;
+}

@@ -1,0 +1,66 @@
+"""Convenience driver: allocates the device buffers with PyTorch and walks one layer through the
+four C-ABI calls.  Every arithmetic step happens inside the library's HIP kernels."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class LayerResult:
+    codes: torch.Tensor          # [r, n] uint8
+    scales: torch.Tensor         # [r, G] float32
+    zeros: torch.Tensor          # [r, G] int32
+    half_E2_rows: torch.Tensor   # [r] float64
+    Wq: torch.Tensor | None      # [r, n] float32 (optional)
+    packed: torch.Tensor | None  # [r, ceil(n*bits/32)] int32 (optional)
+
+
+def new_hessian(n: int, device="cuda") -> torch.Tensor:
+    return torch.zeros((n, n), dtype=torch.float32, device=device)
+
+
+def accumulate(H: torch.Tensor, X: torch.Tensor, chunk: int | None = None) -> None:
+    """H += 2 X X^T, optionally walking the token axis in chunks (multiples of 8 tokens)."""
+    t = X.shape[1]
+    if chunk is None or chunk >= t:
+        B.gptq_hessian_accumulate(H, X)
+        return
+    for c0 in range(0, t, chunk):
+        B.gptq_hessian_accumulate(H, X[:, c0:min(c0 + chunk, t)])
+
+
+def cholesky_inverse(H: torch.Tensor, percdamp: float = 0.01, check: bool = True) -> torch.Tensor:
+    """In place H -> U; returns H (now U).  Raises GptqError if a pivot is not positive."""
+    n = H.shape[0]
+    ws = torch.empty(B.gptq_damp_cholesky_inverse_workspace_bytes(n), dtype=torch.uint8, device=H.device)
+    info = torch.zeros(1, dtype=torch.int32, device=H.device)
+    B.gptq_damp_cholesky_inverse(H, percdamp, ws, info)
+    if check:
+        B.gptq_check_info(info)
+    return H
+
+
+def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", block: int = 128, group: int = 0,
+             want_Wq: bool = False, pack: bool = False, ws: torch.Tensor | None = None) -> LayerResult:
+    r, n = W.shape
+    dev = W.device
+    G = n // group if group else 1
+    codes = torch.empty((r, n), dtype=torch.uint8, device=dev)
+    scales = torch.empty((r, G), dtype=torch.float32, device=dev)
+    zeros = torch.empty((r, G), dtype=torch.int32, device=dev)
+    half = torch.zeros(r, dtype=torch.float64, device=dev)
+    Wq = torch.empty((r, n), dtype=torch.float32, device=dev) if want_Wq else None
+    if ws is None:
+        ws = torch.empty(B.gptq_quantize_layer_workspace_bytes(r, n, block, group), dtype=torch.uint8, device=dev)
+    gid = B.GPTQ_GRID_TERNARY if grid == "ternary" else B.GPTQ_GRID_MINMAX
+    B.gptq_quantize_layer(W, U, bits, gid, block, group, codes, scales, zeros, ws, Wq, half)
+    packed = None
+    if pack:
+        pbits = 2 if grid == "ternary" else bits
+        packed = torch.empty((r, B.packed_words_per_row(n, pbits)), dtype=torch.int32, device=dev)
+        B.gptq_pack(codes, pbits, packed)
+    return LayerResult(codes, scales, zeros, half, Wq, packed)

@@ -1,0 +1,68 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments with the documented codes before touching the device."""
+import ctypes
+
+import pytest
+
+import paper_2210_17323_amd as g
+
+OK, INVALID, NOT_POSDEF, HIP, UNSUPPORTED, WORKSPACE = range(6)
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = g.lib()
+    names = g.exported_symbols()
+    assert {"gptq_hessian_accumulate", "gptq_damp_cholesky_inverse", "gptq_quantize_layer", "gptq_pack"} <= set(names)
+    for name in names:
+        assert getattr(L, name) is not None
+    assert g.version() >= 100
+
+
+def test_workspace_sizes():
+    assert g.gptq_damp_cholesky_inverse_workspace_bytes(256) >= 2 * 128 * 128 * 4 + 256 * 128 * 4
+    big = g.gptq_quantize_layer_workspace_bytes(12288, 49152)
+    assert 12288 * 49152 * 4 < big < 12288 * 49152 * 4 * 1.01 + (1 << 24)
+    assert g.gptq_quantize_layer_workspace_bytes(0, 0) > 0
+
+
+def _err():
+    return g.lib().gptq_last_error().decode()
+
+
+def test_argument_validation_happens_on_the_host():
+    L = g.lib()
+    one = ctypes.c_void_p(256)       # never dereferenced: every call below must fail validation first
+    assert L.gptq_hessian_accumulate(one, 8, one, 0, -1, 8, 8, None) == INVALID
+    assert L.gptq_hessian_accumulate(None, 8, one, 0, 8, 8, 8, None) == INVALID
+    assert L.gptq_hessian_accumulate(one, 4, one, 0, 8, 8, 8, None) == INVALID          # ldh < n
+    assert L.gptq_hessian_accumulate(one, 8, one, 7, 8, 8, 8, None) == INVALID          # dtype
+    assert L.gptq_hessian_accumulate(one, 8, one, 0, 8, 12, 12, None) == INVALID        # ldx % 8
+    assert "ldx" in _err()
+    assert L.gptq_hessian_accumulate(one, 8, one, 0, 0, 8, 8, None) == OK               # empty is a no-op
+    assert L.gptq_damp_cholesky_inverse(one, 8, 8, -0.5, one, 1 << 30, one, None) == INVALID
+    assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, one, 16, one, None) == WORKSPACE
+    assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, None, 0, one, None) == WORKSPACE
+    assert L.gptq_damp_cholesky_inverse(one, 6, 6, 0.01, one, 1 << 30, one, None) == INVALID   # ld % 4
+    q = lambda **kw: L.gptq_quantize_layer(one, kw.get("wd", 0), 256, kw.get("r", 4), 256, one, 256, kw.get("bits", 4),
+                                           kw.get("grid", 0), kw.get("block", 128), kw.get("group", 0), one, 256, one, one,
+                                           None, 0, None, kw.get("ws", one), kw.get("wsb", 1 << 30), None)
+    assert q(bits=5) == INVALID and q(bits=1) == INVALID
+    assert q(grid=3) == INVALID
+    assert q(block=64) == UNSUPPORTED and q(block=0) == INVALID
+    assert q(group=100) == INVALID          # 256 % 100 != 0
+    assert q(group=4) == UNSUPPORTED
+    assert q(wd=9) == INVALID
+    assert q(wsb=1024) == WORKSPACE
+    assert q(r=0) == OK
+    assert q(grid=1, bits=0, wsb=8) == WORKSPACE   # ternary ignores bits; fails later on the workspace
+    assert L.gptq_pack(one, 64, 2, 64, 5, one, 8, None) == INVALID
+    assert L.gptq_pack(one, 64, 2, 64, 3, one, 5, None) == INVALID      # 64*3/32 = 6 words needed
+    assert L.gptq_pack(one, 32, 2, 64, 3, one, 6, None) == INVALID      # ldc < n
+    assert L.gptq_unpack(one, 6, 2, 64, 3, None, 64, None) == INVALID
+    assert L.gptq_pack(one, 64, 0, 64, 3, one, 6, None) == OK
+    assert L.gptq_check_info(None, None, None) == INVALID
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        g.load_library(str(tmp_path / "nope.so"))
