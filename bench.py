@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the GPTQ layer solve on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic layer: zero H, accumulate
+H += 2 X X^T over all calibration tokens (in chunks), damp + Cholesky of the inverse, Algorithm 1
+(block quantizer + trailing updates), bit packing.  Inputs are resident in HBM before timing starts.
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_F16_MFMA_TFLOPS = 2516.6      # MI355X dense fp16/bf16 matrix-core peak
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--layer", default="opt175b_fc2", help="opt175b_fc2 (headline) | opt175b_fc1 | opt6.7b_attn | tiny")
+    ap.add_argument("--tokens", type=int, default=0, help="calibration tokens (default: the layer's own, 262144)")
+    ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptq_hessian_accumulate call")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def pick_layer(name: str, tokens: int):
+    from workloads import configs
+    m = tokens or configs.TOKENS
+    table = {
+        "opt175b_fc2": lambda: configs.config3(m)[1],
+        "opt175b_fc1": lambda: configs.config3(m)[0],
+        "opt6.7b_attn": lambda: configs.config2(m)[0],
+        "tiny": lambda: configs.config1()[0],
+    }
+    return table[name]()
+
+
+def flop_model(r: int, n: int, m: int, B: int = 128):
+    """Algorithmic flops of each step (the conventions are stated in the design doc)."""
+    trailing = sum(2 * r * min(B, n - i) * (n - i - min(B, n - i)) for i in range(0, n, B))
+    inblock = sum(r * min(B, n - i) * (min(B, n - i) - 1) for i in range(0, n, B))
+    return {
+        "hessian": float(n) * (n + 1) * m,            # SYRK: n(n+1)/2 outputs, 2 flops per token
+        "cholesky": float(n) ** 3 / 3.0,              # factorisation
+        "tri_inverse": float(n) ** 3 / 3.0,           # triangular inverse
+        "quantize": float(trailing + inblock),
+    }
+
+
+def generate_inputs(lay, device):
+    import torch
+    scales = lay.x.scales()
+    X = torch.empty((lay.n, lay.x.m), dtype=lay.x.dtype, device=device)
+    rows = max(1, min(lay.n, (1 << 27) // max(lay.x.m, 1)))
+    for r0 in range(0, lay.n, rows):
+        nr = min(rows, lay.n - r0)
+        X[r0:r0 + nr] = lay.x.tile(row0=r0, nrows=nr, device=device, scales=scales)
+    W = torch.empty((lay.r, lay.n), dtype=lay.dtype, device=device)
+    rows = max(1, min(lay.r, (1 << 27) // lay.n))
+    for r0 in range(0, lay.r, rows):
+        nr = min(rows, lay.r - r0)
+        W[r0:r0 + nr] = lay.weights(row0=r0, nrows=nr, device=device)
+    return W, X
+
+
+def cpu_baseline(lay, flops):
+    """The float64 NumPy oracle, as it stands, timed on the host cores on a bounded sample of the
+    same workload; each step is timed on a reduced problem and scaled by its flop count."""
+    import numpy as np
+    from oracle import gptq_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    n_h, t_h = min(lay.n, 4096), min(lay.x.m, 32768)
+    X = lay.x.tile(nrows=n_h, ncols=t_h).double().numpy()
+    t0 = time.perf_counter(); H = O.hessian(X); th = time.perf_counter() - t0
+    full_h = th * flops["hessian"] / (float(n_h) * (n_h + 1) * t_h)
+    t0 = time.perf_counter(); U = O.hinv_cholesky_upper(O.damp(H, lay.percdamp)); tc = time.perf_counter() - t0
+    full_c = tc * (lay.n / n_h) ** 3
+    r_q = min(lay.r, 64)
+    W = lay.weights(nrows=r_q).double().numpy()[:, :n_h]
+    t0 = time.perf_counter(); out = O.gptq_quantize(W, U, lay.bits, lay.grid, lay.block, 0 if not lay.group else lay.group); tq = time.perf_counter() - t0
+    full_q = tq * (lay.r / r_q) * (lay.n / n_h) ** 2
+    t0 = time.perf_counter(); O.pack_codes(out["codes"], 2 if lay.grid == "ternary" else lay.bits); tp = time.perf_counter() - t0
+    full_p = tp * (lay.r / r_q) * (lay.n / n_h)
+    total = full_h + full_c + full_q + full_p
+    return {
+        "value": sum(flops.values()) / total / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"float64 NumPy oracle timed on: Hessian {n_h}x{t_h} tokens ({th:.2f}s), damp+inverse+Cholesky n={n_h} ({tc:.2f}s), "
+                   f"Alg.1 {r_q} rows x {n_h} cols ({tq:.2f}s), pack ({tp:.3f}s); each scaled by flop count to the full layer: "
+                   f"EXTRAPOLATED layer solve {total:.0f} s"),
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the solver is a single-GPU path; --gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2210_17323_amd as g
+    from paper_2210_17323_amd import solver as S
+    g.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    lay = pick_layer(a.layer, a.tokens)
+    r, n, m = lay.r, lay.n, lay.x.m
+    flops = flop_model(r, n, m, lay.block)
+    W, X = generate_inputs(lay, dev)
+    H = torch.empty((n, n), dtype=torch.float32, device=dev)
+    chol_ws = torch.empty(g.gptq_damp_cholesky_inverse_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    info = torch.zeros(1, dtype=torch.int32, device=dev)
+    q_ws = torch.empty(g.gptq_quantize_layer_workspace_bytes(r, n, lay.block, lay.group), dtype=torch.uint8, device=dev)
+    G = n // lay.group if lay.group else 1
+    codes = torch.empty((r, n), dtype=torch.uint8, device=dev)
+    scales = torch.empty((r, G), dtype=torch.float32, device=dev)
+    zeros = torch.empty((r, G), dtype=torch.int32, device=dev)
+    half = torch.empty(r, dtype=torch.float64, device=dev)
+    pbits = 2 if lay.grid == "ternary" else lay.bits
+    packed = torch.empty((r, g.packed_words_per_row(n, pbits)), dtype=torch.int32, device=dev)
+    grid = g.GPTQ_GRID_TERNARY if lay.grid == "ternary" else g.GPTQ_GRID_MINMAX
+    chunk = min(a.chunk, m)
+    chunks = [(c0, min(c0 + chunk, m)) for c0 in range(0, m, chunk)]
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    syrk_events, phase_events = [], []
+
+    def step(record: bool):
+        marks = [ev() for _ in range(5)] if record else None
+        if record: marks[0].record()
+        H.zero_()
+        for (c0, c1) in chunks:
+            if record:
+                e0, e1 = ev(), ev(); e0.record()
+            g.gptq_hessian_accumulate(H, X[:, c0:c1])
+            if record:
+                e1.record(); syrk_events.append((e0, e1, c1 - c0))
+        if record: marks[1].record()
+        g.gptq_damp_cholesky_inverse(H, lay.percdamp, chol_ws, info)
+        if record: marks[2].record()
+        g.gptq_quantize_layer(W, H, lay.bits, grid, lay.block, lay.group, codes, scales, zeros, q_ws, None, half)
+        if record: marks[3].record()
+        g.gptq_pack(codes, pbits, packed)
+        if record:
+            marks[4].record(); phase_events.append(marks)
+
+    for _ in range(a.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    if g.gptq_check_info(info) != 0:
+        raise RuntimeError("Cholesky reported a non-positive pivot")
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / a.steps
+
+    names = ["hessian", "damp_cholesky_inverse", "quantize_layer", "pack"]
+    phases = {nm: sum(mk[i].elapsed_time(mk[i + 1]) for mk in phase_events) / len(phase_events) for i, nm in enumerate(names)}
+    syrk_ms = [e0.elapsed_time(e1) for (e0, e1, _) in syrk_events]
+    syrk_avg_ms = sum(syrk_ms) / len(syrk_ms)
+    syrk_flops_per_launch = sum(float(n) * (n + 1) * t for (_, _, t) in syrk_events) / len(syrk_events)
+    achieved = syrk_flops_per_launch / (syrk_avg_ms * 1e-3) / 1e12
+    total_flops = sum(flops.values())
+    out = {
+        "metric": "gptq_layer_solve_tflops", "value": total_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1); u8 codes",
+        "data": "synthetic",
+        "config": {"workload": f"{lay.name}: W {r}x{n} {str(lay.dtype).split('.')[-1]}, X {n}x{m} {str(lay.x.dtype).split('.')[-1]}, "
+                               f"{lay.bits}-bit {lay.grid} grid, group {lay.group or 'per-row'}, B={lay.block}, damp {lay.percdamp}",
+                   "tokens_per_accumulate_call": chunk},
+        "phases_ms": {k: round(v, 3) for k, v in phases.items()},
+        "phase_tflops": {
+            "hessian_syrk": flops["hessian"] / (phases["hessian"] * 1e-3) / 1e12,
+            "cholesky_plus_inverse_f32": (flops["cholesky"] + flops["tri_inverse"]) / (phases["damp_cholesky_inverse"] * 1e-3) / 1e12,
+            "quantize_f32": flops["quantize"] / (phases["quantize_layer"] * 1e-3) / 1e12,
+        },
+        "pack_GBps": (r * n + packed.numel() * 4) / (phases["pack"] * 1e-3) / 1e9,
+        "algorithmic_flops": flops,
+        "roofline": {"kernel": "syrk_f16_kernel (gptq_hessian_accumulate)", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_F16_MFMA_TFLOPS,
+                     "avg_launch_ms": syrk_avg_ms, "flops_per_launch": syrk_flops_per_launch, "traffic": None},
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(lay, flops)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
