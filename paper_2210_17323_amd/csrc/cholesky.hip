@@ -7,17 +7,16 @@
 // matrix Alg. 1 asks for, at half the flops of "Cholesky, invert, Cholesky again" and without ever
 // forming the explicit inverse.
 //
-// Blocked, right-looking, block size 128, everything in place in the upper triangle:
-//   for block b = last .. first:                       (columns [j0, j1))
+// Two-level blocking (inner 128, outer 512), everything in place in the upper triangle:
+//   factorisation, outer blocks last .. first, inner blocks last .. first:
 //     R_bb  = reverse-Cholesky of the 128x128 diagonal block (one workgroup, block in LDS),
 //             and its inverse R_bb^-1 kept in the workspace
 //     P     = H[0:j0, j0:j1] * R_bb^-T                  (GEMM; P is the panel of R above the block)
-//     H[0:j0, 0:j0] -= P P^T                            (GEMM, upper tiles only)
-//   for block b = first .. last:                        (in-place triangular inverse)
-//     R[b, right]    = -R_bb^-1 * R[b, right]
-//     R[above, right] += R[above, b] * R[b, right]      (the rank-128 update that carries the flops)
-//     R[above, b]    = R[above, b] * R_bb^-1
-//     R[b, b]        = R_bb^-1
+//     H[0:j0, outer block columns left of j0] -= P P^T  (rank-128, confined to the outer block)
+//     after the outer block: H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T   (rank-512, carries the flops)
+//   triangular inverse, outer block columns first .. last:
+//     the 512x512 diagonal block is inverted in place with rank-128 steps, then
+//     U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1)           (K = o0, carries the flops)
 #include "common.h"
 
 namespace gptq {
@@ -118,12 +117,26 @@ __global__ __launch_bounds__(256) void zero_lower_kernel(float* H, int64_t ld, i
 
 using namespace gptq;
 
+namespace {
+constexpr int OB = 512;      // outer block: rank-512 updates keep the big GEMMs compute-bound
+
+struct CholWs { float* dinv; float* P; float* T; float* dense; size_t total; };
+CholWs chol_ws_layout(void* ws, int64_t n) {
+    const size_t nblk = (size_t)ceil_div(std::max<int64_t>(n, 1), NB);
+    size_t off = 0;
+    CholWs l{};
+    char* base = static_cast<char*>(ws);
+    l.dinv = reinterpret_cast<float*>(base + off);  off += round_up(nblk * NB * NB * sizeof(float), 256);
+    l.P = reinterpret_cast<float*>(base + off);     off += round_up((size_t)std::max<int64_t>(n, 1) * NB * sizeof(float), 256);
+    l.T = reinterpret_cast<float*>(base + off);     off += round_up((size_t)std::max<int64_t>(n, 1) * OB * sizeof(float), 256);
+    l.dense = reinterpret_cast<float*>(base + off); off += (size_t)OB * OB * sizeof(float);
+    l.total = off + 256;
+    return l;
+}
+}  // namespace
+
 extern "C" size_t gptq_damp_cholesky_inverse_workspace_bytes(int64_t n) {
-    if (n <= 0) return 256;
-    const size_t nblk = (size_t)ceil_div(n, NB);
-    const size_t dinv = nblk * NB * NB * sizeof(float);
-    const size_t panel = round_up((size_t)n * NB * sizeof(float), 256);
-    return dinv + panel + 256;
+    return chol_ws_layout(nullptr, n < 0 ? 0 : n).total;
 }
 
 extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float percdamp,
@@ -139,75 +152,92 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     if (!ws || !aligned(ws, 256) || ws_bytes < gptq_damp_cholesky_inverse_workspace_bytes(n))
         return fail(GPTQ_ERR_WORKSPACE, "damp_cholesky_inverse: workspace missing, misaligned or too small");
 
-    const int64_t nblk = ceil_div(n, NB);
-    float* dinv = static_cast<float*>(ws);
-    float* P = dinv + nblk * NB * NB;
+    const CholWs w = chol_ws_layout(ws, n);
+    float* dinv = w.dinv;
+    float* P = w.P;
     constexpr size_t diag_lds = 2 * NB * DP * sizeof(float);
     GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(diag_block_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)diag_lds));
 
     hipLaunchKernelGGL(damp_kernel, dim3(1), dim3(1024), 0, s, H, ld, n, percdamp, info_dev);
     GPTQ_LAUNCH_CHECK();
 
-    // ---- H + lambda I = R R^T, from the last block backwards
-    for (int64_t b = nblk - 1; b >= 0; --b) {
-        const int64_t j0 = b * NB;
-        const int nbk = (int)std::min<int64_t>(NB, n - j0);
-        float* Dblk = H + j0 * ld + j0;
-        float* dinv_b = dinv + b * NB * NB;
-        hipLaunchKernelGGL(diag_block_kernel, dim3(1), dim3(256), diag_lds, s, Dblk, ld, nbk, dinv_b, info_dev, (int)j0);
-        GPTQ_LAUNCH_CHECK();
-        if (j0 == 0) break;
-        // P = H[0:j0, j0:j1] * R_bb^-T
+    auto gemm = [&](const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                    float alpha, bool nk, bool overwrite, bool upper, int64_t crow0, int64_t ccol0, bool atri) -> int {
         GemmF32 g{};
-        g.A = H + j0; g.lda = ld; g.B = dinv_b; g.ldb = NB; g.C = P; g.ldc = NB;
-        g.M = j0; g.N = nbk; g.K = nbk; g.alpha = 1.f; g.b_is_nk = true; g.overwrite = true;
-        int rc = launch_gemm_f32(g, s);
-        if (rc) return rc;
-        const int cb = (int)std::min<int64_t>(ceil_div(j0 * nbk, 256), 4096);
-        hipLaunchKernelGGL(copy_block_kernel, dim3(cb), dim3(256), 0, s, H + j0, ld, (const float*)P, (int64_t)NB, j0, nbk, 0);
-        GPTQ_LAUNCH_CHECK();
-        // H[0:j0, 0:j0] -= P P^T (upper tiles)
-        GemmF32 u{};
-        u.A = P; u.lda = NB; u.B = P; u.ldb = NB; u.C = H; u.ldc = ld;
-        u.M = j0; u.N = j0; u.K = nbk; u.alpha = -1.f; u.b_is_nk = true; u.overwrite = false;
-        u.upper_only = true; u.crow0 = 0; u.ccol0 = 0;
-        rc = launch_gemm_f32(u, s);
-        if (rc) return rc;
-    }
+        g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
+        g.b_is_nk = nk; g.overwrite = overwrite; g.upper_only = upper; g.crow0 = crow0; g.ccol0 = ccol0; g.a_upper_tri = atri;
+        return launch_gemm_f32(g, s);
+    };
+    const int64_t nouter = ceil_div(n, OB);
 
-    // ---- U = R^-1 in place
-    for (int64_t b = 0; b < nblk; ++b) {
-        const int64_t j0 = b * NB;
-        const int nbk = (int)std::min<int64_t>(NB, n - j0);
-        const int64_t j1 = j0 + nbk;
-        const float* dinv_b = dinv + b * NB * NB;
-        if (j1 < n) {
-            // R[b, right] = -R_bb^-1 * R[b, right].  In place: a workgroup reads its own 128 columns of
-            // all (<= 128) rows through LDS before its epilogue writes them, and there is one row tile.
-            GemmF32 g{};
-            g.A = dinv_b; g.lda = NB; g.B = H + j0 * ld + j1; g.ldb = ld; g.C = H + j0 * ld + j1; g.ldc = ld;
-            g.M = nbk; g.N = n - j1; g.K = nbk; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = true;
-            int rc = launch_gemm_f32(g, s);
+    // ---- H + lambda I = R R^T, from the last column backwards.  Two levels: inside an outer block of
+    //      512 columns the rank-128 updates touch only that block's columns; the rest of the matrix gets
+    //      one rank-512 update per outer block.
+    for (int64_t o = nouter - 1; o >= 0; --o) {
+        const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);
+        for (int64_t j0 = (ceil_div(o1 - o0, NB) - 1) * NB + o0; j0 >= o0; j0 -= NB) {
+            const int nbk = (int)std::min<int64_t>(NB, n - j0);
+            float* dinv_b = dinv + (j0 / NB) * NB * NB;
+            hipLaunchKernelGGL(diag_block_kernel, dim3(1), dim3(256), diag_lds, s, H + j0 * ld + j0, ld, nbk, dinv_b, info_dev, (int)j0);
+            GPTQ_LAUNCH_CHECK();
+            if (j0 == 0) break;
+            // P = H[0:j0, j0:j1] * R_bb^-T  (the panel of R above the block), then store it in place
+            int rc = gemm(H + j0, ld, dinv_b, NB, P, NB, j0, nbk, nbk, 1.f, true, true, false, 0, 0, false);
             if (rc) return rc;
-            if (j0 > 0) {
-                GemmF32 u{};
-                u.A = H + j0; u.lda = ld; u.B = H + j0 * ld + j1; u.ldb = ld; u.C = H + j1; u.ldc = ld;
-                u.M = j0; u.N = n - j1; u.K = nbk; u.alpha = 1.f; u.b_is_nk = false; u.overwrite = false;
-                rc = launch_gemm_f32(u, s);
+            const int cb = (int)std::min<int64_t>(ceil_div(j0 * nbk, 256), 4096);
+            hipLaunchKernelGGL(copy_block_kernel, dim3(cb), dim3(256), 0, s, H + j0, ld, (const float*)P, (int64_t)NB, j0, nbk, 0);
+            GPTQ_LAUNCH_CHECK();
+            // H[0:j0, o0:j0] -= P * P[o0:j0]^T  (columns of this outer block only; tiles below the diagonal skipped)
+            if (j0 > o0) {
+                rc = gemm(P, NB, P + o0 * NB, NB, H + o0, ld, j0, j0 - o0, nbk, -1.f, true, false, true, 0, o0, false);
                 if (rc) return rc;
             }
         }
-        if (j0 > 0) {
-            // R[above, b] = R[above, b] * R_bb^-1.  In place: one column tile, each workgroup reads all
-            // of its own rows before writing them.
-            GemmF32 g{};
-            g.A = H + j0; g.lda = ld; g.B = dinv_b; g.ldb = NB; g.C = H + j0; g.ldc = ld;
-            g.M = j0; g.N = nbk; g.K = nbk; g.alpha = 1.f; g.b_is_nk = false; g.overwrite = true;
-            int rc = launch_gemm_f32(g, s);
+        // H[0:o0, 0:o0] -= R[0:o0, o0:o1] * R[0:o0, o0:o1]^T  (rank-512, upper tiles)
+        if (o0 > 0) {
+            const int rc = gemm(H + o0, ld, H + o0, ld, H, ld, o0, o0, o1 - o0, -1.f, true, false, true, 0, 0, false);
             if (rc) return rc;
         }
-        hipLaunchKernelGGL(copy_block_kernel, dim3(64), dim3(256), 0, s, H + j0 * ld + j0, ld, dinv_b, (int64_t)NB, (int64_t)nbk, nbk, 1);
-        GPTQ_LAUNCH_CHECK();
+    }
+
+    // ---- U = R^-1 in place, one outer block column at a time (left to right):
+    //      invert the 512 x 512 diagonal block in place with rank-128 steps, then
+    //      U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1), a long-K GEMM against the finished part.
+    for (int64_t o = 0; o < nouter; ++o) {
+        const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);
+        for (int64_t j0 = o0; j0 < o1; j0 += NB) {
+            const int nbk = (int)std::min<int64_t>(NB, n - j0);
+            const int64_t j1 = j0 + nbk;
+            const float* dinv_b = dinv + (j0 / NB) * NB * NB;
+            if (j1 < o1) {
+                // R[b, right] = -R_bb^-1 * R[b, right].  In place: a workgroup reads its own 128 columns of all
+                // (<= 128) rows through LDS before its epilogue writes them, and there is a single tile row.
+                int rc = gemm(dinv_b, NB, H + j0 * ld + j1, ld, H + j0 * ld + j1, ld, nbk, o1 - j1, nbk, -1.f, false, true, false, 0, 0, false);
+                if (rc) return rc;
+                if (j0 > o0) {
+                    rc = gemm(H + o0 * ld + j0, ld, H + j0 * ld + j1, ld, H + o0 * ld + j1, ld, j0 - o0, o1 - j1, nbk, 1.f, false, false, false, 0, 0, false);
+                    if (rc) return rc;
+                }
+            }
+            if (j0 > o0) {
+                // R[above-in-block, b] = R[above-in-block, b] * R_bb^-1.  In place: a single tile column, each
+                // workgroup reads all of its own rows before writing them.
+                const int rc = gemm(H + o0 * ld + j0, ld, dinv_b, NB, H + o0 * ld + j0, ld, j0 - o0, nbk, nbk, 1.f, false, true, false, 0, 0, false);
+                if (rc) return rc;
+            }
+            hipLaunchKernelGGL(copy_block_kernel, dim3(64), dim3(256), 0, s, H + j0 * ld + j0, ld, dinv_b, (int64_t)NB, (int64_t)nbk, nbk, 1);
+            GPTQ_LAUNCH_CHECK();
+        }
+        if (o0 > 0) {
+            const int ow = (int)(o1 - o0);
+            // dense copy of the inverted diagonal block with an explicit zero lower triangle
+            hipLaunchKernelGGL(copy_block_kernel, dim3(256), dim3(256), 0, s, w.dense, (int64_t)OB, (const float*)(H + o0 * ld + o0), ld, (int64_t)ow, ow, 1);
+            GPTQ_LAUNCH_CHECK();
+            int rc = gemm(H + o0, ld, w.dense, OB, w.T, OB, o0, ow, ow, 1.f, false, true, false, 0, 0, false);
+            if (rc) return rc;
+            rc = gemm(H, ld, w.T, OB, H + o0, ld, o0, ow, o0, -1.f, false, true, false, 0, 0, true);
+            if (rc) return rc;
+        }
     }
     hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
     GPTQ_LAUNCH_CHECK();

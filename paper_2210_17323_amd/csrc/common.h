@@ -41,6 +41,8 @@ inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 //   overwrite: C = alpha * A * op(B) instead of accumulating.
 //   upper_only: skip 128x128 output tiles that lie entirely below the diagonal (row0 > col0 + 127),
 //               with (crow0, ccol0) the global offset of C's first element inside its parent matrix.
+//   a_upper_tri: A[M x K] is the top-left part of an upper-triangular matrix (A[i][k] == 0 for k < i
+//               rounded down to 128): the K loop of a tile starts at the tile's first row.
 // All pointers 16-byte aligned, leading dimensions multiples of 4.
 struct GemmF32 {
     const float* A; int64_t lda;
@@ -52,6 +54,7 @@ struct GemmF32 {
     bool overwrite;
     bool upper_only;
     int64_t crow0, ccol0;
+    bool a_upper_tri;   // A is upper triangular with zeros below its diagonal blocks: skip k < first row of the tile
 };
 int launch_gemm_f32(const GemmF32& g, hipStream_t s);
 

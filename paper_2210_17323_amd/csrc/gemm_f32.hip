@@ -24,8 +24,13 @@ struct GemmArgs {
     float alpha;
     int overwrite, upper_only;
     int64_t crow0, ccol0;
-    int tiles_n;
+    int a_upper_tri;
+    int tiles_m, tiles_n;
+    int64_t per_xcd, total;
 };
+
+constexpr int GROUP_M = 16;     // tile rows walked fastest inside a group, so co-resident workgroups share B panels
+constexpr int NXCD = 8;
 
 __device__ __forceinline__ float4 load4_guard(const float* p, int64_t valid) {
     // valid = number of in-range elements starting at p (<= 0: none)
@@ -37,40 +42,42 @@ __device__ __forceinline__ float4 load4_guard(const float* p, int64_t valid) {
     return v;
 }
 
-template <bool B_IS_NK>
-__global__ __launch_bounds__(256, 2) void gemm_f32_kernel(GemmArgs g) {
-    __shared__ float As[2][TK][PITCH];
-    __shared__ float Bs[2][TK][PITCH];
-
+// The body of one tile.  EDGE = false: the tile lies fully inside C and K is a multiple of TK, so every
+// load is an unguarded float4 and the epilogue reads its 16 C values per MFMA tile before it writes any.
+template <bool B_IS_NK, bool EDGE>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int64_t m0, const int64_t n0,
+                                          float (*As)[TK][PITCH], float (*Bs)[TK][PITCH]) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t tile = blockIdx.x;
-    const int64_t m0 = (tile / g.tiles_n) * TM, n0 = (tile % g.tiles_n) * TN;
-    if (g.upper_only && g.crow0 + m0 > g.ccol0 + n0 + (TN - 1)) return;
 
     // ---- global -> register staging: 2 float4 of A and 2 float4 of B per thread per K step
     float4 ra[2], rb[2];
+    const float* pa[2];
+    const float* pb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = tid + 256 * i;
+        pa[i] = g.A + (m0 + (q >> 2)) * g.lda + (q & 3) * 4;
+        pb[i] = B_IS_NK ? g.B + (n0 + (q >> 2)) * g.ldb + (q & 3) * 4
+                        : g.B + (int64_t)(q >> 5) * g.ldb + n0 + (q & 31) * 4;
+    }
     auto load_tiles = [&](int64_t k0) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int q = tid + 256 * i;
-            {
-                const int row = q >> 2, kc = (q & 3) * 4;
-                const int64_t gr = m0 + row;
-                ra[i] = (gr < g.M) ? load4_guard(g.A + gr * g.lda + k0 + kc, g.K - (k0 + kc))
-                                   : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-            if (B_IS_NK) {
-                const int row = q >> 2, kc = (q & 3) * 4;
-                const int64_t gn = n0 + row;
-                rb[i] = (gn < g.N) ? load4_guard(g.B + gn * g.ldb + k0 + kc, g.K - (k0 + kc))
-                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (!EDGE) {
+                ra[i] = *reinterpret_cast<const float4*>(pa[i] + k0);
+                rb[i] = *reinterpret_cast<const float4*>(B_IS_NK ? pb[i] + k0 : pb[i] + k0 * g.ldb);
             } else {
-                const int krow = q >> 5, nc = (q & 31) * 4;
-                const int64_t gk = k0 + krow;
-                rb[i] = (gk < g.K) ? load4_guard(g.B + gk * g.ldb + n0 + nc, g.N - (n0 + nc))
-                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+                const int row = q >> 2, kc = (q & 3) * 4;
+                ra[i] = (m0 + row < g.M) ? load4_guard(pa[i] + k0, g.K - (k0 + kc)) : make_float4(0.f, 0.f, 0.f, 0.f);
+                if (B_IS_NK) {
+                    rb[i] = (n0 + row < g.N) ? load4_guard(pb[i] + k0, g.K - (k0 + kc)) : make_float4(0.f, 0.f, 0.f, 0.f);
+                } else {
+                    const int krow = q >> 5, nc = (q & 31) * 4;
+                    rb[i] = (k0 + krow < g.K) ? load4_guard(pb[i] + k0 * g.ldb, g.N - (n0 + nc)) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
             }
         }
     };
@@ -107,26 +114,40 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_kernel(GemmArgs g) {
             for (int i = 0; i < 16; ++i) acc[s][t][i] = 0.f;
 
     const int64_t ksteps = (g.K + TK - 1) / TK;
-    load_tiles(0);
-    store_tiles(0);
+    // A upper triangular (its row r is zero left of column r): the first m0 columns contribute nothing
+    const int64_t ks0 = g.a_upper_tri ? (m0 / TK) : 0;
+    load_tiles(ks0 * TK);
+    store_tiles(ks0 & 1);
     __syncthreads();
 
     const int l32 = lane & 31, lhi = lane >> 5;
-    for (int64_t ks = 0; ks < ksteps; ++ks) {
+    for (int64_t ks = ks0; ks < ksteps; ++ks) {
         const int buf = ks & 1;
         if (ks + 1 < ksteps) load_tiles((ks + 1) * TK);
+        // operand fragments of step kk+1 are read from LDS while the MFMAs of step kk run
+        float a[2], b[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) a[s] = As[buf][lhi][wm * 64 + s * 32 + l32];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) b[t] = Bs[buf][lhi][wn * 64 + t * 32 + l32];
 #pragma unroll
         for (int kk = 0; kk < TK / 2; ++kk) {
-            float a[2], b[2];
+            float an[2], bn[2];
+            if (kk + 1 < TK / 2) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s) a[s] = As[buf][2 * kk + lhi][wm * 64 + s * 32 + l32];
+                for (int s = 0; s < 2; ++s) an[s] = As[buf][2 * kk + 2 + lhi][wm * 64 + s * 32 + l32];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) b[t] = Bs[buf][2 * kk + lhi][wn * 64 + t * 32 + l32];
+                for (int t = 0; t < 2; ++t) bn[t] = Bs[buf][2 * kk + 2 + lhi][wn * 64 + t * 32 + l32];
+            }
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
                     acc[s][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[t], acc[s][t], 0, 0, 0);
+            if (kk + 1 < TK / 2) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) { a[s] = an[s]; b[s] = bn[s]; }
+            }
         }
         if (ks + 1 < ksteps) {
             store_tiles(buf ^ 1);
@@ -140,17 +161,53 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_kernel(GemmArgs g) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int64_t col = n0 + wn * 64 + t * 32 + l32;
-            if (col >= g.N) continue;
+            const int64_t rbase = m0 + wm * 64 + s * 32 + 4 * lhi;
+            float* cbase = g.C + rbase * g.ldc + col;
+            if (!EDGE) {
+                float cv[16];
+                if (!g.overwrite) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int64_t row = m0 + wm * 64 + s * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
-                if (row < g.M) {
-                    float* c = g.C + row * g.ldc + col;
+                    for (int i = 0; i < 16; ++i) cv[i] = cbase[(int64_t)(8 * (i >> 2) + (i & 3)) * g.ldc];
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
                     const float v = g.alpha * acc[s][t][i];
-                    *c = g.overwrite ? v : (*c + v);
+                    cbase[(int64_t)(8 * (i >> 2) + (i & 3)) * g.ldc] = g.overwrite ? v : (cv[i] + v);
+                }
+            } else {
+                if (col >= g.N) continue;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int64_t row = rbase + 8 * (i >> 2) + (i & 3);
+                    if (row < g.M) {
+                        float* c = g.C + row * g.ldc + col;
+                        const float v = g.alpha * acc[s][t][i];
+                        *c = g.overwrite ? v : (*c + v);
+                    }
                 }
             }
         }
+}
+
+template <bool B_IS_NK>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) void gemm_f32_kernel(GemmArgs g) {
+    __shared__ float As[2][TK][PITCH];
+    __shared__ float Bs[2][TK][PITCH];
+    // Workgroup -> tile: consecutive workgroup ids land on different XCDs, so give each XCD a contiguous
+    // range of the tile order; the order walks GROUP_M tile rows fastest, then tile columns.
+    // (Triangular work -- skipped tiles or row-dependent K ranges -- is dealt round-robin instead, which
+    // balances it across the XCDs.)
+    const int64_t w = blockIdx.x;
+    const int64_t tile = (g.upper_only || g.a_upper_tri) ? w : (w % NXCD) * g.per_xcd + (w / NXCD);
+    if (tile >= g.total) return;
+    const int64_t per_group = (int64_t)GROUP_M * g.tiles_n;
+    const int64_t grp = tile / per_group, rem = tile % per_group;
+    const int rows_in_group = min(GROUP_M, g.tiles_m - (int)grp * GROUP_M);
+    const int64_t m0 = (grp * GROUP_M + rem % rows_in_group) * TM, n0 = (rem / rows_in_group) * TN;
+    if (g.upper_only && g.crow0 + m0 > g.ccol0 + n0 + (TN - 1)) return;
+    const bool interior = (m0 + TM <= g.M) && (n0 + TN <= g.N) && (g.K % TK == 0);
+    if (interior) gemm_tile<B_IS_NK, false>(g, m0, n0, As, Bs);
+    else          gemm_tile<B_IS_NK, true>(g, m0, n0, As, Bs);
 }
 
 int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
@@ -161,10 +218,13 @@ int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
     g.A = p.A; g.lda = p.lda; g.B = p.B; g.ldb = p.ldb; g.C = p.C; g.ldc = p.ldc;
     g.M = p.M; g.N = p.N; g.K = p.K < 0 ? 0 : p.K; g.alpha = p.alpha;
     g.overwrite = p.overwrite; g.upper_only = p.upper_only; g.crow0 = p.crow0; g.ccol0 = p.ccol0;
+    g.a_upper_tri = p.a_upper_tri;
     const int64_t tm = ceil_div(p.M, TM), tn = ceil_div(p.N, TN);
-    if (tm * tn > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "gemm_f32: too many tiles");
-    g.tiles_n = (int)tn;
-    dim3 grid((unsigned)(tm * tn));
+    if (tm * tn > 0x7ffffff0LL) return fail(GPTQ_ERR_UNSUPPORTED, "gemm_f32: too many tiles");
+    g.tiles_m = (int)tm; g.tiles_n = (int)tn;
+    g.total = tm * tn;
+    g.per_xcd = ceil_div(g.total, NXCD);
+    dim3 grid((unsigned)(g.per_xcd * NXCD));
     if (p.b_is_nk) hipLaunchKernelGGL(gemm_f32_kernel<true>, grid, dim3(256), 0, s, g);
     else           hipLaunchKernelGGL(gemm_f32_kernel<false>, grid, dim3(256), 0, s, g);
     GPTQ_LAUNCH_CHECK();

@@ -10,7 +10,8 @@
 //       cross-lane traffic at all; the 128 x 128 block of U is the same for every lane and is read
 //       through uniform (scalar) loads.  The column loop is fully unrolled so every register index
 //       is static.  Outputs: codes, the block's error matrix E (r x 128), per-row sum of e^2.
-//   trailing update    : W[:, i+B:] -= E * U[i:i+B, i+B:], the float32 matrix-core GEMM.
+//   trailing update    : W[:, i+B:] -= E * U[i:i+B, i+B:], the float32 matrix-core GEMM, applied at once to
+//       the rest of the current 512-column outer block and deferred (rank 512) for the columns beyond.
 #include "common.h"
 
 namespace gptq {
@@ -108,7 +109,7 @@ struct QuantArgs {
     float* scales; int32_t* zeros; int64_t ngroups;   // [r x ngroups]
     int64_t group;                  // 0 or the group size
     uint8_t* codes; int64_t ldc;
-    float* E;                       // [r x 128]
+    float* E; int64_t lde;          // this block's 128 columns of the outer error matrix [r x 512]
     double* half_e2;                // [r] or null
     int first_block;
 };
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     }
     if (!active) return;
     // ---- outputs: E row (the registers now hold e_j), codes, per-row error
-    float* edst = a.E + row * QB;
+    float* edst = a.E + row * a.lde;
 #pragma unroll
     for (int k = 0; k < QB; k += 4) *reinterpret_cast<float4*>(edst + k) = make_float4(w[k], w[k + 1], w[k + 2], w[k + 3]);
     uint8_t* cdst = a.codes + row * a.ldc + a.j0;
@@ -214,13 +215,15 @@ static bool group_supported(int64_t group) {
     return group == 8 || group == 16 || group == 32 || group == 64;
 }
 
+constexpr int QOB = 512;    // outer block: trailing updates beyond it are deferred and applied as one rank-512 GEMM
+
 struct QuantWs { size_t wk, e, ub, total; int64_t ldk; };
 static QuantWs quant_ws_layout(int64_t r, int64_t n) {
     QuantWs l;
     l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
     l.wk = 0;
     size_t off = round_up((size_t)std::max<int64_t>(r, 1) * l.ldk * sizeof(float), 256);
-    l.e = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QB * sizeof(float), 256);
+    l.e = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QOB * sizeof(float), 256);
     l.ub = off; off += QB * QB * sizeof(float);
     l.total = off + 256;
     return l;
@@ -282,32 +285,48 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     GPTQ_LAUNCH_CHECK();
 
     const unsigned qblocks = (unsigned)ceil_div(r, 64);
-    for (int64_t j0 = 0; j0 < n; j0 += QB) {
-        const int nbk = (int)std::min<int64_t>(QB, n - j0);
-        const int64_t j1 = j0 + nbk;
-        hipLaunchKernelGGL(copy_u_block_kernel, dim3(16), dim3(256), 0, s, U, ldu, n, j0, Ub);
-        GPTQ_LAUNCH_CHECK();
-        if (group >= QB && j0 % group == 0) {
-            hipLaunchKernelGGL(group_grid_kernel, dim3((unsigned)r), dim3(64), 0, s, (const float*)Wk, lay.ldk, j0, group, grid, (float)maxq, scales, zeros, ngroups, j0 / group);
+    // Lazy batching at two levels (Section 3, Step 2 applied twice): inside an outer block of 512 columns
+    // each 128-column block updates only the rest of the outer block (rank 128); the columns beyond it
+    // get one rank-512 update per outer block.  Same sums as Alg. 1, associated differently.
+    // A group grid must see fully updated weights at its first column, so an outer block may only end
+    // where a group ends: groups that neither divide 512 nor are multiples of it fall back to one level.
+    const int64_t ob = (group >= QB && (QOB % group) && (group % QOB)) ? QB : QOB;
+    for (int64_t o0 = 0; o0 < n; o0 += ob) {
+        const int64_t o1 = std::min<int64_t>(o0 + ob, n);
+        for (int64_t j0 = o0; j0 < o1; j0 += QB) {
+            const int nbk = (int)std::min<int64_t>(QB, n - j0);
+            const int64_t j1 = j0 + nbk;
+            hipLaunchKernelGGL(copy_u_block_kernel, dim3(16), dim3(256), 0, s, U, ldu, n, j0, Ub);
             GPTQ_LAUNCH_CHECK();
+            if (group >= QB && j0 % group == 0) {
+                hipLaunchKernelGGL(group_grid_kernel, dim3((unsigned)r), dim3(64), 0, s, (const float*)Wk, lay.ldk, j0, group, grid, (float)maxq, scales, zeros, ngroups, j0 / group);
+                GPTQ_LAUNCH_CHECK();
+            }
+            QuantArgs a{};
+            a.Wk = Wk; a.ldk = lay.ldk; a.Ub = Ub; a.r = r; a.j0 = j0; a.nbk = nbk; a.grid = grid; a.maxq = maxq;
+            a.scales = scales; a.zeros = zeros; a.ngroups = ngroups; a.group = group;
+            a.codes = codes; a.ldc = ldc; a.E = E + (j0 - o0); a.lde = QOB; a.half_e2 = half_E2_rows; a.first_block = (j0 == 0);
+            const int G = (group > 0 && group < QB) ? (int)group : 0;
+            switch (G) {
+                case 0:  hipLaunchKernelGGL(quant_block_kernel<0>,  dim3(qblocks), dim3(64), 0, s, a); break;
+                case 8:  hipLaunchKernelGGL(quant_block_kernel<8>,  dim3(qblocks), dim3(64), 0, s, a); break;
+                case 16: hipLaunchKernelGGL(quant_block_kernel<16>, dim3(qblocks), dim3(64), 0, s, a); break;
+                case 32: hipLaunchKernelGGL(quant_block_kernel<32>, dim3(qblocks), dim3(64), 0, s, a); break;
+                default: hipLaunchKernelGGL(quant_block_kernel<64>, dim3(qblocks), dim3(64), 0, s, a); break;
+            }
+            GPTQ_LAUNCH_CHECK();
+            if (j1 < o1) {
+                GemmF32 g{};
+                g.A = E + (j0 - o0); g.lda = QOB; g.B = U + j0 * ldu + j1; g.ldb = ldu; g.C = Wk + j1; g.ldc = lay.ldk;
+                g.M = r; g.N = o1 - j1; g.K = nbk; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
+                const int rc = launch_gemm_f32(g, s);
+                if (rc) return rc;
+            }
         }
-        QuantArgs a{};
-        a.Wk = Wk; a.ldk = lay.ldk; a.Ub = Ub; a.r = r; a.j0 = j0; a.nbk = nbk; a.grid = grid; a.maxq = maxq;
-        a.scales = scales; a.zeros = zeros; a.ngroups = ngroups; a.group = group;
-        a.codes = codes; a.ldc = ldc; a.E = E; a.half_e2 = half_E2_rows; a.first_block = (j0 == 0);
-        const int G = (group > 0 && group < QB) ? (int)group : 0;
-        switch (G) {
-            case 0:  hipLaunchKernelGGL(quant_block_kernel<0>,  dim3(qblocks), dim3(64), 0, s, a); break;
-            case 8:  hipLaunchKernelGGL(quant_block_kernel<8>,  dim3(qblocks), dim3(64), 0, s, a); break;
-            case 16: hipLaunchKernelGGL(quant_block_kernel<16>, dim3(qblocks), dim3(64), 0, s, a); break;
-            case 32: hipLaunchKernelGGL(quant_block_kernel<32>, dim3(qblocks), dim3(64), 0, s, a); break;
-            default: hipLaunchKernelGGL(quant_block_kernel<64>, dim3(qblocks), dim3(64), 0, s, a); break;
-        }
-        GPTQ_LAUNCH_CHECK();
-        if (j1 < n) {
+        if (o1 < n) {
             GemmF32 g{};
-            g.A = E; g.lda = QB; g.B = U + j0 * ldu + j1; g.ldb = ldu; g.C = Wk + j1; g.ldc = lay.ldk;
-            g.M = r; g.N = n - j1; g.K = nbk; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
+            g.A = E; g.lda = QOB; g.B = U + o0 * ldu + o1; g.ldb = ldu; g.C = Wk + o1; g.ldc = lay.ldk;
+            g.M = r; g.N = n - o1; g.K = o1 - o0; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
             const int rc = launch_gemm_f32(g, s);
             if (rc) return rc;
         }

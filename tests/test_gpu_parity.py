@@ -158,6 +158,9 @@ QUANT_CASES = [
     (4, "minmax", 32, torch.float16, 64, 256),
     (2, "ternary", 8, torch.float16, 64, 256),
     (3, "minmax", 256, torch.float16, 96, 512),
+    (3, "minmax", 384, torch.float16, 40, 1536),
+    (4, "minmax", 1024, torch.float16, 40, 2048),
+    (3, "minmax", 0, torch.float16, 130, 1280),
     (3, "minmax", 0, torch.float16, 1, 8),
 ]
 
