@@ -59,22 +59,6 @@ def flop_model(r: int, n: int, m: int, B: int = 128):
     }
 
 
-def generate_inputs(lay, device):
-    import torch
-    scales = lay.x.scales()
-    X = torch.empty((lay.n, lay.x.m), dtype=lay.x.dtype, device=device)
-    rows = max(1, min(lay.n, (1 << 27) // max(lay.x.m, 1)))
-    for r0 in range(0, lay.n, rows):
-        nr = min(rows, lay.n - r0)
-        X[r0:r0 + nr] = lay.x.tile(row0=r0, nrows=nr, device=device, scales=scales)
-    W = torch.empty((lay.r, lay.n), dtype=lay.dtype, device=device)
-    rows = max(1, min(lay.r, (1 << 27) // lay.n))
-    for r0 in range(0, lay.r, rows):
-        nr = min(rows, lay.r - r0)
-        W[r0:r0 + nr] = lay.weights(row0=r0, nrows=nr, device=device)
-    return W, X
-
-
 def cpu_baseline(lay, flops):
     """The float64 NumPy oracle, as it stands, timed on the host cores on a bounded sample of the
     same workload; each step is timed on a reduced problem and scaled by its flop count."""
@@ -122,7 +106,8 @@ def main():
     lay = pick_layer(a.layer, a.tokens)
     r, n, m = lay.r, lay.n, lay.x.m
     flops = flop_model(r, n, m, lay.block)
-    W, X = generate_inputs(lay, dev)
+    from workloads import configs
+    W, X = configs.materialize(lay, dev)
     H = torch.empty((n, n), dtype=torch.float32, device=dev)
     chol_ws = torch.empty(g.gptq_damp_cholesky_inverse_workspace_bytes(n), dtype=torch.uint8, device=dev)
     info = torch.zeros(1, dtype=torch.int32, device=dev)

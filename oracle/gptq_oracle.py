@@ -141,7 +141,7 @@ def dequant(codes, scale, zero) -> np.ndarray:
 # --------------------------------------------------------------------------------------------
 
 def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group: int = 0,
-                  decision_dtype=np.float32):
+                  decision_dtype=np.float32, teacher_codes=None):
     """Algorithm 1: quantize W (d_row x d_col) given U = Cholesky(H^-1)^T and block size B.
 
     group == 0: one grid per row, fixed from the original weights before the process starts
@@ -151,12 +151,19 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
     Because updates to columns beyond the current block are deferred, "current" is only well
     defined when no group straddles a block end: B must be a multiple of g or g a multiple of B.
 
+    teacher_codes (optional, d_row x d_col): "teacher forcing" for comparing two arithmetics without the
+    avalanche that follows a single differing rounding decision.  The code this function would choose
+    for each column is still computed from the current weights and returned as `codes`, but the
+    algorithm then continues with the teacher's code (Q, E and all updates use it), so every decision
+    is taken on the teacher's history.  In grouped mode the grids are still computed here.
+
     Returns a dict with codes (int64), scale (rows x groups, decision_dtype), zero (int64),
     Q (float64 dequantised weights), E (d_row x d_col, every column's scaled error),
-    W_final (the working copy after all updates).
+    W_final (the working copy after all updates), and frac (the pre-rounding values w/scale).
+    U may be float32 (it is widened to float64 block row by block row).
     """
     Wk = np.array(W, dtype=np.float64, copy=True)
-    U = np.asarray(U, dtype=np.float64)
+    U = np.asarray(U)
     r, n = Wk.shape
     if group and n % group:
         raise ValueError("d_col must be a multiple of the group size")
@@ -174,20 +181,24 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
     if not group:
         scale, zero = grid_params(Wk, bits, grid, decision_dtype)
         scales[:, 0], zeros[:, 0] = scale, zero
+    frac = np.zeros((r, n), dtype=decision_dtype)
     for i in range(0, n, block):
         iend = min(i + block, n)
         E = np.zeros((r, iend - i))
+        Ub = np.asarray(U[i:iend], dtype=np.float64)        # rows i..iend-1 of U, exact widening
         for j in range(i, iend):
             if group and j % group == 0:
                 scale, zero = grid_params(Wk[:, j:j + group], bits, grid, decision_dtype)
                 scales[:, j // group], zeros[:, j // group] = scale, zero
             codes[:, j] = quant_codes(Wk[:, j], scale, zero, maxq, decision_dtype)
-            Q[:, j] = dequant(codes[:, j], scale, zero)
-            E[:, j - i] = (Wk[:, j] - Q[:, j]) / U[j, j]
-            Wk[:, j:iend] -= np.outer(E[:, j - i], U[j, j:iend])
-        Wk[:, iend:] -= E @ U[i:iend, iend:]
+            frac[:, j] = Wk[:, j].astype(decision_dtype) / scale
+            used = codes[:, j] if teacher_codes is None else np.asarray(teacher_codes)[:, j].astype(np.int64)
+            Q[:, j] = dequant(used, scale, zero)
+            E[:, j - i] = (Wk[:, j] - Q[:, j]) / Ub[j - i, j]
+            Wk[:, j:iend] -= np.outer(E[:, j - i], Ub[j - i, j:iend])
+        Wk[:, iend:] -= E @ Ub[:, iend:]
         E_all[:, i:iend] = E
-    return dict(codes=codes, scale=scales, zero=zeros, Q=Q, E=E_all, W_final=Wk)
+    return dict(codes=codes, scale=scales, zero=zeros, Q=Q, E=E_all, W_final=Wk, frac=frac)
 
 
 def naive_obs_quantize(W, Hd, bits: int, grid: str = "minmax", group: int = 0, decision_dtype=np.float32):

@@ -23,6 +23,10 @@ constexpr int HK = 64;          // token step (halves)
 constexpr int STRIP = 8;        // tile columns per strip
 constexpr int NXCD = 8;
 
+#ifndef GPTQ_SYRK_VARIANT
+#define GPTQ_SYRK_VARIANT 2      // 1: register-staged 8-wavefront kernel; 2: direct-to-LDS 4-wavefront kernel
+#endif
+
 struct SyrkArgs {
     float* H; int64_t ldh;
     const uint16_t* X; int64_t ldx;
@@ -172,6 +176,170 @@ __global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
         }
 }
 
+// ---- 256 x 256 tile, 4 wavefronts of 128 x 128, panels copied global -> LDS directly ----------------
+// Each wavefront keeps a 4 x 4 grid of 32x32 accumulators (256 registers), which halves the LDS reads
+// per MFMA compared with 128 x 64 wavefront tiles.  The two panels of a 32-token step (2 x 16 KB) go
+// straight from global memory into LDS with global_load_lds_dwordx4 (no staging registers, no
+// ds_write): one such instruction moves 16 rows x 64 bytes and lays the 64 lanes down linearly in LDS,
+// so the XOR swizzle of the 16-byte chunks is applied on the global side (lane l fetches chunk
+// (l % 4) ^ ((l / 8) % 4) of row l / 4).  Four stages: while step k is multiplied the copies of steps
+// k+1 .. k+3 are in flight, which is what hides the memory latency with one wavefront per SIMD; one
+// barrier per step.  Requires t % 128 == 0 (the caller splits off the tail).
+constexpr int DK = 32;                                  // tokens per stage
+constexpr int DSTAGE = 2 * 256 * DK * 2;                // bytes per stage: A panel + B panel
+
+template <bool IS_BF16>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void syrk_f16_dma_kernel(SyrkArgs g) {
+    constexpr int BT = 256;
+    constexpr int PANEL = BT * DK * 2;                  // 16 KB
+    // Separate LDS objects, one per stage: the compiler then knows that an asynchronous copy into one
+    // stage cannot alias the operand reads from another and does not make the reads wait for the copy.
+    __shared__ __attribute__((aligned(16))) unsigned char stage0[DSTAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char stage1[DSTAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char stage2[DSTAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char stage3[DSTAGE];
+
+    const int64_t w = blockIdx.x;
+    int64_t L = (w % NXCD) * g.per_xcd + (w / NXCD);
+    if (L >= g.total) return;
+    int bi, bj;
+    {
+        int s = 0;
+        for (;; ++s) {
+            const int cols = min(STRIP, g.nt - s * STRIP);
+            const int rows = min((s + 1) * STRIP, g.nt);
+            const int64_t cnt = (int64_t)cols * rows;
+            if (L < cnt) { bi = (int)(L / cols); bj = s * STRIP + (int)(L % cols); break; }
+            L -= cnt;
+        }
+    }
+    if (bi > bj) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int64_t r0 = (int64_t)bi * BT, c0 = (int64_t)bj * BT;
+
+    // this lane's part of the 4 + 4 copies of a step: row (wave*4 + i)*16 + lane/4 of each panel, chunk
+    // (lane%4) ^ ((lane/8)%4).  Rows past n are clamped: they only feed outputs that are never stored.
+    const int lrow = lane >> 2, lchunk = (lane & 3) ^ ((lane >> 3) & 3);
+    const uint16_t* xcol = g.X + lchunk * 8;
+    auto issue_copies = [&](unsigned char* stage, int64_t k0) {
+        unsigned char* base = stage + wave * 4 * 1024;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = (wave * 4 + i) * 16 + lrow;
+            const uint16_t* sa = xcol + min(r0 + row, g.n - 1) * g.ldx + k0;
+            const uint16_t* sb = xcol + min(c0 + row, g.n - 1) * g.ldx + k0;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sa,
+                                             (__attribute__((address_space(3))) void*)(base + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sb,
+                                             (__attribute__((address_space(3))) void*)(base + PANEL + i * 1024), 16, 0, 0);
+        }
+    };
+
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[s][u][i] = 0.f;
+
+    // This lane's operand rows are wm*128 + s*32 + lane%32 (A) and wn*128 + u*32 + lane%32 (B): the swizzle
+    // term (row / 2) % 4 is (lane / 2) % 4 for all of them, and s / u only add a constant 2048 bytes.
+    const int rowA = (wm * 128 + l32) * 64, rowB = PANEL + (wn * 128 + l32) * 64;
+    const int co0 = (lhi ^ ((l32 >> 1) & 3)) << 4;      // chunk offset of sub-step 0; sub-step 1 flips bit 5
+    // one 32-token step out of `cur`: the operand fragments of the second 16 tokens are fetched from LDS
+    // while the 16 MFMAs of the first 16 run
+    auto multiply = [&](const unsigned char* cur) {
+        uint4 fa[2][4], fb[2][4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            fa[0][s] = *reinterpret_cast<const uint4*>(cur + rowA + co0 + s * 2048);
+            fb[0][s] = *reinterpret_cast<const uint4*>(cur + rowB + co0 + s * 2048);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            fa[1][s] = *reinterpret_cast<const uint4*>(cur + rowA + (co0 ^ 32) + s * 2048);
+            fb[1][s] = *reinterpret_cast<const uint4*>(cur + rowB + (co0 ^ 32) + s * 2048);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[s][u] = mfma16<IS_BF16>(fa[kk][s], fb[kk][u], acc[s][u]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);       // the 8 reads of sub-step 0
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read of sub-step 1
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    };
+    // A bare s_barrier: __syncthreads() would also drain every outstanding copy (it fences all memory),
+    // which is exactly what the multi-stage pipeline must not do.  Visibility of a stage is established by
+    // each wavefront waiting for its own copies of that step -- vmcnt(16): only the 2 x 8 copies of the two
+    // later steps may still be in flight -- before it arrives at the barrier.
+    // The loop body is branch-free: past the last step the copies simply re-read the last 32 tokens into
+    // a stage nobody multiplies again, so every wait is the same vmcnt(16).
+    auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur) {
+        __builtin_amdgcn_s_waitcnt(0x4F70);             // vmcnt(16)
+        asm volatile("s_barrier" ::: "memory");         // everybody's copies of this step landed; everybody left `refill`
+        issue_copies(refill, min(k_refill, g.t - DK));
+        multiply(cur);
+    };
+    const int64_t ksteps = g.t / DK;                    // a multiple of 4 (the caller passes t % 128 == 0)
+    issue_copies(stage0, 0);
+    issue_copies(stage1, DK);
+    issue_copies(stage2, 2 * DK);
+    for (int64_t ks = 0; ks < ksteps; ks += 4) {
+        next_stage(stage3, (ks + 3) * DK, stage0);
+        next_stage(stage0, (ks + 4) * DK, stage1);
+        next_stage(stage1, (ks + 5) * DK, stage2);
+        next_stage(stage2, (ks + 6) * DK, stage3);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // drain the dummy copies before the LDS is released
+
+    // ---- H += 2 * acc
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t col = c0 + wn * 128 + u * 32 + l32;
+            if (col >= g.n) continue;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int64_t row = r0 + wm * 128 + s * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
+                if (row < g.n) {
+                    float* h = g.H + row * g.ldh + col;
+                    *h += 2.0f * acc[s][u][i];
+                }
+            }
+        }
+}
+
+static void syrk_schedule(SyrkArgs& g, int BT) {
+    g.nt = (int)ceil_div(g.n, BT);
+    int64_t total = 0;
+    for (int st = 0; st * STRIP < g.nt; ++st)
+        total += (int64_t)std::min(STRIP, g.nt - st * STRIP) * std::min((st + 1) * STRIP, g.nt);
+    g.total = total;
+    g.per_xcd = ceil_div(total, NXCD);
+}
+
+template <bool IS_BF16>
+static int launch_syrk_dma(SyrkArgs g, hipStream_t s) {
+    syrk_schedule(g, 256);
+    const int64_t blocks = g.per_xcd * NXCD;
+    if (blocks > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
+    auto kern = syrk_f16_dma_kernel<IS_BF16>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, s, g);
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}
+
 template <bool IS_BF16, int BT, int WM, int WN>
 static int launch_syrk(SyrkArgs g, hipStream_t s) {
     g.nt = (int)ceil_div(g.n, BT);
@@ -234,9 +402,28 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
     if (!aligned(X, 16) || ldx % 8) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: 16-bit X must be 16-byte aligned with ldx %% 8 == 0");
     SyrkArgs g{};
     g.H = H; g.ldh = ldh; g.X = static_cast<const uint16_t*>(X); g.ldx = ldx; g.n = n; g.t = t;
-    const bool big = n > 6144;      // 256-wide tiles only fill the chip when there are enough of them
-    if (xdtype == GPTQ_BF16) return big ? launch_syrk<true, 256, 2, 4>(g, s) : launch_syrk<true, 128, 2, 2>(g, s);
-    return big ? launch_syrk<false, 256, 2, 4>(g, s) : launch_syrk<false, 128, 2, 2>(g, s);
+    const bool bf = xdtype == GPTQ_BF16;
+    if (n <= 6144)                  // 256-wide tiles only fill the chip when there are enough of them
+        return bf ? launch_syrk<true, 128, 2, 2>(g, s) : launch_syrk<false, 128, 2, 2>(g, s);
+#if GPTQ_SYRK_VARIANT == 1
+    return bf ? launch_syrk<true, 256, 2, 4>(g, s) : launch_syrk<false, 256, 2, 4>(g, s);
+#else
+    // whole pairs of 64-token steps through the direct-to-LDS kernel, a ragged tail through the guarded one
+    const int64_t t_main = t / (2 * HK) * (2 * HK);
+    if (t_main > 0) {
+        SyrkArgs gm = g;
+        gm.t = t_main;
+        const int rc = bf ? launch_syrk_dma<true>(gm, s) : launch_syrk_dma<false>(gm, s);
+        if (rc) return rc;
+    }
+    if (t_main < t) {
+        SyrkArgs gt = g;
+        gt.X = g.X + t_main;
+        gt.t = t - t_main;
+        return bf ? launch_syrk<true, 256, 2, 4>(gt, s) : launch_syrk<false, 256, 2, 4>(gt, s);
+    }
+    return GPTQ_OK;
+#endif
 }
 
 extern "C" int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* stream) {

@@ -291,3 +291,24 @@ def test_storage_bits_match_paper_figures():
         total = O.bits_per_weight(int(bits), int(group))
         got = total if what == "total" else total - int(bits)
         assert abs(got - float(value)) <= float(tol), (bits, group, got)
+
+
+def test_teacher_forcing_reproduces_own_decisions_and_isolates_a_flip():
+    W, X = _small_layer(8, 64, 300)
+    H, Hd, U, ref = _solve(W, X, bits=3, block=16)
+    # forcing the oracle with its own codes changes nothing
+    same = O.gptq_quantize(W, U, 3, block=16, teacher_codes=ref["codes"])
+    assert (same["codes"] == ref["codes"]).all() and np.array_equal(same["Q"], ref["Q"])
+    # a teacher that differs in one early code: the oracle flags exactly that column as its own different
+    # choice, follows the teacher's history afterwards, and its Q equals the teacher's codes on the grid
+    teacher = ref["codes"].copy()
+    teacher[2, 5] = teacher[2, 5] + (1 if teacher[2, 5] < 7 else -1)
+    forced = O.gptq_quantize(W, U, 3, block=16, teacher_codes=teacher)
+    assert forced["codes"][2, 5] == ref["codes"][2, 5] != teacher[2, 5]
+    assert np.array_equal(forced["Q"], O.dequant(teacher, forced["scale"], forced["zero"]))
+    assert np.allclose(W - forced["Q"], forced["E"] @ U, rtol=1e-9, atol=1e-13)   # the identity holds for any codes
+    # U given as float32 is widened exactly
+    U32 = U.astype(np.float32)
+    a = O.gptq_quantize(W, U32, 3, block=16)
+    b = O.gptq_quantize(W, U32.astype(np.float64), 3, block=16)
+    assert np.array_equal(a["codes"], b["codes"]) and np.array_equal(a["E"], b["E"])

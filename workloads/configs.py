@@ -114,3 +114,20 @@ def scaled_twin(layer: Layer, n: int, r: int | None = None, m: int | None = None
     x = layer.x
     nout = 0 if x.n_outliers == 0 else max(1, round(x.n_outliers * n / x.n))
     return replace(layer, name=layer.name + f"_twin{n}", r=r, n=n, x=replace(x, n=n, m=m, n_outliers=nout))
+
+
+def materialize(layer: Layer, device, max_elems: int = 1 << 27):
+    """(W, X) of a layer as tensors on `device`, generated tile by tile so that the generator's
+    int64 temporaries stay small (X of the largest layer is 24 GiB of fp16)."""
+    scales = layer.x.scales()
+    X = torch.empty((layer.n, layer.x.m), dtype=layer.x.dtype, device=device)
+    rows = max(1, min(layer.n, max_elems // max(layer.x.m, 1)))
+    for r0 in range(0, layer.n, rows):
+        nr = min(rows, layer.n - r0)
+        X[r0:r0 + nr] = layer.x.tile(row0=r0, nrows=nr, device=device, scales=scales)
+    W = torch.empty((layer.r, layer.n), dtype=layer.dtype, device=device)
+    rows = max(1, min(layer.r, max_elems // layer.n))
+    for r0 in range(0, layer.r, rows):
+        nr = min(rows, layer.r - r0)
+        W[r0:r0 + nr] = layer.weights(row0=r0, nrows=nr, device=device)
+    return W, X
