@@ -40,52 +40,115 @@ __global__ __launch_bounds__(1024) void damp_kernel(float* H, int64_t ld, int64_
     if (threadIdx.x == 0) *info = 0;
 }
 
-// Factor the diagonal block D = R R^T (R upper, processed from the last column backwards) and
-// invert R.  Rows/columns beyond nbk are padded with the identity.  One workgroup of 256 threads.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ---- diagonal block: D = R R^T (R upper, from the last column backwards) and R^-1, 128 x 128 -----------
+// Two levels.  A 64 x 64 block is factored and inverted by ONE wavefront entirely in registers: lane i
+// owns row i (64 registers, all indices static because the loops are unrolled), and the one value every
+// lane needs at a step -- R[k][j] -- sits in lane k and is broadcast with v_readlane.  The 128 x 128
+// block combines two of those with 64 x 64 x 64 products on the matrix cores (4 wavefronts, one 32 x 32
+// output tile each, operands read from LDS):
+//     R22 = rchol(D22), X22 = R22^-1;   R12 = D12 X22^T;   D11 -= R12 R12^T;
+//     R11 = rchol(D11), X11 = R11^-1;   X12 = -X11 (R12 X22).
+
+// C[64 x 64] = beta * C + alpha * A[64 x 64] * B, all in LDS with row pitch DP.  B is read as B[k][n] when
+// !BT and as B[n][k] when BT.  Called by all 4 wavefronts; wavefront w owns output tile (w / 2, w % 2).
+template <bool BT>
+__device__ __forceinline__ void mm64(const float* A, const float* B, float* C, float alpha, float beta, int lane, int wave) {
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int tm = (wave >> 1) * 32, tn = (wave & 1) * 32;
+    floatx16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll 8
+    for (int k = 0; k < 64; k += 2) {
+        const float a = A[(tm + l32) * DP + k + lhi];
+        const float b = BT ? B[(tn + l32) * DP + k + lhi] : B[(k + lhi) * DP + tn + l32];
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        float* c = C + (tm + 8 * (i >> 2) + 4 * lhi + (i & 3)) * DP + tn + l32;
+        *c = (beta == 0.f) ? alpha * acc[i] : beta * (*c) + alpha * acc[i];
+    }
+}
+
+// One wavefront: factor the 64 x 64 block at Dm (LDS, pitch DP; upper triangle valid) in place into R and
+// write R^-1 to Xm.  Returns the 1-based index of a non-positive pivot inside the block, or 0.
+__device__ __forceinline__ int rchol_inv64(float* Dm, float* Xm, int lane) {
+    float x[64];
+#pragma unroll
+    for (int c = 0; c < 64; ++c) x[c] = Dm[lane * DP + c];
+    int bad = 0;
+#pragma unroll
+    for (int j = 63; j >= 0; --j) {
+        float dd = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[j]), j));
+        if (!(dd > 0.f)) { bad = j + 1; dd = 1.f; }
+        const float rj = sqrtf(dd);
+        const float inv = 1.0f / rj;
+        x[j] = (lane < j) ? x[j] * inv : ((lane == j) ? rj : 0.f);
+#pragma unroll
+        for (int k = 0; k < j; ++k) {
+            const float rkj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[j]), k));
+            x[k] = fmaf(-x[j], rkj, x[k]);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 64; ++c) Dm[lane * DP + c] = x[c];
+    // X R = I, column by column: X[i][c] = (delta_ic - sum_{k<c} X[i][k] R[k][c]) / R[c][c]
+    float y[64];
+#pragma unroll
+    for (int c = 0; c < 64; ++c) {
+        float s = (lane == c) ? 1.f : 0.f;
+#pragma unroll
+        for (int k = 0; k < c; ++k) {
+            const float rkc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[c]), k));
+            s = fmaf(-y[k], rkc, s);
+        }
+        const float rcc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[c]), c));
+        y[c] = (lane <= c) ? s / rcc : 0.f;
+    }
+#pragma unroll
+    for (int c = 0; c < 64; ++c) Xm[lane * DP + c] = y[c];
+    return bad;
+}
+
+// Rows/columns beyond nbk are padded with the identity.  One workgroup of 256 threads.
 //   H block  <- R (upper part; strictly lower part of the block zeroed)
 //   dinv     <- R^-1 as a dense 128 x 128 block (zeros below the diagonal)
-__global__ __launch_bounds__(256) void diag_block_kernel(float* Hblk, int64_t ld, int nbk, float* dinv, int* info, int col_base) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void diag_block_kernel(float* Hblk, int64_t ld, int nbk, float* dinv, int* info, int col_base) {
     extern __shared__ float sm[];
-    float* D = sm;                  // [NB][DP]
-    float* Xs = sm + NB * DP;       // [NB][DP]  inverse, Xs[k][c]
-    const int tid = threadIdx.x;
+    float* D = sm;                  // [NB][DP]  D, then R
+    float* Xs = sm + NB * DP;       // [NB][DP]  R^-1
+    float* T = Xs + 64 * DP;        // scratch: the lower-left 64 x 64 block of R^-1, zeroed again at the end
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int q = tid; q < NB * NB; q += 256) {
         const int i = q / NB, k = q % NB;
         float v = (i == k) ? 1.f : 0.f;
         if (i < nbk && k < nbk) v = (k >= i) ? Hblk[(int64_t)i * ld + k] : 0.f;
         D[i * DP + k] = v;
+        Xs[i * DP + k] = 0.f;
     }
     __syncthreads();
-    for (int j = NB - 1; j >= 0; --j) {
-        float d = D[j * DP + j];
-        if (!(d > 0.f)) {
-            if (tid == 0) atomicCAS(info, 0, col_base + j + 1);
-            d = 1.f;
-        }
-        const float rjj = sqrtf(d);
-        __syncthreads();
-        if (tid < j) D[tid * DP + j] = D[tid * DP + j] / rjj;
-        if (tid == j) D[j * DP + j] = rjj;
-        __syncthreads();
-        // D[i][k] -= R[i][j] * R[k][j] for i <= k < j
-        for (int q = tid; q < j * j; q += 256) {
-            const int i = q / j, k = q % j;
-            if (i <= k) D[i * DP + k] -= D[i * DP + j] * D[k * DP + j];
-        }
-        // (the next iteration's reads are ordered by the barrier after the pivot read)
-        __syncthreads();
-    }
-    // inverse by back substitution, one column per thread: R x = e_c
-    if (tid < NB) {
-        const int c = tid;
-        for (int i = NB - 1; i > c; --i) Xs[i * DP + c] = 0.f;
-        Xs[c * DP + c] = 1.f / D[c * DP + c];
-        for (int i = c - 1; i >= 0; --i) {
-            float s = 0.f;
-            for (int k = i + 1; k <= c; ++k) s = fmaf(D[i * DP + k], Xs[k * DP + c], s);
-            Xs[i * DP + c] = -s / D[i * DP + i];
-        }
-    }
+    float* D11 = D; float* D12 = D + 64; float* D22 = D + 64 * DP + 64;
+    float* X11 = Xs; float* X12 = Xs + 64; float* X22 = Xs + 64 * DP + 64;
+    int bad = 0;
+    if (wave == 0) { bad = rchol_inv64(D22, X22, lane); if (bad) bad += 64; }
+    __syncthreads();
+    mm64<true>(D12, X22, T, 1.f, 0.f, lane, wave);              // T = D12 X22^T = R12
+    __syncthreads();
+    for (int q = tid; q < 64 * 64; q += 256) D12[(q >> 6) * DP + (q & 63)] = T[(q >> 6) * DP + (q & 63)];
+    __syncthreads();
+    mm64<true>(D12, D12, D11, -1.f, 1.f, lane, wave);           // D11 -= R12 R12^T
+    mm64<false>(D12, X22, T, 1.f, 0.f, lane, wave);             // T = R12 X22
+    __syncthreads();
+    if (wave == 0) { const int b1 = rchol_inv64(D11, X11, lane); if (b1) bad = b1; }
+    __syncthreads();
+    mm64<false>(X11, T, X12, -1.f, 0.f, lane, wave);            // X12 = -X11 (R12 X22)
+    if (tid == 0 && bad) atomicCAS(info, 0, col_base + bad);
+    __syncthreads();
+    for (int q = tid; q < 64 * 64; q += 256) T[(q >> 6) * DP + (q & 63)] = 0.f;
     __syncthreads();
     for (int q = tid; q < NB * NB; q += 256) {
         const int i = q / NB, k = q % NB;
