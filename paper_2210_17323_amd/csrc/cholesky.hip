@@ -263,6 +263,12 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
         }
     }
 
+    // The triangular GEMMs below skip the K range left of a tile's first row and rely on zeros below the
+    // diagonal inside the tile's own rows, so clear the strictly lower triangle first (it holds the input's
+    // lower half and the below-diagonal parts of straddling update tiles); nothing writes there afterwards.
+    hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
+    GPTQ_LAUNCH_CHECK();
+
     // ---- U = R^-1 in place, one outer block column at a time (left to right):
     //      invert the 512 x 512 diagonal block in place with rank-128 steps, then
     //      U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1), a long-K GEMM against the finished part.
@@ -302,8 +308,6 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
             if (rc) return rc;
         }
     }
-    hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
-    GPTQ_LAUNCH_CHECK();
     return GPTQ_OK;
 }
 

@@ -210,6 +210,141 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) voi
     else          gemm_tile<B_IS_NK, true>(g, m0, n0, As, Bs);
 }
 
+// ---- large-tile variant: 256 x 128 tile, operands copied global -> LDS directly, 4 stages ---------------
+// Used when M % 256 == 0, N % 128 == 0 and K % 64 == 0.  8 wavefronts, each 64 x 64 = 2 x 2 MFMA tiles.
+// A stage holds 16 values of K: the A panel as [256 rows][16 floats] and, for B given as [N x K], the B
+// panel as [128 rows][16 floats]; rows are 64 bytes = 4 chunks of 16 bytes, and global_load_lds_dwordx4
+// lays 16 such rows down per instruction with the chunk index XOR-swizzled by (row / 2) % 4 on the global
+// side, so that a ds_read_b128 of one chunk by 32 consecutive rows is bank-conflict free.  One 16-byte
+// read hands a lane four consecutive k of its row; the half-wavefront h uses chunk 2q+h, and the four
+// MFMAs of an octet q consume element i = 0..3 of those reads -- the MFMA's k pairing becomes
+// (8q+i, 8q+4+i), the same for A and B, which is all a dot product needs.  For B given as [K x N] the
+// stage holds [16 k][128 n] linearly and the matching values are read with ds_read_b32.
+// While step k is multiplied the copies of steps k+1..k+3 are in flight; one bare s_barrier per step.
+constexpr int LM = 256, LN = 128, LK = 16;
+constexpr int LA_BYTES = LM * LK * 4, LB_BYTES = LN * LK * 4, LSTAGE = LA_BYTES + LB_BYTES;
+
+template <bool B_IS_NK>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_f32_dma_kernel(GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) unsigned char st0[LSTAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char st1[LSTAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char st2[LSTAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char st3[LSTAGE];
+
+    const int64_t w = blockIdx.x;
+    const int64_t tile = (g.upper_only || g.a_upper_tri) ? w : (w % NXCD) * g.per_xcd + (w / NXCD);
+    if (tile >= g.total) return;
+    const int64_t per_group = (int64_t)GROUP_M * g.tiles_n;
+    const int64_t grp = tile / per_group, rem = tile % per_group;
+    const int rows_in_group = min(GROUP_M, g.tiles_m - (int)grp * GROUP_M);
+    const int64_t m0 = (grp * GROUP_M + rem % rows_in_group) * LM, n0 = (rem / rows_in_group) * LN;
+    if (g.upper_only && g.crow0 + m0 > g.ccol0 + n0 + (LN - 1)) return;
+
+    // 8 wavefronts (two per SIMD, so one can issue MFMAs while the other waits on LDS or the barrier);
+    // wavefront (wm, wn) owns rows wm*64.., columns wn*64.. of the tile: 2 x 2 MFMA tiles.
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // copies: A panel = 16 instructions of 16 rows (2 per wavefront); B panel = 8 instructions (1 per wavefront)
+    const int crow = lane >> 2, cchunk = (lane & 3) ^ ((lane >> 3) & 3);
+    const float* srcA = g.A + (m0 + wave * 32 + crow) * g.lda + cchunk * 4;              // + i*16 rows, + k0
+    const float* srcB = B_IS_NK ? g.B + (n0 + wave * 16 + crow) * g.ldb + cchunk * 4       // + k0
+                                : g.B + (int64_t)(wave * 2 + lhi) * g.ldb + n0 + l32 * 4;   // + k0*ldb
+    auto issue_copies = [&](unsigned char* stage, int64_t k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcA + (int64_t)i * 16 * g.lda + k0),
+                                             (__attribute__((address_space(3))) void*)(stage + (wave * 2 + i) * 1024), 16, 0, 0);
+        const float* sb = B_IS_NK ? srcB + k0 : srcB + k0 * g.ldb;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sb,
+                                         (__attribute__((address_space(3))) void*)(stage + LA_BYTES + wave * 1024), 16, 0, 0);
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[s][t][i] = 0.f;
+
+    const int rowA = (wm * 64 + l32) * 64;                       // + s * 2048
+    const int rowB = LA_BYTES + (wn * 64 + l32) * 64;            // NK: + t * 2048
+    const int swz = (l32 >> 1) & 3;
+    const int colB = LA_BYTES + (wn * 64 + l32) * 4;             // KN: + t * 128 + krow * 512
+    auto multiply = [&](const unsigned char* cur) {
+        float4 a[2][2];
+        float bv[2][2][4];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int co = ((2 * q + lhi) ^ swz) << 4;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) a[q][s] = *reinterpret_cast<const float4*>(cur + rowA + s * 2048 + co);
+            if (B_IS_NK) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const float4 b4 = *reinterpret_cast<const float4*>(cur + rowB + t * 2048 + co);
+                    bv[q][t][0] = b4.x; bv[q][t][1] = b4.y; bv[q][t][2] = b4.z; bv[q][t][3] = b4.w;
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        bv[q][t][i] = *reinterpret_cast<const float*>(cur + colB + t * 128 + (8 * q + 4 * lhi + i) * 512);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const float av = i == 0 ? a[q][s].x : (i == 1 ? a[q][s].y : (i == 2 ? a[q][s].z : a[q][s].w));
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+                        acc[s][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[q][t][i], acc[s][t], 0, 0, 0);
+                }
+    };
+    // 3 copies per wavefront per step; vmcnt(6): only the copies of the two later steps may be outstanding.
+    const int64_t ks0 = g.a_upper_tri ? m0 / LK : 0;             // A upper triangular: nothing left of the tile's rows
+    const int64_t kend = g.K;
+    auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur) {
+        __builtin_amdgcn_s_waitcnt(0x0F76);                     // vmcnt(6)
+        asm volatile("s_barrier" ::: "memory");
+        issue_copies(refill, min(k_refill, kend - LK));
+        multiply(cur);
+    };
+    issue_copies(st0, ks0 * LK);
+    issue_copies(st1, (ks0 + 1) * LK);
+    issue_copies(st2, (ks0 + 2) * LK);
+    for (int64_t k = ks0 * LK; k < kend; k += 4 * LK) {
+        next_stage(st3, k + 3 * LK, st0);
+        next_stage(st0, k + 4 * LK, st1);
+        next_stage(st1, k + 5 * LK, st2);
+        next_stage(st2, k + 6 * LK, st3);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                         // drain the surplus copies before LDS is released
+
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            float* cbase = g.C + (m0 + wm * 64 + s * 32 + 4 * lhi) * g.ldc + n0 + wn * 64 + t * 32 + l32;
+            float cv[16];
+            if (!g.overwrite) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) cv[i] = cbase[(int64_t)(8 * (i >> 2) + (i & 3)) * g.ldc];
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float v = g.alpha * acc[s][t][i];
+                cbase[(int64_t)(8 * (i >> 2) + (i & 3)) * g.ldc] = g.overwrite ? v : (cv[i] + v);
+            }
+        }
+}
+
 int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
     if (p.M <= 0 || p.N <= 0) return GPTQ_OK;
     if (!aligned(p.A, 16) || !aligned(p.B, 16) || (p.lda % 4) || (p.ldb % 4))
@@ -219,14 +354,20 @@ int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
     g.M = p.M; g.N = p.N; g.K = p.K < 0 ? 0 : p.K; g.alpha = p.alpha;
     g.overwrite = p.overwrite; g.upper_only = p.upper_only; g.crow0 = p.crow0; g.ccol0 = p.ccol0;
     g.a_upper_tri = p.a_upper_tri;
-    const int64_t tm = ceil_div(p.M, TM), tn = ceil_div(p.N, TN);
+    const bool large = (p.M % LM == 0) && (p.N % LN == 0) && (g.K % (4 * LK) == 0) && g.K > 0 && aligned(p.C, 4);
+    const int64_t tm = large ? p.M / LM : ceil_div(p.M, TM), tn = large ? p.N / LN : ceil_div(p.N, TN);
     if (tm * tn > 0x7ffffff0LL) return fail(GPTQ_ERR_UNSUPPORTED, "gemm_f32: too many tiles");
     g.tiles_m = (int)tm; g.tiles_n = (int)tn;
     g.total = tm * tn;
     g.per_xcd = ceil_div(g.total, NXCD);
     dim3 grid((unsigned)(g.per_xcd * NXCD));
-    if (p.b_is_nk) hipLaunchKernelGGL(gemm_f32_kernel<true>, grid, dim3(256), 0, s, g);
-    else           hipLaunchKernelGGL(gemm_f32_kernel<false>, grid, dim3(256), 0, s, g);
+    if (large) {
+        if (p.b_is_nk) hipLaunchKernelGGL(gemm_f32_dma_kernel<true>, grid, dim3(512), 0, s, g);
+        else           hipLaunchKernelGGL(gemm_f32_dma_kernel<false>, grid, dim3(512), 0, s, g);
+    } else {
+        if (p.b_is_nk) hipLaunchKernelGGL(gemm_f32_kernel<true>, grid, dim3(256), 0, s, g);
+        else           hipLaunchKernelGGL(gemm_f32_kernel<false>, grid, dim3(256), 0, s, g);
+    }
     GPTQ_LAUNCH_CHECK();
     return GPTQ_OK;
 }
