@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--tokens", type=int, default=0, help="calibration tokens (default: the layer's own, 262144)")
     ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptq_hessian_accumulate call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="before the timed region, run one plain 1 GiB device-to-device copy (a kernel of known "
+                         "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
     return ap.parse_args()
 
 
@@ -122,6 +125,8 @@ def main():
     grid = g.GPTQ_GRID_TERNARY if lay.grid == "ternary" else g.GPTQ_GRID_MINMAX
     chunk = min(a.chunk, m)
     chunks = [(c0, min(c0 + chunk, m)) for c0 in range(0, m, chunk)]
+    h_bytes = g.gptq_hessian_accumulate_workspace_bytes(n, chunk, lay.x.dtype)
+    h_ws = torch.empty(h_bytes, dtype=torch.uint8, device=dev) if h_bytes else None
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     syrk_events, phase_events = [], []
@@ -133,7 +138,7 @@ def main():
         for (c0, c1) in chunks:
             if record:
                 e0, e1 = ev(), ev(); e0.record()
-            g.gptq_hessian_accumulate(H, X[:, c0:c1])
+            g.gptq_hessian_accumulate(H, X[:, c0:c1], h_ws)
             if record:
                 e1.record(); syrk_events.append((e0, e1, c1 - c0))
         if record: marks[1].record()
@@ -145,6 +150,12 @@ def main():
         if record:
             marks[4].record(); phase_events.append(marks)
 
+    if a.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step(False)
     torch.cuda.synchronize()

@@ -56,11 +56,17 @@ GPTQ_API const char* gptq_last_error(void);
  *       (GPTQ_F16 / GPTQ_BF16: products are exact in float32 and accumulated in float32 by the
  *       matrix cores; GPTQ_F32: float32 matrix-core products).
  *       X must be 16-byte aligned and ldx a multiple of 8 (f16/bf16) or 4 (f32) elements.
+ *   ws  optional workspace (may be NULL) of gptq_hessian_accumulate_workspace_bytes(n, t, xdtype) bytes,
+ *       256-byte aligned.  With it, large 16-bit chunks are first repacked so that every 256-channel x
+ *       32-token panel step is one contiguous 16 KB block, which the matrix-core kernel copies with far
+ *       better cache-line and DRAM-page locality; without it the kernel reads X in place (same result bit
+ *       for bit, lower speed).  The size is 0 where the repack is not used.
  *   No normalisation by the token count is applied (the quantization result is invariant to the
  *   scale of H).  n == 0 or t == 0 is a valid no-op.
  */
+GPTQ_API size_t gptq_hessian_accumulate_workspace_bytes(int64_t n, int64_t t, int xdtype);
 GPTQ_API int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int xdtype,
-                            int64_t n, int64_t t, int64_t ldx, void* stream);
+                            int64_t n, int64_t t, int64_t ldx, void* ws, size_t ws_bytes, void* stream);
 
 /* Copies the upper triangle of H onto the lower one (H[j][i] = H[i][j] for j > i). */
 GPTQ_API int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* stream);

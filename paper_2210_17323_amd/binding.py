@@ -45,7 +45,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     i64, vp, ci, sz, f32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
     L.gptq_version.restype = ci
     L.gptq_last_error.restype = ctypes.c_char_p
-    L.gptq_hessian_accumulate.argtypes = [vp, i64, vp, ci, i64, i64, i64, vp]
+    L.gptq_hessian_accumulate.argtypes = [vp, i64, vp, ci, i64, i64, i64, vp, sz, vp]
+    L.gptq_hessian_accumulate_workspace_bytes.argtypes = [i64, i64, ci]
+    L.gptq_hessian_accumulate_workspace_bytes.restype = sz
     L.gptq_hessian_symmetrize.argtypes = [vp, i64, i64, vp]
     L.gptq_damp_cholesky_inverse_workspace_bytes.argtypes = [i64]
     L.gptq_damp_cholesky_inverse_workspace_bytes.restype = sz
@@ -102,14 +104,21 @@ def packed_words_per_row(n: int, bits: int) -> int:
     return (n * bits + 31) // 32
 
 
-def gptq_hessian_accumulate(H: torch.Tensor, X: torch.Tensor) -> None:
-    """H[upper] += 2 X X^T for one chunk X [n x t] (tokens contiguous)."""
+def gptq_hessian_accumulate_workspace_bytes(n: int, t: int, dtype: torch.dtype = torch.float16) -> int:
+    return lib().gptq_hessian_accumulate_workspace_bytes(n, t, _DTYPE[dtype])
+
+
+def gptq_hessian_accumulate(H: torch.Tensor, X: torch.Tensor, ws: torch.Tensor | None = None) -> None:
+    """H[upper] += 2 X X^T for one chunk X [n x t] (tokens contiguous); ws: optional uint8 workspace."""
     _dev2d(H, "H", (torch.float32,))
     _dev2d(X, "X", tuple(_DTYPE))
     n, t = X.shape
     if H.shape != (n, n):
         raise ValueError("H must be n x n")
-    _check(lib().gptq_hessian_accumulate(_ptr(H), _ld(H), _ptr(X), _DTYPE[X.dtype], n, t, _ld(X), _stream()))
+    if ws is not None and (ws.dtype != torch.uint8 or not ws.is_cuda):
+        raise ValueError("ws must be a GPU uint8 tensor")
+    _check(lib().gptq_hessian_accumulate(_ptr(H), _ld(H), _ptr(X), _DTYPE[X.dtype], n, t, _ld(X),
+                                         _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
 
 
 def gptq_hessian_symmetrize(H: torch.Tensor) -> None:

@@ -34,6 +34,8 @@ struct SyrkArgs {
     int nt;                     // tiles per side
     int64_t total;              // enumerated tile slots (including skipped ones in diagonal patches)
     int64_t per_xcd;
+    const unsigned char* Xb;    // repacked copy of the chunk (see repack_kernel), or null: copy straight from X
+    int64_t nsteps;             // 32-token steps in the repacked chunk
 };
 
 template <bool IS_BF16>
@@ -176,6 +178,32 @@ __global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
         }
 }
 
+// ---- repack of one token chunk into the order the SYRK kernel consumes it -----------------------------
+// In X a panel step (256 channels x 32 tokens) is 256 pieces of 64 bytes that lie a whole row apart: every
+// piece is its own half cache line, its own DRAM page.  The repacked chunk stores each panel step as one
+// contiguous 16 KB block, [panel][step][256 rows][64 bytes], with the 16-byte chunks of a row already in
+// their swizzled LDS positions, so a workgroup's copy of a panel step is 16 linear 1 KB transfers.
+// Channels past n are zero rows.  Cost: one read and one write of the chunk per call, ~1-2 % of the SYRK.
+__global__ __launch_bounds__(256) void repack_kernel(const uint16_t* X, int64_t ldx, int64_t n, int64_t nsteps, unsigned char* Xb) {
+    // a workgroup takes 16 rows x 512 tokens: it reads 1 KB runs of each row and writes 1 KB runs of 16 blocks
+    const int64_t rg = blockIdx.x;                       // row group of 16
+    const int64_t tg = blockIdx.y;                       // token group of 512 (16 steps)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = threadIdx.x + 256 * i;
+        const int rr = q >> 6, c64 = q & 63;             // row in group, 16-byte chunk in the 1 KB run
+        const int64_t row = rg * 16 + rr;
+        const int64_t step = tg * 16 + (c64 >> 2);
+        if (step >= nsteps) continue;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row < n) v = *reinterpret_cast<const uint4*>(X + row * ldx + step * 32 + (c64 & 3) * 8);
+        const int64_t panel = row >> 8;
+        const int r = (int)(row & 255);
+        const int pos = (c64 & 3) ^ ((r >> 1) & 3);
+        *reinterpret_cast<uint4*>(Xb + (panel * nsteps + step) * 16384 + r * 64 + pos * 16) = v;
+    }
+}
+
 // ---- 256 x 256 tile, 4 wavefronts of 128 x 128, panels copied global -> LDS directly ----------------
 // Each wavefront keeps a 4 x 4 grid of 32x32 accumulators (256 registers), which halves the LDS reads
 // per MFMA compared with 128 x 64 wavefront tiles.  The two panels of a 32-token step (2 x 16 KB) go
@@ -188,7 +216,7 @@ __global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
 constexpr int DK = 32;                                  // tokens per stage
 constexpr int DSTAGE = 2 * 256 * DK * 2;                // bytes per stage: A panel + B panel
 
-template <bool IS_BF16>
+template <bool IS_BF16, bool BLOCKED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void syrk_f16_dma_kernel(SyrkArgs g) {
     constexpr int BT = 256;
     constexpr int PANEL = BT * DK * 2;                  // 16 KB
@@ -200,7 +228,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __shared__ __attribute__((aligned(16))) unsigned char stage3[DSTAGE];
 
     const int64_t w = blockIdx.x;
-    int64_t L = (w % NXCD) * g.per_xcd + (w / NXCD);
+    // Workgroup w runs on XCD w % 8.  A patch = 32 consecutive tile slots (~4 x 8 tiles of one strip) goes to
+    // one XCD so that its 32 CUs share the patch's panels in that XCD's L2; consecutive patches go to
+    // consecutive XCDs, so at any time the 8 XCDs work on neighbouring row groups of the same strip and find
+    // each other's column panels in the memory-side cache instead of HBM.
+    const int64_t xcd = w % NXCD, slot = w / NXCD;
+    int64_t L = ((slot / 32) * NXCD + xcd) * 32 + (slot % 32);
     if (L >= g.total) return;
     int bi, bj;
     {
@@ -224,8 +257,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // (lane%4) ^ ((lane/8)%4).  Rows past n are clamped: they only feed outputs that are never stored.
     const int lrow = lane >> 2, lchunk = (lane & 3) ^ ((lane >> 3) & 3);
     const uint16_t* xcol = g.X + lchunk * 8;
+    const unsigned char* blkA = BLOCKED ? g.Xb + (int64_t)bi * g.nsteps * 16384 + wave * 4096 + lane * 16 : nullptr;
+    const unsigned char* blkB = BLOCKED ? g.Xb + (int64_t)bj * g.nsteps * 16384 + wave * 4096 + lane * 16 : nullptr;
     auto issue_copies = [&](unsigned char* stage, int64_t k0) {
         unsigned char* base = stage + wave * 4 * 1024;
+        if (BLOCKED) {
+            const int64_t off = (k0 / DK) * 16384;     // this step's block inside the panel
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blkA + off + i * 1024),
+                                                 (__attribute__((address_space(3))) void*)(base + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blkB + off + i * 1024),
+                                                 (__attribute__((address_space(3))) void*)(base + PANEL + i * 1024), 16, 0, 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = (wave * 4 + i) * 16 + lrow;
@@ -330,12 +376,23 @@ static void syrk_schedule(SyrkArgs& g, int BT) {
 }
 
 template <bool IS_BF16>
-static int launch_syrk_dma(SyrkArgs g, hipStream_t s) {
+static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s) {
     syrk_schedule(g, 256);
+    g.per_xcd = ceil_div(ceil_div(g.total, 32), NXCD) * 32;      // whole patches of 32 slots per XCD
     const int64_t blocks = g.per_xcd * NXCD;
     if (blocks > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
-    auto kern = syrk_f16_dma_kernel<IS_BF16>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, s, g);
+    g.nsteps = g.t / DK;
+    g.Xb = static_cast<const unsigned char*>(ws);
+    if (ws) {
+        const int64_t rgroups = (int64_t)g.nt * 16, tgroups = ceil_div(g.nsteps, 16);
+        if (tgroups > 65535) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: chunk too long for the repack grid (split the call)");
+        hipLaunchKernelGGL(repack_kernel, dim3((unsigned)rgroups, (unsigned)tgroups), dim3(256), 0, s, g.X, g.ldx, g.n, g.nsteps,
+                           static_cast<unsigned char*>(ws));
+        GPTQ_LAUNCH_CHECK();
+        hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, true>), dim3((unsigned)blocks), dim3(256), 0, s, g);
+    } else {
+        hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, false>), dim3((unsigned)blocks), dim3(256), 0, s, g);
+    }
     GPTQ_LAUNCH_CHECK();
     return GPTQ_OK;
 }
@@ -379,8 +436,18 @@ __global__ __launch_bounds__(256) void symmetrize_kernel(float* H, int64_t ld, i
 
 using namespace gptq;
 
+static size_t syrk_ws_bytes(int64_t n, int64_t t, int xdtype) {
+    if (xdtype == GPTQ_F32 || n <= 6144 || t < 2 * HK) return 0;
+    return (size_t)ceil_div(n, 256) * 256 * (size_t)(t / (2 * HK) * (2 * HK)) * 2;
+}
+
+extern "C" size_t gptq_hessian_accumulate_workspace_bytes(int64_t n, int64_t t, int xdtype) {
+    if (n <= 0 || t <= 0) return 0;
+    return syrk_ws_bytes(n, t, xdtype);
+}
+
 extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int xdtype,
-                                       int64_t n, int64_t t, int64_t ldx, void* stream) {
+                                       int64_t n, int64_t t, int64_t ldx, void* ws, size_t ws_bytes, void* stream) {
     if (n < 0 || t < 0) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: negative size");
     if (n == 0 || t == 0) return GPTQ_OK;
     if (!H || !X) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate: null pointer");
@@ -413,7 +480,10 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
     if (t_main > 0) {
         SyrkArgs gm = g;
         gm.t = t_main;
-        const int rc = bf ? launch_syrk_dma<true>(gm, s) : launch_syrk_dma<false>(gm, s);
+        // with a workspace the chunk is first repacked into contiguous panel steps (much better DRAM and
+        // cache-line locality for the copies); without one the kernel copies straight from X
+        void* wsp = (ws && aligned(ws, 256) && ws_bytes >= syrk_ws_bytes(n, t, xdtype)) ? ws : nullptr;
+        const int rc = bf ? launch_syrk_dma<true>(gm, wsp, s) : launch_syrk_dma<false>(gm, wsp, s);
         if (rc) return rc;
     }
     if (t_main < t) {

@@ -25,12 +25,12 @@ def new_hessian(n: int, device="cuda") -> torch.Tensor:
 
 def accumulate(H: torch.Tensor, X: torch.Tensor, chunk: int | None = None) -> None:
     """H += 2 X X^T, optionally walking the token axis in chunks (multiples of 8 tokens)."""
-    t = X.shape[1]
-    if chunk is None or chunk >= t:
-        B.gptq_hessian_accumulate(H, X)
-        return
-    for c0 in range(0, t, chunk):
-        B.gptq_hessian_accumulate(H, X[:, c0:min(c0 + chunk, t)])
+    n, t = X.shape
+    step = t if chunk is None or chunk >= t else chunk
+    nbytes = B.gptq_hessian_accumulate_workspace_bytes(n, step, X.dtype)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=X.device) if nbytes else None
+    for c0 in range(0, t, step):
+        B.gptq_hessian_accumulate(H, X[:, c0:min(c0 + step, t)], ws)
 
 
 def cholesky_inverse(H: torch.Tensor, percdamp: float = 0.01, check: bool = True) -> torch.Tensor:

@@ -68,6 +68,14 @@ def test_hessian_matches_oracle(case):
     _say(f"  n={n} t={X.shape[1]} rel_fro={err:.3e}")
     assert err <= 1e-5
     assert np.array_equal(got, got.T)
+    # the repacked-workspace path must give the same bits as the in-place path
+    nbytes = g.gptq_hessian_accumulate_workspace_bytes(n, X.shape[1], X.dtype)
+    if nbytes:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        H2 = _padded(n, n, torch.float32, 4)
+        g.gptq_hessian_accumulate(H2, X, ws)
+        g.gptq_hessian_symmetrize(H2)
+        assert torch.equal(H2, H)
 
 
 def test_hessian_exact_on_small_integers_and_chunked():

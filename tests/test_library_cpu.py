@@ -23,6 +23,8 @@ def test_workspace_sizes():
     big = g.gptq_quantize_layer_workspace_bytes(12288, 49152)
     assert 12288 * 49152 * 4 < big < 12288 * 49152 * 4 * 1.01 + (1 << 24)
     assert g.gptq_quantize_layer_workspace_bytes(0, 0) > 0
+    assert g.gptq_hessian_accumulate_workspace_bytes(49152, 32768) == 49152 * 32768 * 2
+    assert g.gptq_hessian_accumulate_workspace_bytes(4096, 32768) == 0
 
 
 def _err():
@@ -32,13 +34,13 @@ def _err():
 def test_argument_validation_happens_on_the_host():
     L = g.lib()
     one = ctypes.c_void_p(256)       # never dereferenced: every call below must fail validation first
-    assert L.gptq_hessian_accumulate(one, 8, one, 0, -1, 8, 8, None) == INVALID
-    assert L.gptq_hessian_accumulate(None, 8, one, 0, 8, 8, 8, None) == INVALID
-    assert L.gptq_hessian_accumulate(one, 4, one, 0, 8, 8, 8, None) == INVALID          # ldh < n
-    assert L.gptq_hessian_accumulate(one, 8, one, 7, 8, 8, 8, None) == INVALID          # dtype
-    assert L.gptq_hessian_accumulate(one, 8, one, 0, 8, 12, 12, None) == INVALID        # ldx % 8
+    assert L.gptq_hessian_accumulate(one, 8, one, 0, -1, 8, 8, None, 0, None) == INVALID
+    assert L.gptq_hessian_accumulate(None, 8, one, 0, 8, 8, 8, None, 0, None) == INVALID
+    assert L.gptq_hessian_accumulate(one, 4, one, 0, 8, 8, 8, None, 0, None) == INVALID          # ldh < n
+    assert L.gptq_hessian_accumulate(one, 8, one, 7, 8, 8, 8, None, 0, None) == INVALID          # dtype
+    assert L.gptq_hessian_accumulate(one, 8, one, 0, 8, 12, 12, None, 0, None) == INVALID        # ldx % 8
     assert "ldx" in _err()
-    assert L.gptq_hessian_accumulate(one, 8, one, 0, 0, 8, 8, None) == OK               # empty is a no-op
+    assert L.gptq_hessian_accumulate(one, 8, one, 0, 0, 8, 8, None, 0, None) == OK               # empty is a no-op
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, -0.5, one, 1 << 30, one, None) == INVALID
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, one, 16, one, None) == WORKSPACE
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, None, 0, one, None) == WORKSPACE
