@@ -23,10 +23,6 @@ constexpr int HK = 64;          // token step (halves)
 constexpr int STRIP = 8;        // tile columns per strip
 constexpr int NXCD = 8;
 
-#ifndef GPTQ_SYRK_VARIANT
-#define GPTQ_SYRK_VARIANT 2      // 1: register-staged 8-wavefront kernel; 2: direct-to-LDS 4-wavefront kernel
-#endif
-
 struct SyrkArgs {
     float* H; int64_t ldh;
     const uint16_t* X; int64_t ldx;
@@ -183,8 +179,9 @@ __global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
 // piece is its own half cache line, its own DRAM page.  The repacked chunk stores each panel step as one
 // contiguous 16 KB block, [panel][step][256 rows][64 bytes], with the 16-byte chunks of a row already in
 // their swizzled LDS positions, so a workgroup's copy of a panel step is 16 linear 1 KB transfers.
-// Channels past n are zero rows.  Cost: one read and one write of the chunk per call, ~1-2 % of the SYRK.
-__global__ __launch_bounds__(256) void repack_kernel(const uint16_t* X, int64_t ldx, int64_t n, int64_t nsteps, unsigned char* Xb) {
+// Channels past n and tokens past t are zeros (the step count is padded to what the kernel's loop needs).
+// Cost: one read and one write of the chunk per call, ~1-2 % of the SYRK.
+__global__ __launch_bounds__(256) void repack_kernel(const uint16_t* X, int64_t ldx, int64_t n, int64_t t, int64_t nsteps, unsigned char* Xb) {
     // a workgroup takes 16 rows x 512 tokens: it reads 1 KB runs of each row and writes 1 KB runs of 16 blocks
     const int64_t rg = blockIdx.x;                       // row group of 16
     const int64_t tg = blockIdx.y;                       // token group of 512 (16 steps)
@@ -196,7 +193,8 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint16_t* X, int64_t 
         const int64_t step = tg * 16 + (c64 >> 2);
         if (step >= nsteps) continue;
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (row < n) v = *reinterpret_cast<const uint4*>(X + row * ldx + step * 32 + (c64 & 3) * 8);
+        const int64_t tok = step * 32 + (c64 & 3) * 8;
+        if (row < n) v = load8h_guard(X + row * ldx + tok, t - tok);     // zeros past the last token
         const int64_t panel = row >> 8;
         const int r = (int)(row & 255);
         const int pos = (c64 & 3) ^ ((r >> 1) & 3);
@@ -210,11 +208,12 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint16_t* X, int64_t 
 // straight from global memory into LDS with global_load_lds_dwordx4 (no staging registers, no
 // ds_write): one such instruction moves 16 rows x 64 bytes and lays the 64 lanes down linearly in LDS,
 // so the XOR swizzle of the 16-byte chunks is applied on the global side (lane l fetches chunk
-// (l % 4) ^ ((l / 8) % 4) of row l / 4).  Four stages: while step k is multiplied the copies of steps
-// k+1 .. k+3 are in flight, which is what hides the memory latency with one wavefront per SIMD; one
-// barrier per step.  Requires t % 128 == 0 (the caller splits off the tail).
+// (l % 4) ^ ((l / 8) % 4) of row l / 4).  Five stages (all 160 KB of LDS): while step k is multiplied the
+// copies of steps k+1 .. k+4 are in flight, which is what hides the memory latency with one wavefront per SIMD; one
+// barrier per step.  Requires t % 160 == 0 (the caller splits off the tail).
 constexpr int DK = 32;                                  // tokens per stage
 constexpr int DSTAGE = 2 * 256 * DK * 2;                // bytes per stage: A panel + B panel
+constexpr int DMA_TOKENS = 5 * DK;                      // tokens per trip of the 5-stage loop
 
 template <bool IS_BF16, bool BLOCKED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void syrk_f16_dma_kernel(SyrkArgs g) {
@@ -226,6 +225,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __shared__ __attribute__((aligned(16))) unsigned char stage1[DSTAGE];
     __shared__ __attribute__((aligned(16))) unsigned char stage2[DSTAGE];
     __shared__ __attribute__((aligned(16))) unsigned char stage3[DSTAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char stage4[DSTAGE];      // 5 x 32 KB: all 160 KB of LDS
 
     const int64_t w = blockIdx.x;
     // Workgroup w runs on XCD w % 8.  A patch = 32 consecutive tile slots (~4 x 8 tiles of one strip) goes to
@@ -326,41 +326,55 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
     // A bare s_barrier: __syncthreads() would also drain every outstanding copy (it fences all memory),
     // which is exactly what the multi-stage pipeline must not do.  Visibility of a stage is established by
-    // each wavefront waiting for its own copies of that step -- vmcnt(16): only the 2 x 8 copies of the two
-    // later steps may still be in flight -- before it arrives at the barrier.
+    // each wavefront waiting for its own copies of that step -- vmcnt(24): only the 3 x 8 copies of the
+    // three later steps may still be in flight -- before it arrives at the barrier.
     // The loop body is branch-free: past the last step the copies simply re-read the last 32 tokens into
-    // a stage nobody multiplies again, so every wait is the same vmcnt(16).
+    // a stage nobody multiplies again, so every wait is the same vmcnt(24).
     auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur) {
-        __builtin_amdgcn_s_waitcnt(0x4F70);             // vmcnt(16)
+        __builtin_amdgcn_s_waitcnt(0x4F78);             // vmcnt(24)
         asm volatile("s_barrier" ::: "memory");         // everybody's copies of this step landed; everybody left `refill`
         issue_copies(refill, min(k_refill, g.t - DK));
         multiply(cur);
     };
-    const int64_t ksteps = g.t / DK;                    // a multiple of 4 (the caller passes t % 128 == 0)
+    const int64_t ksteps = g.t / DK;                    // a multiple of 5 (the caller passes t % 160 == 0)
     issue_copies(stage0, 0);
     issue_copies(stage1, DK);
     issue_copies(stage2, 2 * DK);
-    for (int64_t ks = 0; ks < ksteps; ks += 4) {
-        next_stage(stage3, (ks + 3) * DK, stage0);
-        next_stage(stage0, (ks + 4) * DK, stage1);
-        next_stage(stage1, (ks + 5) * DK, stage2);
-        next_stage(stage2, (ks + 6) * DK, stage3);
+    issue_copies(stage3, 3 * DK);
+    for (int64_t ks = 0; ks < ksteps; ks += 5) {
+        next_stage(stage4, (ks + 4) * DK, stage0);
+        next_stage(stage0, (ks + 5) * DK, stage1);
+        next_stage(stage1, (ks + 6) * DK, stage2);
+        next_stage(stage2, (ks + 7) * DK, stage3);
+        next_stage(stage3, (ks + 8) * DK, stage4);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                 // drain the dummy copies before the LDS is released
 
-    // ---- H += 2 * acc
+    // ---- H += 2 * acc.  Inside the matrix the 16 values of an MFMA tile are read before any is written, so
+    // the loads overlap instead of each waiting for its own round trip.
+    const bool inside = (r0 + BT <= g.n) && (c0 + BT <= g.n);
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int64_t col = c0 + wn * 128 + u * 32 + l32;
-            if (col >= g.n) continue;
+            const int64_t rbase = r0 + wm * 128 + s * 32 + 4 * lhi;
+            if (inside) {
+                float* hb = g.H + rbase * g.ldh + col;
+                float hv[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int64_t row = r0 + wm * 128 + s * 32 + 8 * (i >> 2) + 4 * lhi + (i & 3);
-                if (row < g.n) {
-                    float* h = g.H + row * g.ldh + col;
-                    *h += 2.0f * acc[s][u][i];
+                for (int i = 0; i < 16; ++i) hv[i] = hb[(int64_t)(8 * (i >> 2) + (i & 3)) * g.ldh];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) hb[(int64_t)(8 * (i >> 2) + (i & 3)) * g.ldh] = hv[i] + 2.0f * acc[s][u][i];
+            } else {
+                if (col >= g.n) continue;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int64_t row = rbase + 8 * (i >> 2) + (i & 3);
+                    if (row < g.n) {
+                        float* h = g.H + row * g.ldh + col;
+                        *h += 2.0f * acc[s][u][i];
+                    }
                 }
             }
         }
@@ -381,16 +395,18 @@ static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s) {
     g.per_xcd = ceil_div(ceil_div(g.total, 32), NXCD) * 32;      // whole patches of 32 slots per XCD
     const int64_t blocks = g.per_xcd * NXCD;
     if (blocks > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
-    g.nsteps = g.t / DK;
     g.Xb = static_cast<const unsigned char*>(ws);
     if (ws) {
+        g.nsteps = ceil_div(ceil_div(g.t, DK), 5) * 5;           // zero-padded to whole trips of the 5-stage loop
         const int64_t rgroups = (int64_t)g.nt * 16, tgroups = ceil_div(g.nsteps, 16);
         if (tgroups > 65535) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: chunk too long for the repack grid (split the call)");
-        hipLaunchKernelGGL(repack_kernel, dim3((unsigned)rgroups, (unsigned)tgroups), dim3(256), 0, s, g.X, g.ldx, g.n, g.nsteps,
+        hipLaunchKernelGGL(repack_kernel, dim3((unsigned)rgroups, (unsigned)tgroups), dim3(256), 0, s, g.X, g.ldx, g.n, g.t, g.nsteps,
                            static_cast<unsigned char*>(ws));
         GPTQ_LAUNCH_CHECK();
+        g.t = g.nsteps * DK;
         hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, true>), dim3((unsigned)blocks), dim3(256), 0, s, g);
     } else {
+        g.nsteps = g.t / DK;
         hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, false>), dim3((unsigned)blocks), dim3(256), 0, s, g);
     }
     GPTQ_LAUNCH_CHECK();
@@ -437,8 +453,8 @@ __global__ __launch_bounds__(256) void symmetrize_kernel(float* H, int64_t ld, i
 using namespace gptq;
 
 static size_t syrk_ws_bytes(int64_t n, int64_t t, int xdtype) {
-    if (xdtype == GPTQ_F32 || n <= 6144 || t < 2 * HK) return 0;
-    return (size_t)ceil_div(n, 256) * 256 * (size_t)(t / (2 * HK) * (2 * HK)) * 2;
+    if (xdtype == GPTQ_F32 || n <= 6144) return 0;
+    return (size_t)ceil_div(n, 256) * 256 * (size_t)(ceil_div(t, DMA_TOKENS) * DMA_TOKENS) * 2;
 }
 
 extern "C" size_t gptq_hessian_accumulate_workspace_bytes(int64_t n, int64_t t, int xdtype) {
@@ -472,18 +488,17 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
     const bool bf = xdtype == GPTQ_BF16;
     if (n <= 6144)                  // 256-wide tiles only fill the chip when there are enough of them
         return bf ? launch_syrk<true, 128, 2, 2>(g, s) : launch_syrk<false, 128, 2, 2>(g, s);
-#if GPTQ_SYRK_VARIANT == 1
-    return bf ? launch_syrk<true, 256, 2, 4>(g, s) : launch_syrk<false, 256, 2, 4>(g, s);
-#else
-    // whole pairs of 64-token steps through the direct-to-LDS kernel, a ragged tail through the guarded one
-    const int64_t t_main = t / (2 * HK) * (2 * HK);
+    // With a workspace the chunk is first repacked into contiguous, zero-padded panel steps (much better
+    // DRAM-page and cache-line locality for the copies) and the direct-to-LDS kernel takes all of it.
+    if (ws && aligned(ws, 256) && ws_bytes >= syrk_ws_bytes(n, t, xdtype))
+        return bf ? launch_syrk_dma<true>(g, ws, s) : launch_syrk_dma<false>(g, ws, s);
+    // Without one the kernel copies straight from X: whole trips of its 5-stage loop (160 tokens) go through
+    // it, the tail through the guarded kernel.
+    const int64_t t_main = t / DMA_TOKENS * DMA_TOKENS;
     if (t_main > 0) {
         SyrkArgs gm = g;
         gm.t = t_main;
-        // with a workspace the chunk is first repacked into contiguous panel steps (much better DRAM and
-        // cache-line locality for the copies); without one the kernel copies straight from X
-        void* wsp = (ws && aligned(ws, 256) && ws_bytes >= syrk_ws_bytes(n, t, xdtype)) ? ws : nullptr;
-        const int rc = bf ? launch_syrk_dma<true>(gm, wsp, s) : launch_syrk_dma<false>(gm, wsp, s);
+        const int rc = bf ? launch_syrk_dma<true>(gm, nullptr, s) : launch_syrk_dma<false>(gm, nullptr, s);
         if (rc) return rc;
     }
     if (t_main < t) {
@@ -493,7 +508,6 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
         return bf ? launch_syrk<true, 256, 2, 4>(gt, s) : launch_syrk<false, 256, 2, 4>(gt, s);
     }
     return GPTQ_OK;
-#endif
 }
 
 extern "C" int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* stream) {
