@@ -296,57 +296,68 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // term (row / 2) % 4 is (lane / 2) % 4 for all of them, and s / u only add a constant 2048 bytes.
     const int rowA = (wm * 128 + l32) * 64, rowB = PANEL + (wn * 128 + l32) * 64;
     const int co0 = (lhi ^ ((l32 >> 1) & 3)) << 4;      // chunk offset of sub-step 0; sub-step 1 flips bit 5
-    // one 32-token step out of `cur`: the operand fragments of the second 16 tokens are fetched from LDS
-    // while the 16 MFMAs of the first 16 run
-    auto multiply = [&](const unsigned char* cur) {
-        uint4 fa[2][4], fb[2][4];
+    // One 32-token step out of `cur`.  The operand fragments of its first 16 tokens are already in fa[0]/fb[0]
+    // (fetched at the end of the previous step); those of the second 16 tokens are fetched from LDS while the
+    // first 16 MFMAs run, and the first fragments of the NEXT step (`nxt`, whose copies have landed) while
+    // the second 16 run -- so no MFMA ever waits for an LDS round trip, not even right after the barrier.
+    uint4 fa[2][4], fb[2][4];
+    auto fetch = [&](const unsigned char* st, int kk) {
+        const int co = co0 ^ (kk << 5);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            fa[0][s] = *reinterpret_cast<const uint4*>(cur + rowA + co0 + s * 2048);
-            fb[0][s] = *reinterpret_cast<const uint4*>(cur + rowB + co0 + s * 2048);
+            fa[kk][s] = *reinterpret_cast<const uint4*>(st + rowA + co + s * 2048);
+            fb[kk][s] = *reinterpret_cast<const uint4*>(st + rowB + co + s * 2048);
         }
+    };
+    auto multiply = [&](const unsigned char* cur, const unsigned char* nxt) {
+        fetch(cur, 1);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            fa[1][s] = *reinterpret_cast<const uint4*>(cur + rowA + (co0 ^ 32) + s * 2048);
-            fb[1][s] = *reinterpret_cast<const uint4*>(cur + rowB + (co0 ^ 32) + s * 2048);
-        }
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int u = 0; u < 4; ++u) acc[s][u] = mfma16<IS_BF16>(fa[kk][s], fb[kk][u], acc[s][u]);
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);       // the 8 reads of sub-step 0
+            for (int u = 0; u < 4; ++u) acc[s][u] = mfma16<IS_BF16>(fa[0][s], fb[0][u], acc[s][u]);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read of sub-step 1
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+        fetch(nxt, 0);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[s][u] = mfma16<IS_BF16>(fa[1][s], fb[1][u], acc[s][u]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
     };
     // A bare s_barrier: __syncthreads() would also drain every outstanding copy (it fences all memory),
     // which is exactly what the multi-stage pipeline must not do.  Visibility of a stage is established by
-    // each wavefront waiting for its own copies of that step -- vmcnt(24): only the 3 x 8 copies of the
-    // three later steps may still be in flight -- before it arrives at the barrier.
+    // each wavefront waiting for its own copies of that step before it arrives at the barrier.  A step's
+    // barrier publishes the stage of the FOLLOWING step (the one `multiply` prefetches from at its end):
+    // vmcnt(16) = only the 2 x 8 copies of the two steps after that may still be in flight.
     // The loop body is branch-free: past the last step the copies simply re-read the last 32 tokens into
-    // a stage nobody multiplies again, so every wait is the same vmcnt(24).
-    auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur) {
-        __builtin_amdgcn_s_waitcnt(0x4F78);             // vmcnt(24)
-        asm volatile("s_barrier" ::: "memory");         // everybody's copies of this step landed; everybody left `refill`
+    // a stage nobody multiplies again, so every wait is the same.
+    auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur, const unsigned char* nxt) {
+        __builtin_amdgcn_s_waitcnt(0x4F70);             // vmcnt(16)
+        asm volatile("s_barrier" ::: "memory");         // the next step's stage is complete; everybody left `refill`
         issue_copies(refill, min(k_refill, g.t - DK));
-        multiply(cur);
+        multiply(cur, nxt);
     };
     const int64_t ksteps = g.t / DK;                    // a multiple of 5 (the caller passes t % 160 == 0)
     issue_copies(stage0, 0);
     issue_copies(stage1, DK);
     issue_copies(stage2, 2 * DK);
     issue_copies(stage3, 3 * DK);
+    __builtin_amdgcn_s_waitcnt(0x4F78);                 // vmcnt(24): step 0 has landed
+    asm volatile("s_barrier" ::: "memory");
+    fetch(stage0, 0);
     for (int64_t ks = 0; ks < ksteps; ks += 5) {
-        next_stage(stage4, (ks + 4) * DK, stage0);
-        next_stage(stage0, (ks + 5) * DK, stage1);
-        next_stage(stage1, (ks + 6) * DK, stage2);
-        next_stage(stage2, (ks + 7) * DK, stage3);
-        next_stage(stage3, (ks + 8) * DK, stage4);
+        next_stage(stage4, (ks + 4) * DK, stage0, stage1);
+        next_stage(stage0, (ks + 5) * DK, stage1, stage2);
+        next_stage(stage1, (ks + 6) * DK, stage2, stage3);
+        next_stage(stage2, (ks + 7) * DK, stage3, stage4);
+        next_stage(stage3, (ks + 8) * DK, stage4, stage0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                 // drain the dummy copies before the LDS is released
 
