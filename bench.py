@@ -22,6 +22,11 @@ PEAK_F16_MFMA_TFLOPS = 2516.6      # MI355X dense fp16/bf16 matrix-core peak
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes of ONE syrk_f16_dma_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
+# what the same counter reads for a plain 1 GiB copy (factors 2.000 and 1.000): see
+# profiles/layer_solve_opt175b_fc2_pmc_counters.txt.  Keyed by (n, tokens per call); other shapes: not measured.
+MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (7.7812e7 * 2.0 + 4.9099e6 * 1.0) * 1024}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -192,9 +197,12 @@ def main():
         },
         "pack_GBps": (r * n + packed.numel() * 4) / (phases["pack"] * 1e-3) / 1e9,
         "algorithmic_flops": flops,
-        "roofline": {"kernel": "syrk_f16_kernel (gptq_hessian_accumulate)", "bound": "mfma", "achieved": achieved,
+        "roofline": {"kernel": "syrk_f16_dma_kernel (one gptq_hessian_accumulate call; the events also span its ~1.4 ms repack_kernel)",
+                     "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_F16_MFMA_TFLOPS,
-                     "avg_launch_ms": syrk_avg_ms, "flops_per_launch": syrk_flops_per_launch, "traffic": None},
+                     "avg_launch_ms": syrk_avg_ms, "flops_per_launch": syrk_flops_per_launch,
+                     "traffic": MEASURED_SYRK_TRAFFIC_BYTES.get((n, chunk)) if lay.x.dtype != torch.float32 else None,
+                     "traffic_unit": "bytes per launch"},
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(lay, flops)
