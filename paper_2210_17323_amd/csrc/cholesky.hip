@@ -7,15 +7,15 @@
 // matrix Alg. 1 asks for, at half the flops of "Cholesky, invert, Cholesky again" and without ever
 // forming the explicit inverse.
 //
-// Two-level blocking (inner 128, outer 512), everything in place in the upper triangle:
+// Two-level blocking (inner 128, outer 1024), everything in place in the upper triangle:
 //   factorisation, outer blocks last .. first, inner blocks last .. first:
 //     R_bb  = reverse-Cholesky of the 128x128 diagonal block (one workgroup, block in LDS),
 //             and its inverse R_bb^-1 kept in the workspace
 //     P     = H[0:j0, j0:j1] * R_bb^-T                  (GEMM; P is the panel of R above the block)
 //     H[0:j0, outer block columns left of j0] -= P P^T  (rank-128, confined to the outer block)
-//     after the outer block: H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T   (rank-512, carries the flops)
+//     after the outer block: H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T   (rank-1024, carries the flops)
 //   triangular inverse, outer block columns first .. last:
-//     the 512x512 diagonal block is inverted in place with rank-128 steps, then
+//     the 1024x1024 diagonal block is inverted in place with rank-128 steps, then
 //     U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1)           (K = o0, carries the flops)
 #include "common.h"
 
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void zero_lower_kernel(float* H, int64_t ld, i
 using namespace gptq;
 
 namespace {
-constexpr int OB = 512;      // outer block: rank-512 updates keep the big GEMMs compute-bound
+constexpr int OB = 1024;     // outer block: rank-1024 updates keep the big GEMMs compute-bound and their tiles long
 
 struct CholWs { float* dinv; float* P; float* T; float* dense; size_t total; };
 CholWs chol_ws_layout(void* ws, int64_t n) {
@@ -234,8 +234,8 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     const int64_t nouter = ceil_div(n, OB);
 
     // ---- H + lambda I = R R^T, from the last column backwards.  Two levels: inside an outer block of
-    //      512 columns the rank-128 updates touch only that block's columns; the rest of the matrix gets
-    //      one rank-512 update per outer block.
+    //      1024 columns the rank-128 updates touch only that block's columns; the rest of the matrix gets
+    //      one rank-1024 update per outer block.
     for (int64_t o = nouter - 1; o >= 0; --o) {
         const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);
         for (int64_t j0 = (ceil_div(o1 - o0, NB) - 1) * NB + o0; j0 >= o0; j0 -= NB) {
@@ -256,7 +256,7 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
                 if (rc) return rc;
             }
         }
-        // H[0:o0, 0:o0] -= R[0:o0, o0:o1] * R[0:o0, o0:o1]^T  (rank-512, upper tiles)
+        // H[0:o0, 0:o0] -= R[0:o0, o0:o1] * R[0:o0, o0:o1]^T  (rank-1024, upper tiles)
         if (o0 > 0) {
             const int rc = gemm(H + o0, ld, H + o0, ld, H, ld, o0, o0, o1 - o0, -1.f, true, false, true, 0, 0, false);
             if (rc) return rc;
@@ -270,7 +270,7 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     GPTQ_LAUNCH_CHECK();
 
     // ---- U = R^-1 in place, one outer block column at a time (left to right):
-    //      invert the 512 x 512 diagonal block in place with rank-128 steps, then
+    //      invert the 1024 x 1024 diagonal block in place with rank-128 steps, then
     //      U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1), a long-K GEMM against the finished part.
     for (int64_t o = 0; o < nouter; ++o) {
         const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);

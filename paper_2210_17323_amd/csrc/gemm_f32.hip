@@ -273,57 +273,78 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int rowB = LA_BYTES + (wn * 64 + l32) * 64;            // NK: + t * 2048
     const int swz = (l32 >> 1) & 3;
     const int colB = LA_BYTES + (wn * 64 + l32) * 4;             // KN: + t * 128 + krow * 512
-    auto multiply = [&](const unsigned char* cur) {
-        float4 a[2][2];
-        float bv[2][2][4];
+    // One 16-deep step out of `cur`.  The fragments of its first 8 k are already in registers (fetched at the
+    // end of the previous step); those of the second 8 are read from LDS while the first 16 MFMAs run, and
+    // the first fragments of the next step (`nxt`, whose copies have landed) while the second 16 run.
+    float4 a[2][2];
+    float bv[2][2][4];
+    auto fetch = [&](const unsigned char* st, int q) {
+        const int co = ((2 * q + lhi) ^ swz) << 4;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int co = ((2 * q + lhi) ^ swz) << 4;
+        for (int s = 0; s < 2; ++s) a[q][s] = *reinterpret_cast<const float4*>(st + rowA + s * 2048 + co);
+        if (B_IS_NK) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s) a[q][s] = *reinterpret_cast<const float4*>(cur + rowA + s * 2048 + co);
-            if (B_IS_NK) {
+            for (int t = 0; t < 2; ++t) {
+                const float4 b4 = *reinterpret_cast<const float4*>(st + rowB + t * 2048 + co);
+                bv[q][t][0] = b4.x; bv[q][t][1] = b4.y; bv[q][t][2] = b4.z; bv[q][t][3] = b4.w;
+            }
+        } else {
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const float4 b4 = *reinterpret_cast<const float4*>(cur + rowB + t * 2048 + co);
-                    bv[q][t][0] = b4.x; bv[q][t][1] = b4.y; bv[q][t][2] = b4.z; bv[q][t][3] = b4.w;
-                }
-            } else {
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    bv[q][t][i] = *reinterpret_cast<const float*>(st + colB + t * 128 + (8 * q + 4 * lhi + i) * 512);
+        }
+    };
+    auto mfmas = [&](int q) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const float av = i == 0 ? a[q][s].x : (i == 1 ? a[q][s].y : (i == 2 ? a[q][s].z : a[q][s].w));
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        bv[q][t][i] = *reinterpret_cast<const float*>(cur + colB + t * 128 + (8 * q + 4 * lhi + i) * 512);
+                    acc[s][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[q][t][i], acc[s][t], 0, 0, 0);
             }
-        }
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const float av = i == 0 ? a[q][s].x : (i == 1 ? a[q][s].y : (i == 2 ? a[q][s].z : a[q][s].w));
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        acc[s][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[q][t][i], acc[s][t], 0, 0, 0);
-                }
     };
-    // 3 copies per wavefront per step; vmcnt(6): only the copies of the two later steps may be outstanding.
+    auto multiply = [&](const unsigned char* cur, const unsigned char* nxt) {
+        fetch(cur, 1);
+        mfmas(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+        }
+        fetch(nxt, 0);
+        mfmas(1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
+    // 3 copies per wavefront per step.  A step's barrier publishes the stage of the FOLLOWING step (the one
+    // `multiply` prefetches from at its end): vmcnt(3) = only the copies of the step after that may be in flight.
+    // Past the last step the copies re-read the last panels into a stage nobody multiplies again.
     const int64_t ks0 = g.a_upper_tri ? m0 / LK : 0;             // A upper triangular: nothing left of the tile's rows
     const int64_t kend = g.K;
-    auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur) {
-        __builtin_amdgcn_s_waitcnt(0x0F76);                     // vmcnt(6)
+    auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur, const unsigned char* nxt) {
+        __builtin_amdgcn_s_waitcnt(0x0F73);                     // vmcnt(3)
         asm volatile("s_barrier" ::: "memory");
         issue_copies(refill, min(k_refill, kend - LK));
-        multiply(cur);
+        multiply(cur, nxt);
     };
     issue_copies(st0, ks0 * LK);
     issue_copies(st1, (ks0 + 1) * LK);
     issue_copies(st2, (ks0 + 2) * LK);
+    __builtin_amdgcn_s_waitcnt(0x0F76);                         // vmcnt(6): step 0 has landed
+    asm volatile("s_barrier" ::: "memory");
+    fetch(st0, 0);
     for (int64_t k = ks0 * LK; k < kend; k += 4 * LK) {
-        next_stage(st3, k + 3 * LK, st0);
-        next_stage(st0, k + 4 * LK, st1);
-        next_stage(st1, k + 5 * LK, st2);
-        next_stage(st2, k + 6 * LK, st3);
+        next_stage(st3, k + 3 * LK, st0, st1);
+        next_stage(st0, k + 4 * LK, st1, st2);
+        next_stage(st1, k + 5 * LK, st2, st3);
+        next_stage(st2, k + 6 * LK, st3, st0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                         // drain the surplus copies before LDS is released
 

@@ -11,7 +11,7 @@
 //       through uniform (scalar) loads.  The column loop is fully unrolled so every register index
 //       is static.  Outputs: codes, the block's error matrix E (r x 128), per-row sum of e^2.
 //   trailing update    : W[:, i+B:] -= E * U[i:i+B, i+B:], the float32 matrix-core GEMM, applied at once to
-//       the rest of the current 512-column outer block and deferred (rank 512) for the columns beyond.
+//       the rest of the current 1024-column outer block and deferred (rank 1024) for the columns beyond.
 #include "common.h"
 
 namespace gptq {
@@ -109,7 +109,7 @@ struct QuantArgs {
     float* scales; int32_t* zeros; int64_t ngroups;   // [r x ngroups]
     int64_t group;                  // 0 or the group size
     uint8_t* codes; int64_t ldc;
-    float* E; int64_t lde;          // this block's 128 columns of the outer error matrix [r x 512]
+    float* E; int64_t lde;          // this block's 128 columns of the outer error matrix [r x 1024]
     double* half_e2;                // [r] or null
     int first_block;
 };
@@ -215,7 +215,7 @@ static bool group_supported(int64_t group) {
     return group == 8 || group == 16 || group == 32 || group == 64;
 }
 
-constexpr int QOB = 512;    // outer block: trailing updates beyond it are deferred and applied as one rank-512 GEMM
+constexpr int QOB = 1024;   // outer block: trailing updates beyond it are deferred and applied as one rank-1024 GEMM
 
 struct QuantWs { size_t wk, e, ub, total; int64_t ldk; };
 static QuantWs quant_ws_layout(int64_t r, int64_t n) {
@@ -285,11 +285,11 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     GPTQ_LAUNCH_CHECK();
 
     const unsigned qblocks = (unsigned)ceil_div(r, 64);
-    // Lazy batching at two levels (Section 3, Step 2 applied twice): inside an outer block of 512 columns
+    // Lazy batching at two levels (Section 3, Step 2 applied twice): inside an outer block of 1024 columns
     // each 128-column block updates only the rest of the outer block (rank 128); the columns beyond it
-    // get one rank-512 update per outer block.  Same sums as Alg. 1, associated differently.
+    // get one rank-1024 update per outer block.  Same sums as Alg. 1, associated differently.
     // A group grid must see fully updated weights at its first column, so an outer block may only end
-    // where a group ends: groups that neither divide 512 nor are multiples of it fall back to one level.
+    // where a group ends: groups that neither divide 1024 nor are multiples of it fall back to one level.
     const int64_t ob = (group >= QB && (QOB % group) && (group % QOB)) ? QB : QOB;
     for (int64_t o0 = 0; o0 < n; o0 += ob) {
         const int64_t o1 = std::min<int64_t>(o0 + ob, n);
