@@ -224,18 +224,26 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     hipLaunchKernelGGL(damp_kernel, dim3(1), dim3(1024), 0, s, H, ld, n, percdamp, info_dev);
     GPTQ_LAUNCH_CHECK();
 
-    auto gemm = [&](const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int64_t N, int64_t K,
-                    float alpha, bool nk, bool overwrite, bool upper, int64_t crow0, int64_t ccol0, bool atri) -> int {
+    auto gemm_on = [&](hipStream_t st, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                       float alpha, bool nk, bool overwrite, bool upper, int64_t crow0, int64_t ccol0, bool atri) -> int {
         GemmF32 g{};
         g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
         g.b_is_nk = nk; g.overwrite = overwrite; g.upper_only = upper; g.crow0 = crow0; g.ccol0 = ccol0; g.a_upper_tri = atri;
-        return launch_gemm_f32(g, s);
+        return launch_gemm_f32(g, st);
+    };
+    auto gemm = [&](const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                    float alpha, bool nk, bool overwrite, bool upper, int64_t crow0, int64_t ccol0, bool atri) -> int {
+        return gemm_on(s, A, lda, B, ldb, C, ldc, M, N, K, alpha, nk, overwrite, upper, crow0, ccol0, atri);
     };
     const int64_t nouter = ceil_div(n, OB);
+    Lookahead* la = nullptr;
+    if (int rc = lookahead_get(&la)) return rc;
+    hipStream_t s2 = la->stream;
 
     // ---- H + lambda I = R R^T, from the last column backwards.  Two levels: inside an outer block of
     //      1024 columns the rank-128 updates touch only that block's columns; the rest of the matrix gets
     //      one rank-1024 update per outer block.
+    hipEvent_t rest_done = nullptr;         // the helper stream's last trailing update, if one is pending
     for (int64_t o = nouter - 1; o >= 0; --o) {
         const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);
         for (int64_t j0 = (ceil_div(o1 - o0, NB) - 1) * NB + o0; j0 >= o0; j0 -= NB) {
@@ -256,10 +264,27 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
                 if (rc) return rc;
             }
         }
-        // H[0:o0, 0:o0] -= R[0:o0, o0:o1] * R[0:o0, o0:o1]^T  (rank-1024, upper tiles)
+        // H[0:o0, 0:o0] -= R[0:o0, o0:o1] * R[0:o0, o0:o1]^T  (rank-1024, upper tiles), with look-ahead:
+        // the columns [p0, o0) of the next outer block are updated first, on the caller's stream, which then
+        // goes on to factor that block (short, serial kernels); the rest, H[0:p0, 0:p0], is updated on the
+        // helper stream meanwhile.  The two parts and the next block's factorisation write disjoint regions;
+        // the next block's own column update waits for the helper's, which wrote the same region.
         if (o0 > 0) {
-            const int rc = gemm(H + o0, ld, H + o0, ld, H, ld, o0, o0, o1 - o0, -1.f, true, false, true, 0, 0, false);
+            const int64_t p0 = o0 - OB;                  // outer blocks start at multiples of OB
+            hipEvent_t factored = la->event();
+            GPTQ_HIP_CHECK(hipEventRecord(factored, s));
+            if (rest_done) GPTQ_HIP_CHECK(hipStreamWaitEvent(s, rest_done, 0));
+            int rc = gemm(H + o0, ld, H + p0 * ld + o0, ld, H + p0, ld, o0, o0 - p0, o1 - o0, -1.f, true, false, true, 0, p0, false);
             if (rc) return rc;
+            if (p0 > 0) {
+                GPTQ_HIP_CHECK(hipStreamWaitEvent(s2, factored, 0));
+                rc = gemm_on(s2, H + o0, ld, H + o0, ld, H, ld, p0, p0, o1 - o0, -1.f, true, false, true, 0, 0, false);
+                if (rc) return rc;
+                rest_done = la->event();
+                GPTQ_HIP_CHECK(hipEventRecord(rest_done, s2));
+            } else {
+                rest_done = nullptr;
+            }
         }
     }
 
@@ -268,10 +293,17 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     // lower half and the below-diagonal parts of straddling update tiles); nothing writes there afterwards.
     hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
     GPTQ_LAUNCH_CHECK();
+    {
+        hipEvent_t cleared = la->event();
+        GPTQ_HIP_CHECK(hipEventRecord(cleared, s));
+        GPTQ_HIP_CHECK(hipStreamWaitEvent(s2, cleared, 0));
+    }
 
     // ---- U = R^-1 in place, one outer block column at a time (left to right):
     //      invert the 1024 x 1024 diagonal block in place with rank-128 steps, then
     //      U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1), a long-K GEMM against the finished part.
+    //      The in-block inversions touch nothing but their own diagonal block, so they all run ahead on the
+    //      helper stream while the caller's stream carries the long GEMMs, each waiting for its block's event.
     for (int64_t o = 0; o < nouter; ++o) {
         const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);
         for (int64_t j0 = o0; j0 < o1; j0 += NB) {
@@ -281,21 +313,26 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
             if (j1 < o1) {
                 // R[b, right] = -R_bb^-1 * R[b, right].  In place: a workgroup reads its own 128 columns of all
                 // (<= 128) rows through LDS before its epilogue writes them, and there is a single tile row.
-                int rc = gemm(dinv_b, NB, H + j0 * ld + j1, ld, H + j0 * ld + j1, ld, nbk, o1 - j1, nbk, -1.f, false, true, false, 0, 0, false);
+                int rc = gemm_on(s2, dinv_b, NB, H + j0 * ld + j1, ld, H + j0 * ld + j1, ld, nbk, o1 - j1, nbk, -1.f, false, true, false, 0, 0, false);
                 if (rc) return rc;
                 if (j0 > o0) {
-                    rc = gemm(H + o0 * ld + j0, ld, H + j0 * ld + j1, ld, H + o0 * ld + j1, ld, j0 - o0, o1 - j1, nbk, 1.f, false, false, false, 0, 0, false);
+                    rc = gemm_on(s2, H + o0 * ld + j0, ld, H + j0 * ld + j1, ld, H + o0 * ld + j1, ld, j0 - o0, o1 - j1, nbk, 1.f, false, false, false, 0, 0, false);
                     if (rc) return rc;
                 }
             }
             if (j0 > o0) {
                 // R[above-in-block, b] = R[above-in-block, b] * R_bb^-1.  In place: a single tile column, each
                 // workgroup reads all of its own rows before writing them.
-                const int rc = gemm(H + o0 * ld + j0, ld, dinv_b, NB, H + o0 * ld + j0, ld, j0 - o0, nbk, nbk, 1.f, false, true, false, 0, 0, false);
+                const int rc = gemm_on(s2, H + o0 * ld + j0, ld, dinv_b, NB, H + o0 * ld + j0, ld, j0 - o0, nbk, nbk, 1.f, false, true, false, 0, 0, false);
                 if (rc) return rc;
             }
-            hipLaunchKernelGGL(copy_block_kernel, dim3(64), dim3(256), 0, s, H + j0 * ld + j0, ld, dinv_b, (int64_t)NB, (int64_t)nbk, nbk, 1);
+            hipLaunchKernelGGL(copy_block_kernel, dim3(64), dim3(256), 0, s2, H + j0 * ld + j0, ld, dinv_b, (int64_t)NB, (int64_t)nbk, nbk, 1);
             GPTQ_LAUNCH_CHECK();
+        }
+        {
+            hipEvent_t inverted = la->event();
+            GPTQ_HIP_CHECK(hipEventRecord(inverted, s2));
+            GPTQ_HIP_CHECK(hipStreamWaitEvent(s, inverted, 0));
         }
         if (o0 > 0) {
             const int ow = (int)(o1 - o0);

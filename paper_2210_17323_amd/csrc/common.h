@@ -34,6 +34,20 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 
+// ---- look-ahead: a helper stream and a ring of events (runtime.hip) ----------------------------
+// The blocked solvers put the short, serial kernels of the next block column and the long trailing GEMM
+// of the current one on two streams so that they overlap.  The helper stream (default priority,
+// non-blocking) and its events are created once per host thread and device and live until the process
+// ends.  Every use forks from and joins back into the caller's stream with events, so after an entry
+// point returns all of its work is ordered on the caller's stream alone.
+struct Lookahead {
+    hipStream_t stream = nullptr;
+    hipEvent_t ev[8] = {};
+    unsigned next = 0;
+    hipEvent_t event() { return ev[next++ & 7]; }
+};
+int lookahead_get(Lookahead** out);     // for the current device; GPTQ_OK or an error code
+
 // ---- float32 matrix-core GEMM used by several steps (gemm_f32.hip) --------------------------
 // C[M x N] += alpha * A[M x K] * op(B), A row-major (K contiguous).
 //   b_is_nk = true : B is [N x K] row-major (K contiguous)  -> C += alpha * A * B^T

@@ -223,7 +223,7 @@ static QuantWs quant_ws_layout(int64_t r, int64_t n) {
     l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
     l.wk = 0;
     size_t off = round_up((size_t)std::max<int64_t>(r, 1) * l.ldk * sizeof(float), 256);
-    l.e = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QOB * sizeof(float), 256);
+    l.e = off; off += 2 * round_up((size_t)std::max<int64_t>(r, 1) * QOB * sizeof(float), 256);   // two error panels (look-ahead)
     l.ub = off; off += QB * QB * sizeof(float);
     l.total = off + 256;
     return l;
@@ -266,7 +266,8 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* base = static_cast<char*>(ws);
     float* Wk = reinterpret_cast<float*>(base + lay.wk);
-    float* E = reinterpret_cast<float*>(base + lay.e);
+    float* Ebuf[2] = {reinterpret_cast<float*>(base + lay.e),
+                      reinterpret_cast<float*>(base + lay.e + round_up((size_t)r * QOB * sizeof(float), 256))};
     float* Ub = reinterpret_cast<float*>(base + lay.ub);
     const int maxq = (grid == GPTQ_GRID_TERNARY) ? 2 : ((1 << bits) - 1);
     const int64_t ngroups = group ? n / group : 1;
@@ -291,8 +292,19 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     // A group grid must see fully updated weights at its first column, so an outer block may only end
     // where a group ends: groups that neither divide 1024 nor are multiples of it fall back to one level.
     const int64_t ob = (group >= QB && (QOB % group) && (group % QOB)) ? QB : QOB;
-    for (int64_t o0 = 0; o0 < n; o0 += ob) {
+    // Look-ahead: after an outer block is quantized, the columns of the next outer block are updated first, on
+    // the caller's stream, which goes straight on to quantize them (short, serial kernels); all columns
+    // beyond are updated on the helper stream meanwhile.  The two updates and the next block's kernels touch
+    // disjoint columns of the weights; the error panel E alternates between two buffers because the helper's
+    // GEMM still reads one while the next block fills the other.
+    Lookahead* la = nullptr;
+    if (int rc = lookahead_get(&la)) return rc;
+    hipStream_t s2 = la->stream;
+    hipEvent_t rest_done = nullptr;         // the helper stream's last trailing update, if one is pending
+    int eb = 0;
+    for (int64_t o0 = 0; o0 < n; o0 += ob, eb ^= 1) {
         const int64_t o1 = std::min<int64_t>(o0 + ob, n);
+        float* E = Ebuf[eb];
         for (int64_t j0 = o0; j0 < o1; j0 += QB) {
             const int nbk = (int)std::min<int64_t>(QB, n - j0);
             const int64_t j1 = j0 + nbk;
@@ -324,11 +336,24 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
             }
         }
         if (o1 < n) {
+            const int64_t o2 = std::min<int64_t>(o1 + ob, n);
+            hipEvent_t quantized = la->event();
+            GPTQ_HIP_CHECK(hipEventRecord(quantized, s));
+            if (rest_done) GPTQ_HIP_CHECK(hipStreamWaitEvent(s, rest_done, 0));    // it wrote the columns from o1 on
             GemmF32 g{};
             g.A = E; g.lda = QOB; g.B = U + o0 * ldu + o1; g.ldb = ldu; g.C = Wk + o1; g.ldc = lay.ldk;
-            g.M = r; g.N = n - o1; g.K = o1 - o0; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
-            const int rc = launch_gemm_f32(g, s);
+            g.M = r; g.N = o2 - o1; g.K = o1 - o0; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
+            int rc = launch_gemm_f32(g, s);
             if (rc) return rc;
+            rest_done = nullptr;
+            if (o2 < n) {
+                GPTQ_HIP_CHECK(hipStreamWaitEvent(s2, quantized, 0));
+                g.B = U + o0 * ldu + o2; g.C = Wk + o2; g.N = n - o2;
+                rc = launch_gemm_f32(g, s2);
+                if (rc) return rc;
+                rest_done = la->event();
+                GPTQ_HIP_CHECK(hipEventRecord(rest_done, s2));
+            }
         }
     }
     if (Wq) {

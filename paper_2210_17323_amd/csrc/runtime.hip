@@ -1,4 +1,4 @@
-// Library-wide helpers: version, thread-local error text.
+// Library-wide helpers: version, thread-local error text, the look-ahead stream.
 #include "common.h"
 
 #include <cstring>
@@ -17,6 +17,23 @@ void set_error(const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+}
+
+int lookahead_get(Lookahead** out) {
+    constexpr int MAXDEV = 64;
+    static thread_local Lookahead table[MAXDEV];
+    int dev = 0;
+    GPTQ_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAXDEV) return fail(GPTQ_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+    Lookahead& l = table[dev];
+    if (!l.stream) {
+        hipStream_t st = nullptr;
+        GPTQ_HIP_CHECK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+        for (hipEvent_t& e : l.ev) GPTQ_HIP_CHECK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        l.stream = st;
+    }
+    *out = &l;
+    return GPTQ_OK;
 }
 
 }  // namespace gptq

@@ -21,7 +21,7 @@ def test_library_loads_and_exports_every_declared_symbol():
 def test_workspace_sizes():
     assert g.gptq_damp_cholesky_inverse_workspace_bytes(256) >= 2 * 128 * 128 * 4 + 256 * 128 * 4
     big = g.gptq_quantize_layer_workspace_bytes(12288, 49152)
-    assert 12288 * 49152 * 4 < big < 12288 * 49152 * 4 * 1.03 + (1 << 24)      # W copy + the r x 1024 error panel
+    assert 12288 * 49152 * 4 < big < 12288 * 49152 * 4 * 1.05 + (1 << 24)      # W copy + two r x 1024 error panels
     assert g.gptq_quantize_layer_workspace_bytes(0, 0) > 0
     assert g.gptq_hessian_accumulate_workspace_bytes(49152, 32768) == 49152 * 32800 * 2
     assert g.gptq_hessian_accumulate_workspace_bytes(4096, 32768) == 0
