@@ -300,6 +300,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // (fetched at the end of the previous step); those of the second 16 tokens are fetched from LDS while the
     // first 16 MFMAs run, and the first fragments of the NEXT step (`nxt`, whose copies have landed) while
     // the second 16 run -- so no MFMA ever waits for an LDS round trip, not even right after the barrier.
+    // The step's 8 copies are spread over its MFMAs as well: with one wavefront per SIMD nothing else can
+    // issue while a copy instruction is being accepted (tens of cycles each), so copies issued back to back
+    // idle the matrix core, while one copy every four MFMAs hides behind the MFMA in flight.
     uint4 fa[2][4], fb[2][4];
     auto fetch = [&](const unsigned char* st, int kk) {
         const int co = co0 ^ (kk << 5);
@@ -319,6 +322,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int i = 0; i < 8; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+            if (i & 1) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 of this step's 8 copies
         }
         fetch(nxt, 0);
 #pragma unroll
@@ -329,6 +333,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int i = 0; i < 8; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i & 1) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
         }
     };
     // A bare s_barrier: __syncthreads() would also drain every outstanding copy (it fences all memory),
