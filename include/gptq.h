@@ -87,6 +87,9 @@ GPTQ_API int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* str
  *   Computed as a Cholesky factorisation taken from the last column backwards, H + lambda I = R R^T with R
  *   upper triangular, followed by the triangular inverse U = R^-1 (the same matrix, by uniqueness of
  *   the Cholesky factor), all in float32.
+ *   Part of the work is enqueued on a helper stream owned by the library (created once per host thread and
+ *   device, default priority) and joined back with events: when the call returns, everything it enqueued
+ *   is ordered on `stream`, and nothing of it starts before the work already on `stream`.
  */
 GPTQ_API size_t gptq_damp_cholesky_inverse_workspace_bytes(int64_t n);
 GPTQ_API int gptq_damp_cholesky_inverse(float* H_U, int64_t ld, int64_t n, float percdamp,
@@ -120,7 +123,8 @@ GPTQ_API int gptq_check_info(const int* info_dev, int* host_info, void* stream);
  *            E[:, j] = (W[:, j] - Q[:, j]) / U[j][j] at the time column j is quantized (Alg. 1).  Its
  *            sum over rows equals (1/2) tr((W-Q)(H + lambda I)(W-Q)^T).  May be NULL.
  *   ws       at least gptq_quantize_layer_workspace_bytes(r, n, block, group) bytes, 256-byte aligned.
- *   r == 0 or n == 0 is a valid no-op.
+ *   r == 0 or n == 0 is a valid no-op.  Like step 2, the call puts part of its work on the library's helper
+ *   stream and joins it back before returning.
  */
 GPTQ_API size_t gptq_quantize_layer_workspace_bytes(int64_t r, int64_t n, int block, int64_t group);
 GPTQ_API int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
