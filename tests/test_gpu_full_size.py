@@ -1,6 +1,8 @@
-"""Parity at the headline size (OPT-175B fc2: W 12288 x 49152, X 49152 x 262144 fp16, 3-bit), in the
-launch configuration bench.py times.  A float64 oracle cannot run this layer whole, so every step is
-checked on sampled outputs it can compute one by one, or through properties that hold at any size:
+"""Parity at full size: the headline layer (OPT-175B fc2: W 12288 x 49152, X 49152 x 262144 fp16, 3-bit) in the
+launch configuration bench.py times, and one layer of every other workload shape (OPT-175B fc1, OPT-6.7B
+attention, BLOOM-176B attention with 2-bit and ternary grids at group size 128, a 12288 x 12288 projection at
+4 bits), all with the full 262144 calibration tokens.  A float64 oracle cannot run these layers whole, so every
+step is checked on sampled outputs it can compute one by one, or through properties that hold at any size:
 
   Hessian   sampled 128 x 128 blocks of H over the full token range           (rel. Frobenius <= 1e-5)
   U         the trailing corner U[k:, k:] depends only on H[k:, k:]            (oracle on that corner)
@@ -36,25 +38,41 @@ def _sym_block(Hd_gpu, r0, r1, c0, c1):
     return up
 
 
-def test_fc2_full_size_sampled_parity():
+def _layers():
+    c3, c4, c5 = configs.config3(), configs.config4(), configs.config5(bits=4)
+    return {
+        "opt175b_fc2_3bit": c3[1],
+        "opt175b_fc1_3bit": c3[0],
+        "opt6.7b_attn_4bit": configs.config2()[0],
+        "bloom176b_qkv_2bit_g128": c4[0],
+        "bloom176b_out_ternary_g128": c4[3],
+        "opt175b_q_4bit": c5[0],
+    }
+
+
+@pytest.mark.parametrize("which", list(_layers()))
+def test_full_size_sampled_parity(which):
     import paper_2210_17323_amd as g
     from paper_2210_17323_amd import solver as S
-    lay = configs.config3()[1]
+    lay = _layers()[which]
     r, n, m = lay.r, lay.n, lay.x.m
+    _say(f"full size {which}: W {r} x {n}, X {n} x {m}, bits={lay.bits} grid={lay.grid} group={lay.group}")
     t0 = time.time()
     W, X = configs.materialize(lay, "cuda")
     torch.cuda.synchronize()
     _say(f"generated W {tuple(W.shape)} and X {tuple(X.shape)} in {time.time() - t0:.1f}s")
     # the generator gives the same bits on both devices
-    assert torch.equal(X[40000:40004, 200000:200064].cpu(), lay.x.tile(row0=40000, nrows=4, col0=200000, ncols=64))
-    assert torch.equal(W[7000:7002, 30000:30064].cpu(), lay.weights(row0=7000, nrows=2)[:, 30000:30064])
+    xr, wr, wc = n // 2 + 17, r // 2 + 856, n - 4000
+    assert torch.equal(X[xr:xr + 4, 200000:200064].cpu(), lay.x.tile(row0=xr, nrows=4, col0=200000, ncols=64))
+    assert torch.equal(W[wr:wr + 2, wc:wc + 64].cpu(), lay.weights(row0=wr, nrows=2)[:, wc:wc + 64])
 
     # ---- step 1
     H = S.new_hessian(n)
     S.accumulate(H, X, chunk=32768)
     torch.cuda.synchronize()
     _say(f"hessian done at {time.time() - t0:.1f}s")
-    for bi, bj in ((0, 0), (5, 300), (17, 200), (383, 383)):
+    nb = n // 128
+    for bi, bj in ((0, 0), (nb // 77, nb - 1 - nb // 5), (nb // 23, nb // 2 + nb // 48), (nb - 1, nb - 1)):
         A = X[bi * 128:(bi + 1) * 128].cpu().double().numpy()
         B = X[bj * 128:(bj + 1) * 128].cpu().double().numpy()
         want = 2.0 * (A @ B.T)
@@ -107,7 +125,8 @@ def test_fc2_full_size_sampled_parity():
     res = S.quantize(W, U, lay.bits, lay.grid, lay.block, lay.group, want_Wq=False, pack=True)
     torch.cuda.synchronize()
     _say(f"quantize + pack done at {time.time() - t0:.1f}s")
-    rows = np.array([0, 1, 63, 64, 4097, 8191, 11000, 12287])
+    rows = np.unique(np.array([0, 1, 63, 64, r // 3 + 1, 2 * r // 3 - 1, r - 1288, r - 1]))
+    gsz = lay.group if lay.group else n
     Wr = W[rows].double().cpu().numpy()
     codes_g = res.codes[rows].cpu().numpy().astype(np.int64)
     zero_g = res.zeros[rows].cpu().numpy().astype(np.int64)
@@ -116,8 +135,16 @@ def test_fc2_full_size_sampled_parity():
     _say(f"  U on the host at {time.time() - t0:.1f}s")
     forced = O.gptq_quantize(Wr, Uh, lay.bits, lay.grid, lay.block, lay.group, teacher_codes=codes_g)
     _say(f"  teacher-forced oracle done at {time.time() - t0:.1f}s")
-    assert np.array_equal(forced["zero"], zero_g) and np.array_equal(forced["scale"], scale_g)
-    diff = np.abs(forced["codes"] - codes_g)
+    # Per-row grids come from the original weights: identical.  Group grids come from each side's own working
+    # weights (float32 vs float64 history): scales agree to rounding, a zero point may differ at a tie of
+    # rint(-lo/scale), which shifts that group's codes as a whole -- so compare levels, code - zero.
+    assert np.allclose(forced["scale"], scale_g, rtol=1e-5)
+    if lay.group == 0:
+        assert np.array_equal(forced["zero"], zero_g) and np.array_equal(forced["scale"], scale_g)
+    zdiff = float((forced["zero"] != zero_g).mean())
+    _say(f"  zero points differing: {zdiff:.6f}")
+    assert zdiff <= 1e-3
+    diff = np.abs((forced["codes"] - np.repeat(forced["zero"], gsz, axis=1)) - (codes_g - np.repeat(zero_g, gsz, axis=1)))
     agree = float((diff == 0).mean())
     _say(f"  teacher-forced agreement {agree:.6f} over {diff.size} weights, {int((diff != 0).sum())} differ, max step {diff.max()}")
     assert agree >= 0.999 and diff.max() <= 1
@@ -127,10 +154,11 @@ def test_fc2_full_size_sampled_parity():
         _say(f"  largest distance from a tie among the differing decisions: {dist.max():.3e}")
         assert dist.max() <= 2e-3
     own = O.gptq_quantize(Wr, Uh, lay.bits, lay.grid, lay.block, lay.group)
-    raw = float((own["codes"] == codes_g).mean())
+    raw = float(((own["codes"] - np.repeat(own["zero"], gsz, axis=1)) == (codes_g - np.repeat(zero_g, gsz, axis=1))).mean())
     _say(f"  unforced oracle done at {time.time() - t0:.1f}s; raw agreement {raw:.6f} (informational: one tie flip cascades)")
     # layer error of the sampled rows through the damped Hessian, float64, from the GPU's H
-    Dg = Wr - forced["Q"]                              # forced Q == the GPU's codes on the GPU's grid
+    Qg = np.repeat(scale_g.astype(np.float64), gsz, axis=1) * (codes_g - np.repeat(zero_g, gsz, axis=1))
+    Dg = Wr - Qg                                       # the GPU's codes on the GPU's grid
     Do = Wr - own["Q"]
     eg = np.zeros(len(rows)); eo = np.zeros(len(rows))
     for r0 in range(0, n, 4096):
@@ -144,7 +172,8 @@ def test_fc2_full_size_sampled_parity():
     _say(f"  row errors: gpu {eg.sum():.6e} oracle {eo.sum():.6e} kernel (1/2)sum e^2 {half.sum():.6e}")
     assert abs(eg.sum() - eo.sum()) <= 0.01 * eo.sum()
     assert np.all(np.abs(half - eg) <= 0.01 * eg)
-    assert np.allclose(0.5 * np.sum(forced["E"] ** 2, axis=1), eg, rtol=1e-3)    # identity (1/2)|E|^2 = (1/2) d Hd d^T
+    if zdiff == 0.0:
+        assert np.allclose(0.5 * np.sum(forced["E"] ** 2, axis=1), eg, rtol=1e-3)    # identity (1/2)|E|^2 = (1/2) d Hd d^T
     # packing of the sampled rows
     assert np.array_equal(res.packed[rows].cpu().numpy().view(np.uint32), O.pack_codes(codes_g, lay.bits))
     _say(f"full-size parity done in {time.time() - t0:.1f}s")
