@@ -23,9 +23,9 @@ PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
 # HBM-side bytes of ONE syrk_f16_dma_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
-# what the same counter reads for a plain 1 GiB copy (factors 2.000 and 1.000): see
+# what the same counter reads for a plain 1 GiB copy kernel (factors 2.000 and 1.000): see
 # profiles/layer_solve_opt175b_fc2_pmc_counters.txt.  Keyed by (n, tokens per call); other shapes: not measured.
-MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (7.7812e7 * 2.0 + 4.9099e6 * 1.0) * 1024}
+MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (1.2461e8 * 2.0 + 5.0879e6 * 1.0) * 1024}
 
 
 def parse():
@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptq_hessian_accumulate call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="before the timed region, run one plain 1 GiB device-to-device copy (a kernel of known "
+                    help="before the timed region, run one plain 1 GiB device-to-device copy kernel (dst = src * 1: known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
     return ap.parse_args()
 
@@ -158,7 +158,7 @@ def main():
     if a.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        torch.mul(src, 1.0, out=dst)        # an elementwise kernel (a same-dtype copy_ would be a DMA transfer, not a kernel)
         torch.cuda.synchronize()
         del src, dst
     for _ in range(a.warmup):
