@@ -33,7 +33,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--layer", default="opt175b_fc2", help="opt175b_fc2 (headline) | opt175b_fc1 | opt6.7b_attn | tiny")
+    ap.add_argument("--layer", default="opt175b_fc2", help="opt175b_fc2 (headline) | opt175b_fc1 | opt6.7b_attn | bloom176b_qkv_2bit_g128 | "
+                         "bloom176b_out_ternary_g128 | opt175b_q | tiny")
     ap.add_argument("--tokens", type=int, default=0, help="calibration tokens (default: the layer's own, 262144)")
     ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptq_hessian_accumulate call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -50,6 +51,9 @@ def pick_layer(name: str, tokens: int):
         "opt175b_fc2": lambda: configs.config3(m)[1],
         "opt175b_fc1": lambda: configs.config3(m)[0],
         "opt6.7b_attn": lambda: configs.config2(m)[0],
+        "bloom176b_qkv_2bit_g128": lambda: configs.config4(m)[0],
+        "bloom176b_out_ternary_g128": lambda: configs.config4(m)[3],
+        "opt175b_q": lambda: configs.config5(m)[0],
         "tiny": lambda: configs.config1()[0],
     }
     return table[name]()

@@ -317,6 +317,25 @@ def unpack_codes(words, n: int, bits: int) -> np.ndarray:
     return (stream.reshape(r, n, bits).astype(np.int64) * weights).sum(axis=2)
 
 
+def dequantize_packed(words, n: int, bits: int, scale, zero, group: int = 0) -> np.ndarray:
+    """The weight matrix a packed layer stands for: entry (i, k) is scale * (code - zero) with the
+    scale and zero point of row i (group == 0) or of row i's group k // group (Section 4, "Practical
+    Speedups": weights are dequantized when they are needed).  float64."""
+    codes = unpack_codes(words, n, bits)
+    scale = np.asarray(scale, dtype=np.float64)
+    zero = np.asarray(zero, dtype=np.float64)
+    if group:
+        scale = np.repeat(scale, group, axis=1)[:, :n]
+        zero = np.repeat(zero, group, axis=1)[:, :n]
+    return scale * (codes - zero)
+
+
+def matvec_packed(words, n: int, bits: int, scale, zero, group: int, x) -> np.ndarray:
+    """Quantized-matrix times full-precision vector (Section 4, "Practical Speedups"): y = Q x with
+    Q the dequantized matrix; the vector is not quantized.  float64."""
+    return dequantize_packed(words, n, bits, scale, zero, group) @ np.asarray(x, dtype=np.float64)
+
+
 def bits_per_weight(bits: int, group: int, scale_bits: int = 16) -> float:
     """Average storage per weight for a grouped grid holding one scale of scale_bits and one
     bits-wide integer zero point per group ("Extreme Quantization": FP16 scale and 2-bit zero

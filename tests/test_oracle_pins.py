@@ -312,3 +312,42 @@ def test_teacher_forcing_reproduces_own_decisions_and_isolates_a_flip():
     a = O.gptq_quantize(W, U32, 3, block=16)
     b = O.gptq_quantize(W, U32.astype(np.float64), 3, block=16)
     assert np.array_equal(a["codes"], b["codes"]) and np.array_equal(a["E"], b["E"])
+
+
+# ------------------------------------------------------------------ consumers of the packed format
+
+def test_dequantize_and_matvec_by_hand():
+    # the 3-bit words of test_pack_hand_computed_words: codes 1 2 3 4 5 6 7 0 1 2 7 (the last one straddles the words)
+    words = np.array([[0xD11F58D1, 0x1]], dtype=np.uint32)
+    Q = O.dequantize_packed(words, 11, 3, scale=[[0.5]], zero=[[3]])
+    assert Q.tolist() == [[-1.0, -0.5, 0.0, 0.5, 1.0, 1.5, 2.0, -1.5, -1.0, -0.5, 2.0]]
+    x = np.array([1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11.0])
+    # -1 - 1 + 0 + 2 + 5 + 9 + 14 - 12 - 9 - 5 + 22 = 24
+    assert O.matvec_packed(words, 11, 3, [[0.5]], [[3]], 0, x).tolist() == [24.0]
+    # two groups of 4 columns over 8 columns, 2-bit codes 3 0 1 2 | 3 0 1 2, scales 2 and 0.25, zeros 1 and 2
+    w2 = np.array([[0x9393]], dtype=np.uint32)
+    Qg = O.dequantize_packed(w2, 8, 2, scale=[[2.0, 0.25]], zero=[[1, 2]], group=4)
+    assert Qg.tolist() == [[4.0, -2.0, 0.0, 2.0, 0.25, -0.5, -0.25, 0.0]]
+    assert O.matvec_packed(w2, 8, 2, [[2.0, 0.25]], [[1, 2]], 4, np.ones(8)).tolist() == [3.5]
+
+
+@pytest.mark.parametrize("bits,grid,group", [(3, "minmax", 0), (4, "minmax", 32), (2, "ternary", 8), (2, "minmax", 128)])
+def test_packed_consumers_reproduce_algorithm_1_output(bits, grid, group):
+    # what Alg. 1 calls Q is what the packed layer must stand for, bit for bit
+    rng = np.random.default_rng(41 + bits)
+    r, n = 9, 256
+    W = rng.normal(size=(r, n)) * 0.02
+    X = rng.normal(size=(n, 4 * n))
+    U = O.hinv_cholesky_upper(O.damp(O.hessian(X)))
+    out = O.gptq_quantize(W, U, bits, grid, 128, group)
+    words = O.pack_codes(out["codes"], bits)
+    Q = O.dequantize_packed(words, n, bits, out["scale"], out["zero"], group)
+    assert np.array_equal(Q, out["Q"])
+    x = rng.normal(size=n)
+    y = O.matvec_packed(words, n, bits, out["scale"], out["zero"], group, x)
+    loops = np.array([sum(out["Q"][i, k] * x[k] for k in range(n)) for i in range(r)])
+    assert np.allclose(y, loops, rtol=1e-12, atol=1e-15)
+    # closed form: equal codes c, one scale s, zero z  =>  y = s (c - z) sum(x)
+    c = np.full((2, 70), 5 % (1 << bits))
+    yc = O.matvec_packed(O.pack_codes(c, bits), 70, bits, [[0.5], [2.0]], [[1], [0]], 0, x[:70])
+    assert np.allclose(yc, [0.5 * (c[0, 0] - 1) * x[:70].sum(), 2.0 * c[0, 0] * x[:70].sum()], rtol=1e-12)
