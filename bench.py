@@ -184,6 +184,25 @@ def main():
     syrk_flops_per_launch = sum(float(n) * (n + 1) * t for (_, _, t) in syrk_events) / len(syrk_events)
     achieved = syrk_flops_per_launch / (syrk_avg_ms * 1e-3) / 1e12
     total_flops = sum(flops.values())
+
+    # Consumers of the packed layer (outside the timed step): batch-1 product and full decompression
+    xv = torch.randn(n, device=dev).half()
+    yv = torch.empty(r, dtype=torch.float32, device=dev)
+    Wd = torch.empty((r, n), dtype=torch.float16, device=dev)
+    def timed(fn, reps):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    mv_ms = timed(lambda: g.gptq_matvec_packed(packed, n, pbits, scales, zeros, lay.group, xv, yv), 50)
+    dq_ms = timed(lambda: g.gptq_dequantize_packed(packed, n, pbits, scales, zeros, lay.group, Wd), 10)
+    grid_bytes = scales.numel() * 8
+    mv_bytes = packed.numel() * 4 + grid_bytes + n * 2 + r * 4
+    dq_bytes = packed.numel() * 4 + grid_bytes + r * n * 2
+    del Wd
     out = {
         "metric": "gptq_layer_solve_tflops", "value": total_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -201,6 +220,10 @@ def main():
         },
         "pack_GBps": (r * n + packed.numel() * 4) / (phases["pack"] * 1e-3) / 1e9,
         "algorithmic_flops": flops,
+        "packed_consumers": {"matvec_us": mv_ms * 1e3, "matvec_GBps": mv_bytes / (mv_ms * 1e-3) / 1e9,
+                             "matvec_frac_of_hbm_peak": mv_bytes / (mv_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                             "dequantize_f16_ms": dq_ms, "dequantize_GBps": dq_bytes / (dq_ms * 1e-3) / 1e9,
+                             "dequantize_frac_of_hbm_peak": dq_bytes / (dq_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "roofline": {"kernel": "syrk_f16_dma_kernel (one gptq_hessian_accumulate call; the events also span its ~1.4 ms repack_kernel)",
                      "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_F16_MFMA_TFLOPS,

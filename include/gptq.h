@@ -6,6 +6,7 @@
  *   2. gptq_damp_cholesky_inverse   U = Cholesky((H + lambda I)^-1)^T                (Section 3, Step 3; Alg. 1)
  *   3. gptq_quantize_layer          the block / column loop with lazy batch updates  (Section 3, Step 2; Alg. 1)
  *   4. gptq_pack                    dense 2/3/4-bit stream of the resulting codes    (Section 4, "Practical Speedups")
+ * and two consumers of the packed layer (same section): gptq_dequantize_packed, gptq_matvec_packed.
  *
  * Conventions
  *   - Every data pointer is a DEVICE pointer to memory owned by the caller, valid on the current
@@ -149,6 +150,30 @@ GPTQ_API int gptq_pack(const uint8_t* codes, int64_t ldc, int64_t r, int64_t n, 
 /* Inverse of gptq_pack. */
 GPTQ_API int gptq_unpack(const uint32_t* words, int64_t ld_words, int64_t r, int64_t n, int bits,
                 uint8_t* codes, int64_t ldc, void* stream);
+
+/*
+ * Consumers of the packed format (Section 4, "Practical Speedups"; appendix on the benchmarking setup).
+ *
+ *   words    [r x ld_words] uint32, the layout gptq_pack writes; scales [r x G] float32 and zeros [r x G] int32
+ *            as gptq_quantize_layer writes them (G = 1 for group == 0, else n / group; n % group == 0).
+ *            A weight is scale * (code - zero) with the grid of its row, or of its row's group k / group.
+ *            A ternary layer is bits = 2 with zero = 1.
+ *
+ * gptq_dequantize_packed: the whole matrix, decompressed ahead of a large-batch product.
+ *   out      [r x n] float16 or float32 (odtype = GPTQ_F16 / GPTQ_F32), ldo >= n.  The float32 product
+ *            scale * (code - zero), for float16 rounded once more to nearest even.
+ *
+ * gptq_matvec_packed: y = Q x for one vector (batch-1 generation): weights are dequantized as they are read, the
+ *   vector is not quantized.
+ *   x        [n] float16 or float32 (xdtype); y [r] float32, overwritten.  Sums are accumulated in float32.
+ *            group must be 0, 8, 16 or a multiple of 32.  n == 0 gives y = 0; r == 0 is a no-op.
+ */
+GPTQ_API int gptq_dequantize_packed(const uint32_t* words, int64_t ld_words, int64_t r, int64_t n, int bits,
+                           const float* scales, const int32_t* zeros, int64_t group,
+                           void* out, int odtype, int64_t ldo, void* stream);
+GPTQ_API int gptq_matvec_packed(const uint32_t* words, int64_t ld_words, int64_t r, int64_t n, int bits,
+                       const float* scales, const int32_t* zeros, int64_t group,
+                       const void* x, int xdtype, float* y, void* stream);
 
 #ifdef __cplusplus
 }

@@ -58,6 +58,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_quantize_layer.argtypes = [vp, ci, i64, i64, i64, vp, i64, ci, ci, ci, i64, vp, i64, vp, vp, vp, i64, vp, vp, sz, vp]
     L.gptq_pack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     L.gptq_unpack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
+    L.gptq_dequantize_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, i64, vp]
+    L.gptq_matvec_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, vp, vp]
     for name in ("gptq_hessian_accumulate", "gptq_hessian_symmetrize", "gptq_damp_cholesky_inverse", "gptq_check_info",
                  "gptq_quantize_layer", "gptq_pack", "gptq_unpack"):
         getattr(L, name).restype = ci
@@ -184,3 +186,37 @@ def gptq_unpack(words: torch.Tensor, n: int, bits: int, codes: torch.Tensor) -> 
     _dev2d(words, "words", (torch.int32, torch.uint32))
     r = codes.shape[0]
     _check(lib().gptq_unpack(_ptr(words), _ld(words), r, n, bits, _ptr(codes), _ld(codes), _stream()))
+
+
+def _grids(scales: torch.Tensor, zeros: torch.Tensor, r: int, n: int, group: int) -> None:
+    G = n // group if group else 1
+    for t, name, dt in ((scales, "scales", torch.float32), (zeros, "zeros", torch.int32)):
+        if not t.is_cuda or t.dtype != dt or not t.is_contiguous() or t.numel() != r * G:
+            raise ValueError(f"{name} must be a dense GPU {dt} tensor of r x {G} entries")
+
+
+def gptq_dequantize_packed(words: torch.Tensor, n: int, bits: int, scales: torch.Tensor, zeros: torch.Tensor,
+                           group: int, out: torch.Tensor) -> None:
+    """out[r x n] (float16 or float32) = scale * (code - zero) of the packed layer."""
+    _dev2d(words, "words", (torch.int32, torch.uint32))
+    _dev2d(out, "out", (torch.float16, torch.float32))
+    r = out.shape[0]
+    if out.shape[1] != n or words.shape[0] != r:
+        raise ValueError("out must be r x n and words must have r rows")
+    _grids(scales, zeros, r, n, group)
+    _check(lib().gptq_dequantize_packed(_ptr(words), _ld(words), r, n, bits, _ptr(scales), _ptr(zeros), group,
+                                        _ptr(out), _DTYPE[out.dtype], _ld(out), _stream()))
+
+
+def gptq_matvec_packed(words: torch.Tensor, n: int, bits: int, scales: torch.Tensor, zeros: torch.Tensor,
+                       group: int, x: torch.Tensor, y: torch.Tensor) -> None:
+    """y[r] (float32) = Q x for the packed layer Q and a float16 or float32 vector x[n]."""
+    _dev2d(words, "words", (torch.int32, torch.uint32))
+    r = words.shape[0]
+    if not x.is_cuda or x.dim() != 1 or x.shape[0] != n or not x.is_contiguous() or x.dtype not in (torch.float16, torch.float32):
+        raise ValueError("x must be a dense GPU float16 or float32 vector of n entries")
+    if not y.is_cuda or y.dim() != 1 or y.shape[0] != r or not y.is_contiguous() or y.dtype != torch.float32:
+        raise ValueError("y must be a dense GPU float32 vector of r entries")
+    _grids(scales, zeros, r, n, group)
+    _check(lib().gptq_matvec_packed(_ptr(words), _ld(words), r, n, bits, _ptr(scales), _ptr(zeros), group,
+                                    _ptr(x), _DTYPE[x.dtype], _ptr(y), _stream()))

@@ -1,0 +1,441 @@
+// Consumers of the packed format (Section 4, "Practical Speedups", and the appendix on the benchmarking
+// setup): the full-matrix decompression used before a large-batch product, and the quantized-matrix times
+// full-precision-vector product of batch-1 generation, which dequantizes weights as it reads them and does
+// not quantize the vector.  Both are bound by HBM: the packed words are read once.
+//
+// Layout (same as pack.hip): per row, code k occupies bits [k*b, (k+1)*b) of a little-endian stream of uint32
+// words; 32 codes are exactly b words.  A weight is scale * (code - zero) with the scale and zero point of its
+// row (group == 0) or of its row's group k / group.
+#include "common.h"
+
+#include <hip/hip_fp16.h>
+
+namespace gptq {
+
+struct PackedArgs {
+    const uint32_t* words; int64_t ldp;
+    int64_t r, n, words_per_row;
+    const float* scales; const int32_t* zeros;
+    int64_t group, ngroups;      // group == 0: one grid per row (ngroups == 1)
+    int64_t rows_per_wg;         // matvec: rows a workgroup walks, a multiple of its row chunk
+};
+
+template <int BITS>
+__device__ __forceinline__ uint32_t code_at(const uint32_t (&w)[BITS], int i) {
+    const int pos = i * BITS, wi = pos >> 5, off = pos & 31;
+    uint32_t v = w[wi] >> off;
+    if (off + BITS > 32) v |= w[(wi + 1) % BITS] << (32 - off);      // % only keeps the index in range for the compiler
+    return v & ((1u << BITS) - 1u);
+}
+
+// ---- full-matrix decompression: one thread per 8 codes = 8 consecutive outputs (one 16-byte store of halves) ---
+// 8 codes are 8*b consecutive bits starting at a multiple of 8 bits: at most two words.  Neighbouring lanes
+// write neighbouring 16 bytes, and re-read words their neighbours also read (served by the vector cache).
+template <int BITS, typename OT>
+__global__ __launch_bounds__(256) void dequantize_kernel(PackedArgs a, OT* out, int64_t ldo, int64_t octets_per_row) {
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= a.r * octets_per_row) return;
+    const int64_t row = gid / octets_per_row, oc = gid % octets_per_row;
+    const int64_t k0 = oc * 8;
+    const int64_t bit0 = k0 * BITS, wi = bit0 >> 5;
+    const int off = (int)(bit0 & 31);
+    const uint32_t* p = a.words + row * a.ldp + wi;
+    const uint64_t lo = p[0];
+    const uint64_t hi = (off + 8 * BITS > 32 && wi + 1 < a.words_per_row) ? p[1] : 0u;
+    const uint32_t bits8 = (uint32_t)(((hi << 32) | lo) >> off);        // the 8 codes, code i at bits [i*b, (i+1)*b)
+    const bool one_grid = (a.group == 0) || (a.group % 8 == 0);
+    const int64_t gbase = row * a.ngroups;
+    float sc = 0.f, zf = 0.f;
+    if (one_grid) {
+        const int64_t gi = a.group ? k0 / a.group : 0;
+        sc = a.scales[gbase + gi];
+        zf = (float)a.zeros[gbase + gi];
+    }
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (!one_grid && k0 + i < a.n) {
+            const int64_t gi = (k0 + i) / a.group;
+            sc = a.scales[gbase + gi];
+            zf = (float)a.zeros[gbase + gi];
+        }
+        v[i] = sc * ((float)((bits8 >> (i * BITS)) & ((1u << BITS) - 1u)) - zf);
+    }
+    OT* dst = out + row * ldo + k0;
+    if ((k0 + 8 <= a.n) && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+        if constexpr (sizeof(OT) == 2) {
+            union { uint4 u; __half h[8]; } pk;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pk.h[i] = __float2half_rn(v[i]);
+            *reinterpret_cast<uint4*>(dst) = pk.u;
+        } else {
+            reinterpret_cast<float4*>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);
+            reinterpret_cast<float4*>(dst)[1] = make_float4(v[4], v[5], v[6], v[7]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (k0 + i < a.n) {
+                if constexpr (sizeof(OT) == 2) dst[i] = __float2half_rn(v[i]);
+                else dst[i] = v[i];
+            }
+    }
+}
+
+// ---- y = Q x, batch 1 -----------------------------------------------------------------------------------------
+// A workgroup of 4 wavefronts owns MV_ROWS rows.  A wavefront walks every fourth 2048-column segment of those
+// rows: a lane holds the 32 vector entries of its 32 columns in registers (read once per segment, shared by all
+// the rows), reads b consecutive words per row -- a wavefront reads 64*b*4 contiguous bytes of a row -- and
+// accumulates  scale * (sum code*x - zero * sum x)  in float32.  The lane sums of a row are reduced across the
+// wavefront with DPP-style shuffles and across the four wavefronts through LDS.
+constexpr int MV_ROWS = 4;
+constexpr int MV_SEG = 64 * 32;
+
+template <typename XT>
+__device__ __forceinline__ void load_x32(const XT* x, int64_t k0, int64_t n, float (&xf)[32]) {
+    if (k0 + 32 <= n && (reinterpret_cast<uintptr_t>(x + k0) & 15) == 0) {
+        if constexpr (sizeof(XT) == 2) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                union { uint4 u; __half h[8]; } pk;
+                pk.u = reinterpret_cast<const uint4*>(x + k0)[q];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) xf[8 * q + i] = __half2float(pk.h[i]);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const float4 f = reinterpret_cast<const float4*>(x + k0)[q];
+                xf[4 * q] = f.x; xf[4 * q + 1] = f.y; xf[4 * q + 2] = f.z; xf[4 * q + 3] = f.w;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            float v = 0.f;
+            if (k0 + i < n) {
+                if constexpr (sizeof(XT) == 2) v = __half2float(x[k0 + i]);
+                else v = x[k0 + i];
+            }
+            xf[i] = v;                       // columns past n contribute nothing
+        }
+    }
+}
+
+// GSUB = number of grids inside a lane's 32 columns: 1 (one grid per row, or groups of a multiple of 32), 2 (16), 4 (8)
+template <int BITS, int GSUB, typename XT>
+__global__ __launch_bounds__(256) void matvec_kernel(PackedArgs a, const XT* x, float* y) {
+    __shared__ float part[4][MV_ROWS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t nseg = (a.n + MV_SEG - 1) / MV_SEG;
+    constexpr int GL = 32 / GSUB;            // columns per grid inside the lane's 32
+    const int64_t row_end = min(((int64_t)blockIdx.x + 1) * a.rows_per_wg, a.r);
+    for (int64_t row0 = (int64_t)blockIdx.x * a.rows_per_wg; row0 < row_end; row0 += MV_ROWS) {
+    float acc[MV_ROWS];
+#pragma unroll
+    for (int rr = 0; rr < MV_ROWS; ++rr) acc[rr] = 0.f;
+    for (int64_t s = wave; s < nseg; s += 4) {
+        const int64_t k0 = s * MV_SEG + (int64_t)lane * 32;
+        if (k0 >= a.n) continue;
+        float xf[32];
+        load_x32<XT>(x, k0, a.n, xf);
+        float sx[GSUB];
+#pragma unroll
+        for (int j = 0; j < GSUB; ++j) {
+            float t = 0.f;
+#pragma unroll
+            for (int i = 0; i < GL; ++i) t += xf[j * GL + i];
+            sx[j] = t;
+        }
+        const int64_t w0 = (k0 >> 5) * BITS;
+        const int64_t g0 = a.group ? k0 / a.group : 0;
+#pragma unroll
+        for (int rr = 0; rr < MV_ROWS; ++rr) {
+            const int64_t row = min(row0 + rr, a.r - 1);         // rows past r repeat the last one and are dropped below
+            const uint32_t* p = a.words + row * a.ldp + w0;
+            uint32_t w[BITS];
+#pragma unroll
+            for (int i = 0; i < BITS; ++i) w[i] = (w0 + i < a.words_per_row) ? p[i] : 0u;
+#pragma unroll
+            for (int j = 0; j < GSUB; ++j) {
+                float dot = 0.f;
+#pragma unroll
+                for (int i = 0; i < GL; ++i) dot = fmaf((float)code_at<BITS>(w, j * GL + i), xf[j * GL + i], dot);
+                const int64_t gi = row * a.ngroups + min(g0 + j, a.ngroups - 1);
+                acc[rr] = fmaf(a.scales[gi], dot - (float)a.zeros[gi] * sx[j], acc[rr]);
+            }
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < MV_ROWS; ++rr) {
+        float v = acc[rr];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (lane == 0) part[wave][rr] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < MV_ROWS && row0 + threadIdx.x < a.r)
+        y[row0 + threadIdx.x] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+    __syncthreads();
+    }
+}
+
+// float16 vector, one grid per lane segment (one grid per row, or groups of a multiple of 32): two weights per
+// v_dot2_f32_f16, and codes become halves without a conversion.  With the exponent bits of 2^b or-ed in, a code
+// sitting at mantissa bits [10-b, 10) of a half IS the float16 number 2^b + code.  Two codes whose bit positions
+// differ by 16 (mod 32) sit at the same place of the two halves of a 32-bit word, so one shift puts both at
+// [10-b, 10) / [26-b, 26) and one and-or masks them and sets both exponents:
+//   b = 4: codes k and k+4 of a word;  b = 2: codes k and k+8 of a word;
+//   b = 3: codes k and k+16 of the 96-bit group are 48 bits apart -- low half of one word, high half of another,
+//          joined by one byte permute that serves four or five pairs; the two pairs whose codes straddle a
+//          16-bit boundary (5, 21 and 10, 26) are cut out one code at a time.
+// The vector's halves are paired the same way once per segment.  The dot products accumulate
+// sum (2^b + code) x in float32, and  sum (code - zero) x = that - (2^b + zero) sum x;  the offset is of the size
+// of the codes themselves, so the subtraction costs no accuracy worth naming.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+constexpr int MV2_ROWS = 4;
+
+struct PairSpec { int lo_word, hi_word, rel, k_lo, k_hi; };      // lo_word < 0: cut the two codes out one at a time
+template <int BITS> struct PairTable;
+template <> struct PairTable<4> {
+    static constexpr PairSpec at(int i) { return {i / 4, i / 4, 4 * (i % 4), 8 * (i / 4) + i % 4, 8 * (i / 4) + i % 4 + 4}; }
+};
+template <> struct PairTable<2> {
+    static constexpr PairSpec at(int i) { return {i / 8, i / 8, 2 * (i % 8), 16 * (i / 8) + i % 8, 16 * (i / 8) + i % 8 + 8}; }
+};
+template <> struct PairTable<3> {
+    static constexpr PairSpec at(int i) {
+        if (i < 5) return {0, 1, 3 * i, i, i + 16};                                   // k = 0..4
+        if (i < 9) return {2, 0, 3 * (i + 1) - 16, (i + 1) + 16, i + 1};              // k = 6..9
+        if (i < 14) return {1, 2, 3 * (i + 2) - 32, i + 2, (i + 2) + 16};             // k = 11..15
+        return i == 14 ? PairSpec{-1, -1, 0, 5, 21} : PairSpec{-1, -1, 0, 10, 26};
+    }
+};
+
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
+    uint32_t v;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(v) : "v"(a), "s"(mask), "v"(c));   // written out: the compiler spends two on it
+    return v;
+}
+
+// 32 bits of the stream of words w[0..BITS] (w[BITS] = 0) starting at bit `from` (may be negative: shifted in zeros)
+template <int BITS>
+__device__ __forceinline__ uint32_t stream_bits(const uint32_t (&w)[BITS + 1], int from) {
+    if (from < 0) return w[0] << (-from);
+    const int wi = from >> 5, sh = from & 31;
+    return sh ? __builtin_amdgcn_alignbit(w[wi + 1], w[wi], sh) : w[wi];
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __half* x, float* y) {
+    __shared__ float part[4][MV2_ROWS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int WANT = 10 - BITS;
+    constexpr uint32_t M = (1u << BITS) - 1u;
+    constexpr uint32_t MASK_LO = M << WANT, MASK_HI = M << (16 + WANT), MASK = MASK_LO | MASK_HI;
+    const uint32_t magic = 0x3C003C00u + (uint32_t)BITS * 0x04000400u;       // (2^b, 2^b) as two halves
+    const float offset = (float)(1 << BITS);
+    const int64_t nseg = (a.n + MV_SEG - 1) / MV_SEG;
+    const int64_t row_end = min(((int64_t)blockIdx.x + 1) * a.rows_per_wg, a.r);
+    for (int64_t row0 = (int64_t)blockIdx.x * a.rows_per_wg; row0 < row_end; row0 += MV2_ROWS) {
+    float acc[MV2_ROWS];
+#pragma unroll
+    for (int rr = 0; rr < MV2_ROWS; ++rr) acc[rr] = 0.f;
+    for (int64_t s = wave; s < nseg; s += 4) {
+        const int64_t k0 = s * MV_SEG + (int64_t)lane * 32;
+        if (k0 >= a.n) continue;
+        uint32_t xp[16];                                     // the lane's 32 vector entries, two halves per register
+        if (k0 + 32 <= a.n && (reinterpret_cast<uintptr_t>(x + k0) & 15) == 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint4 u = reinterpret_cast<const uint4*>(x + k0)[q];
+                xp[4 * q] = u.x; xp[4 * q + 1] = u.y; xp[4 * q + 2] = u.z; xp[4 * q + 3] = u.w;
+            }
+        } else {
+            const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t lo = (k0 + 2 * i < a.n) ? xb[k0 + 2 * i] : 0u;
+                const uint32_t hi = (k0 + 2 * i + 1 < a.n) ? xb[k0 + 2 * i + 1] : 0u;
+                xp[i] = lo | (hi << 16);                     // columns past n contribute nothing
+            }
+        }
+        float sx = 0.f;
+        half2v xq[16];                                       // the same entries paired like the codes
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            sx = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, xp[i]), __builtin_bit_cast(half2v, 0x3C003C00u), sx, false);
+            const PairSpec sp = PairTable<BITS>::at(i);
+            const uint32_t lo = (xp[sp.k_lo >> 1] >> (16 * (sp.k_lo & 1))) & 0xFFFFu;
+            const uint32_t hi = (sp.k_hi & 1) ? (xp[sp.k_hi >> 1] & 0xFFFF0000u) : (xp[sp.k_hi >> 1] << 16);
+            xq[i] = __builtin_bit_cast(half2v, lo | hi);
+        }
+        const int64_t w0 = (k0 >> 5) * BITS;
+        const int64_t g0 = a.group ? k0 / a.group : 0;
+        uint32_t w[MV2_ROWS][BITS + 1];
+        int64_t gi[MV2_ROWS];
+#pragma unroll
+        for (int rr = 0; rr < MV2_ROWS; ++rr) {
+            const int64_t row = min(row0 + rr, a.r - 1);     // rows past r repeat the last one and are dropped below
+            const uint32_t* p = a.words + row * a.ldp + w0;
+            if (w0 + BITS <= a.words_per_row) {              // the usual case: one load of b words (4-byte aligned)
+                struct __attribute__((packed, aligned(4))) Words { uint32_t v[BITS]; };
+                const Words t = *reinterpret_cast<const Words*>(p);
+#pragma unroll
+                for (int i = 0; i < BITS; ++i) w[rr][i] = t.v[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < BITS; ++i) w[rr][i] = (w0 + i < a.words_per_row) ? p[i] : 0u;
+            }
+            w[rr][BITS] = 0u;
+            gi[rr] = row * a.ngroups + g0;
+        }
+#pragma unroll
+        for (int rr = 0; rr < MV2_ROWS; ++rr) {
+            // two interleaved chains per row, so consecutive dot products do not wait for each other
+            float d0 = 0.f, d1 = 0.f;
+            uint32_t joined[3] = {0u, 0u, 0u};
+            if constexpr (BITS == 3) {
+                joined[0] = __builtin_amdgcn_perm(w[rr][1], w[rr][0], 0x07060100u);      // low half of w0, high half of w1
+                joined[1] = __builtin_amdgcn_perm(w[rr][0], w[rr][2], 0x07060100u);      // low half of w2, high half of w0
+                joined[2] = __builtin_amdgcn_perm(w[rr][2], w[rr][1], 0x07060100u);      // low half of w1, high half of w2
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const PairSpec sp = PairTable<BITS>::at(i);
+                uint32_t v;
+                if (sp.lo_word < 0) {
+                    const uint32_t ta = stream_bits<BITS>(w[rr], BITS * sp.k_lo - WANT);
+                    const uint32_t tb = stream_bits<BITS>(w[rr], BITS * sp.k_hi - (16 + WANT));
+                    v = and_or(tb, MASK_HI, and_or(ta, MASK_LO, magic));
+                } else {
+                    uint32_t m;
+                    if (sp.lo_word == sp.hi_word) m = w[rr][sp.lo_word];
+                    else m = joined[sp.lo_word == 0 ? 0 : (sp.lo_word == 2 ? 1 : 2)];
+                    const uint32_t t = sp.rel >= WANT ? (m >> (sp.rel - WANT)) : (m << (WANT - sp.rel));
+                    v = and_or(t, MASK, magic);
+                }
+                if (i & 1) d1 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, v), xq[i], d1, false);
+                else       d0 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, v), xq[i], d0, false);
+            }
+            acc[rr] = fmaf(a.scales[gi[rr]], (d0 + d1) - (offset + (float)a.zeros[gi[rr]]) * sx, acc[rr]);
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < MV2_ROWS; ++rr) {
+        float v = acc[rr];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (lane == 0) part[wave][rr] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < MV2_ROWS && row0 + threadIdx.x < a.r)
+        y[row0 + threadIdx.x] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+    __syncthreads();
+    }
+}
+
+__global__ void zero_vector_kernel(float* y, int64_t r) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < r) y[i] = 0.f;
+}
+
+static int check_packed(const char* who, const uint32_t* words, int64_t ldp, int64_t r, int64_t n, int bits,
+                        const float* scales, const int32_t* zeros, int64_t group, PackedArgs* a) {
+    if (r < 0 || n < 0) return fail(GPTQ_ERR_INVALID_ARG, "%s: negative size", who);
+    if (bits < 2 || bits > 4) return fail(GPTQ_ERR_INVALID_ARG, "%s: bits must be 2, 3 or 4 (got %d)", who, bits);
+    if (group < 0) return fail(GPTQ_ERR_INVALID_ARG, "%s: negative group", who);
+    if (group > 0 && n % group) return fail(GPTQ_ERR_INVALID_ARG, "%s: n must be a multiple of the group size", who);
+    if (r == 0 || n == 0) return GPTQ_OK;
+    if (!words || !scales || !zeros) return fail(GPTQ_ERR_INVALID_ARG, "%s: null pointer", who);
+    const int64_t wpr = (n * bits + 31) / 32;
+    if (ldp < wpr) return fail(GPTQ_ERR_INVALID_ARG, "%s: word pitch smaller than ceil(n*bits/32)", who);
+    a->words = words; a->ldp = ldp; a->r = r; a->n = n; a->words_per_row = wpr;
+    a->scales = scales; a->zeros = zeros; a->group = group; a->ngroups = group ? n / group : 1;
+    return -1;
+}
+
+}  // namespace gptq
+
+using namespace gptq;
+
+extern "C" int gptq_dequantize_packed(const uint32_t* words, int64_t ldp, int64_t r, int64_t n, int bits,
+                                      const float* scales, const int32_t* zeros, int64_t group,
+                                      void* out, int odtype, int64_t ldo, void* stream) {
+    PackedArgs a{};
+    const int rc = check_packed("dequantize_packed", words, ldp, r, n, bits, scales, zeros, group, &a);
+    if (rc >= 0) return rc;
+    if (odtype != GPTQ_F16 && odtype != GPTQ_F32) return fail(GPTQ_ERR_INVALID_ARG, "dequantize_packed: output type must be float16 or float32");
+    if (!out) return fail(GPTQ_ERR_INVALID_ARG, "dequantize_packed: null pointer");
+    if (ldo < n) return fail(GPTQ_ERR_INVALID_ARG, "dequantize_packed: ldo < n");
+    const int64_t g32 = (n + 7) / 8;               // octets of codes per row
+    if (r * g32 > (int64_t)0x7fffffff * 256) return fail(GPTQ_ERR_UNSUPPORTED, "dequantize_packed: too large");
+    const unsigned blocks = (unsigned)ceil_div(r * g32, 256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define GPTQ_DQ(B)                                                                                                              \
+    if (odtype == GPTQ_F16) hipLaunchKernelGGL((dequantize_kernel<B, __half>), dim3(blocks), dim3(256), 0, s, a, static_cast<__half*>(out), ldo, g32); \
+    else hipLaunchKernelGGL((dequantize_kernel<B, float>), dim3(blocks), dim3(256), 0, s, a, static_cast<float*>(out), ldo, g32)
+    if (bits == 2) { GPTQ_DQ(2); } else if (bits == 3) { GPTQ_DQ(3); } else { GPTQ_DQ(4); }
+#undef GPTQ_DQ
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}
+
+// Rows are dealt to about eight workgroups per CU (what the kernels' registers allow) in equal shares, each a
+// multiple of the kernel's row chunk: with one chunk per workgroup the last round of a large launch would run
+// the chip partly empty.
+static int64_t rows_per_workgroup(int64_t r, int chunk) {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+        else cus = 256;
+    }
+    const int64_t slots = (int64_t)cus * 8;
+    return (int64_t)round_up((size_t)ceil_div(r, slots), (size_t)chunk);
+}
+
+template <int BITS, typename XT>
+static void launch_matvec(PackedArgs a, const XT* x, float* y, hipStream_t s) {
+    const int gsub = (a.group == 0 || a.group % 32 == 0) ? 1 : (int)(32 / a.group);
+    if constexpr (sizeof(XT) == 2) {
+        if (gsub == 1) {
+            a.rows_per_wg = rows_per_workgroup(a.r, MV2_ROWS);
+            hipLaunchKernelGGL((matvec_dot2_kernel<BITS>), dim3((unsigned)ceil_div(a.r, a.rows_per_wg)), dim3(256), 0, s, a, x, y);
+            return;
+        }
+    }
+    a.rows_per_wg = rows_per_workgroup(a.r, MV_ROWS);
+    const unsigned blocks = (unsigned)ceil_div(a.r, a.rows_per_wg);
+    if (gsub == 1) hipLaunchKernelGGL((matvec_kernel<BITS, 1, XT>), dim3(blocks), dim3(256), 0, s, a, x, y);
+    else if (gsub == 2) hipLaunchKernelGGL((matvec_kernel<BITS, 2, XT>), dim3(blocks), dim3(256), 0, s, a, x, y);
+    else hipLaunchKernelGGL((matvec_kernel<BITS, 4, XT>), dim3(blocks), dim3(256), 0, s, a, x, y);
+}
+
+extern "C" int gptq_matvec_packed(const uint32_t* words, int64_t ldp, int64_t r, int64_t n, int bits,
+                                  const float* scales, const int32_t* zeros, int64_t group,
+                                  const void* x, int xdtype, float* y, void* stream) {
+    PackedArgs a{};
+    const int rc = check_packed("matvec_packed", words, ldp, r, n, bits, scales, zeros, group, &a);
+    if (rc >= 0) {
+        if (rc == GPTQ_OK && r > 0 && n == 0) {          // an empty sum: y = 0
+            if (!y) return fail(GPTQ_ERR_INVALID_ARG, "matvec_packed: null pointer");
+            hipLaunchKernelGGL(zero_vector_kernel, dim3((unsigned)ceil_div(r, 256)), dim3(256), 0, static_cast<hipStream_t>(stream), y, r);
+            GPTQ_LAUNCH_CHECK();
+        }
+        return rc;
+    }
+    if (xdtype != GPTQ_F16 && xdtype != GPTQ_F32) return fail(GPTQ_ERR_INVALID_ARG, "matvec_packed: vector type must be float16 or float32");
+    if (!x || !y) return fail(GPTQ_ERR_INVALID_ARG, "matvec_packed: null pointer");
+    if (group > 0 && group % 32 && group != 8 && group != 16)
+        return fail(GPTQ_ERR_UNSUPPORTED, "matvec_packed: group size %lld not built (8, 16 or a multiple of 32)", (long long)group);
+    if (ceil_div(r, MV_ROWS) > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "matvec_packed: too many rows");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define GPTQ_MV(B)                                                                              \
+    if (xdtype == GPTQ_F16) launch_matvec<B, __half>(a, static_cast<const __half*>(x), y, s);   \
+    else launch_matvec<B, float>(a, static_cast<const float*>(x), y, s)
+    if (bits == 2) { GPTQ_MV(2); } else if (bits == 3) { GPTQ_MV(3); } else { GPTQ_MV(4); }
+#undef GPTQ_MV
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}

@@ -63,6 +63,14 @@ def test_argument_validation_happens_on_the_host():
     assert L.gptq_unpack(one, 6, 2, 64, 3, None, 64, None) == INVALID
     assert L.gptq_pack(one, 64, 0, 64, 3, one, 6, None) == OK
     assert L.gptq_check_info(None, None, None) == INVALID
+    dq = lambda **kw: L.gptq_dequantize_packed(one, kw.get("ldp", 6), kw.get("r", 2), kw.get("n", 64), kw.get("bits", 3), one, one,
+                                               kw.get("group", 0), kw.get("out", one), kw.get("od", 0), kw.get("ldo", 64), None)
+    assert dq(bits=5) == INVALID and dq(ldp=5) == INVALID and dq(group=48) == INVALID and dq(od=1) == INVALID
+    assert dq(ldo=32) == INVALID and dq(out=None) == INVALID and dq(r=0) == OK
+    mv = lambda **kw: L.gptq_matvec_packed(one, kw.get("ldp", 6), kw.get("r", 2), kw.get("n", 64), kw.get("bits", 3), one, one,
+                                           kw.get("group", 0), kw.get("x", one), kw.get("xd", 0), kw.get("y", one), None)
+    assert mv(bits=1) == INVALID and mv(ldp=2) == INVALID and mv(xd=1) == INVALID and mv(x=None) == INVALID
+    assert mv(group=4) == UNSUPPORTED and mv(group=-8) == INVALID and mv(r=0) == OK
 
 
 def test_missing_library_fails_loudly(tmp_path):
