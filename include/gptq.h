@@ -69,6 +69,17 @@ GPTQ_API size_t gptq_hessian_accumulate_workspace_bytes(int64_t n, int64_t t, in
 GPTQ_API int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int xdtype,
                             int64_t n, int64_t t, int64_t ldx, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Step 1 for token-major activations: X is [t x n] (one row per token, channels contiguous, ldx >= n) -- the
+ * layout of a layer's input in a framework -- of type float16 or bfloat16; H[upper] += 2 X^T X.  Same arithmetic
+ * and result as gptq_hessian_accumulate on the transposed chunk with its workspace.  The workspace is required:
+ * gptq_hessian_accumulate_token_major_workspace_bytes(n, t, xdtype) bytes, 256-byte aligned.  X 16-byte
+ * aligned, ldx % 8 == 0.  float32 activations are not taken in this layout (GPTQ_ERR_UNSUPPORTED).
+ */
+GPTQ_API size_t gptq_hessian_accumulate_token_major_workspace_bytes(int64_t n, int64_t t, int xdtype);
+GPTQ_API int gptq_hessian_accumulate_token_major(float* H, int64_t ldh, const void* X, int xdtype,
+                                        int64_t n, int64_t t, int64_t ldx, void* ws, size_t ws_bytes, void* stream);
+
 /* Copies the upper triangle of H onto the lower one (H[j][i] = H[i][j] for j > i). */
 GPTQ_API int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* stream);
 

@@ -49,6 +49,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_hessian_accumulate_workspace_bytes.argtypes = [i64, i64, ci]
     L.gptq_hessian_accumulate_workspace_bytes.restype = sz
     L.gptq_hessian_symmetrize.argtypes = [vp, i64, i64, vp]
+    L.gptq_hessian_accumulate_token_major.argtypes = [vp, i64, vp, ci, i64, i64, i64, vp, sz, vp]
+    L.gptq_hessian_accumulate_token_major_workspace_bytes.argtypes = [i64, i64, ci]
+    L.gptq_hessian_accumulate_token_major_workspace_bytes.restype = sz
     L.gptq_damp_cholesky_inverse_workspace_bytes.argtypes = [i64]
     L.gptq_damp_cholesky_inverse_workspace_bytes.restype = sz
     L.gptq_damp_cholesky_inverse.argtypes = [vp, i64, i64, f32, vp, sz, vp, vp]
@@ -121,6 +124,23 @@ def gptq_hessian_accumulate(H: torch.Tensor, X: torch.Tensor, ws: torch.Tensor |
         raise ValueError("ws must be a GPU uint8 tensor")
     _check(lib().gptq_hessian_accumulate(_ptr(H), _ld(H), _ptr(X), _DTYPE[X.dtype], n, t, _ld(X),
                                          _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
+
+
+def gptq_hessian_accumulate_token_major_workspace_bytes(n: int, t: int, dtype: torch.dtype = torch.float16) -> int:
+    return lib().gptq_hessian_accumulate_token_major_workspace_bytes(n, t, _DTYPE[dtype])
+
+
+def gptq_hessian_accumulate_token_major(H: torch.Tensor, X: torch.Tensor, ws: torch.Tensor) -> None:
+    """H[upper] += 2 X^T X for one chunk X [t x n] (channels contiguous); ws: uint8 workspace (required)."""
+    _dev2d(H, "H", (torch.float32,))
+    _dev2d(X, "X", (torch.float16, torch.bfloat16))
+    t, n = X.shape
+    if H.shape != (n, n):
+        raise ValueError("H must be n x n")
+    if ws is None or ws.dtype != torch.uint8 or not ws.is_cuda:
+        raise ValueError("ws must be a GPU uint8 tensor")
+    _check(lib().gptq_hessian_accumulate_token_major(_ptr(H), _ld(H), _ptr(X), _DTYPE[X.dtype], n, t, _ld(X),
+                                                     _ptr(ws), ws.numel(), _stream()))
 
 
 def gptq_hessian_symmetrize(H: torch.Tensor) -> None:

@@ -202,6 +202,37 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint16_t* X, int64_t 
     }
 }
 
+// The same repacked chunk from token-major activations X[t x n] (channels contiguous: the layout a framework's
+// layer input has).  A workgroup turns one panel step -- 32 tokens x 256 channels, read as 512-byte runs of
+// each token -- around in LDS and writes it as one contiguous 16 KB block.
+__global__ __launch_bounds__(256) void repack_token_major_kernel(const uint16_t* X, int64_t ldx, int64_t n, int64_t t, int64_t nsteps,
+                                                                 unsigned char* Xb) {
+    __shared__ uint16_t tile[256][32 + 2];               // [channel][token], padded against bank conflicts
+    const int64_t panel = blockIdx.x, step = blockIdx.y;
+    const int64_t ch0 = panel * 256, tok0 = step * 32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = threadIdx.x + 256 * i;
+        const int tk = q >> 5, c8 = (q & 31) * 8;        // token in the step, first of 8 channels
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (tok0 + tk < t) v = load8h_guard(X + (tok0 + tk) * ldx + ch0 + c8, n - (ch0 + c8));    // zeros past the last channel
+        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[c8 + e][tk] = (uint16_t)(wds[e >> 1] >> (16 * (e & 1)));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = threadIdx.x + 256 * i;
+        const int r = q >> 2, c = q & 3;                 // channel in the panel, 16-byte chunk (8 tokens) of its row
+        uint32_t wds[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wds[e] = (uint32_t)tile[r][c * 8 + 2 * e] | ((uint32_t)tile[r][c * 8 + 2 * e + 1] << 16);
+        const int pos = c ^ ((r >> 1) & 3);
+        *reinterpret_cast<uint4*>(Xb + (panel * nsteps + step) * 16384 + r * 64 + pos * 16) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+    }
+}
+
 // ---- 256 x 256 tile, 4 wavefronts of 128 x 128, panels copied global -> LDS directly ----------------
 // Each wavefront keeps a 4 x 4 grid of 32x32 accumulators (256 registers), which halves the LDS reads
 // per MFMA compared with 128 x 64 wavefront tiles.  The two panels of a 32-token step (2 x 16 KB) go
@@ -406,7 +437,7 @@ static void syrk_schedule(SyrkArgs& g, int BT) {
 }
 
 template <bool IS_BF16>
-static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s) {
+static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s, bool token_major = false) {
     syrk_schedule(g, 256);
     g.per_xcd = ceil_div(ceil_div(g.total, 32), NXCD) * 32;      // whole patches of 32 slots per XCD
     const int64_t blocks = g.per_xcd * NXCD;
@@ -415,9 +446,13 @@ static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s) {
     if (ws) {
         g.nsteps = ceil_div(ceil_div(g.t, DK), 5) * 5;           // zero-padded to whole trips of the 5-stage loop
         const int64_t rgroups = (int64_t)g.nt * 16, tgroups = ceil_div(g.nsteps, 16);
-        if (tgroups > 65535) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: chunk too long for the repack grid (split the call)");
-        hipLaunchKernelGGL(repack_kernel, dim3((unsigned)rgroups, (unsigned)tgroups), dim3(256), 0, s, g.X, g.ldx, g.n, g.t, g.nsteps,
-                           static_cast<unsigned char*>(ws));
+        if (tgroups > 65535 || g.nsteps > 65535) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: chunk too long for the repack grid (split the call)");
+        if (token_major)
+            hipLaunchKernelGGL(repack_token_major_kernel, dim3((unsigned)g.nt, (unsigned)g.nsteps), dim3(256), 0, s, g.X, g.ldx, g.n, g.t,
+                               g.nsteps, static_cast<unsigned char*>(ws));
+        else
+            hipLaunchKernelGGL(repack_kernel, dim3((unsigned)rgroups, (unsigned)tgroups), dim3(256), 0, s, g.X, g.ldx, g.n, g.t, g.nsteps,
+                               static_cast<unsigned char*>(ws));
         GPTQ_LAUNCH_CHECK();
         g.t = g.nsteps * DK;
         hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, true>), dim3((unsigned)blocks), dim3(256), 0, s, g);
@@ -524,6 +559,33 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
         return bf ? launch_syrk<true, 256, 2, 4>(gt, s) : launch_syrk<false, 256, 2, 4>(gt, s);
     }
     return GPTQ_OK;
+}
+
+static size_t syrk_token_major_ws_bytes(int64_t n, int64_t t) {
+    return (size_t)ceil_div(n, 256) * 256 * (size_t)(ceil_div(t, DMA_TOKENS) * DMA_TOKENS) * 2;
+}
+
+extern "C" size_t gptq_hessian_accumulate_token_major_workspace_bytes(int64_t n, int64_t t, int xdtype) {
+    if (n <= 0 || t <= 0 || xdtype == GPTQ_F32) return 0;
+    return syrk_token_major_ws_bytes(n, t);
+}
+
+extern "C" int gptq_hessian_accumulate_token_major(float* H, int64_t ldh, const void* X, int xdtype,
+                                                   int64_t n, int64_t t, int64_t ldx, void* ws, size_t ws_bytes, void* stream) {
+    if (n < 0 || t < 0) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate_token_major: negative size");
+    if (n == 0 || t == 0) return GPTQ_OK;
+    if (!H || !X) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate_token_major: null pointer");
+    if (ldh < n || ldx < n) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate_token_major: leading dimension smaller than the row length");
+    if (xdtype == GPTQ_F32) return fail(GPTQ_ERR_UNSUPPORTED, "hessian_accumulate_token_major: float32 activations are only taken channel-major");
+    if (xdtype != GPTQ_F16 && xdtype != GPTQ_BF16) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate_token_major: unknown xdtype %d", xdtype);
+    if (!aligned(H, 4)) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate_token_major: H misaligned");
+    if (!aligned(X, 16) || ldx % 8) return fail(GPTQ_ERR_INVALID_ARG, "hessian_accumulate_token_major: X must be 16-byte aligned with ldx %% 8 == 0");
+    if (!ws || !aligned(ws, 256) || ws_bytes < syrk_token_major_ws_bytes(n, t))
+        return fail(GPTQ_ERR_WORKSPACE, "hessian_accumulate_token_major: workspace missing, misaligned or too small");
+    SyrkArgs g{};
+    g.H = H; g.ldh = ldh; g.X = static_cast<const uint16_t*>(X); g.ldx = ldx; g.n = n; g.t = t;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return xdtype == GPTQ_BF16 ? launch_syrk_dma<true>(g, ws, s, true) : launch_syrk_dma<false>(g, ws, s, true);
 }
 
 extern "C" int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* stream) {

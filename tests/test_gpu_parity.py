@@ -80,6 +80,34 @@ def test_hessian_matches_oracle(case):
         assert _rel_fro(H2.double().cpu().numpy(), want) <= 1e-5
 
 
+@pytest.mark.parametrize("n,t,dtype", [(6416, 2056, torch.float16), (320, 1000, torch.float16), (200, 264, torch.bfloat16), (1, 1, torch.float16)])
+def test_hessian_token_major_matches_oracle(n, t, dtype):
+    # activations given as [tokens x channels], the layout of a layer input
+    _say(f"hessian token-major n={n} t={t} {dtype}")
+    X = _layer(configs.config3()[1], n, 8, t).x.tile(device="cuda").to(dtype)           # [n x t]
+    Xt = _padded(t, n, dtype, 8)
+    Xt.copy_(X.T)
+    ws = torch.empty(g.gptq_hessian_accumulate_token_major_workspace_bytes(n, t, dtype), dtype=torch.uint8, device="cuda")
+    H = _padded(n, n, torch.float32, 4)
+    g.gptq_hessian_accumulate_token_major(H, Xt, ws)
+    g.gptq_hessian_accumulate_token_major(H, Xt, ws)                                    # accumulates
+    g.gptq_hessian_symmetrize(H)
+    want = 2.0 * O.hessian(X.double().cpu().numpy())
+    err = _rel_fro(H.double().cpu().numpy(), want)
+    _say(f"  rel_fro={err:.3e}")
+    assert err <= 1e-5
+    nbytes = g.gptq_hessian_accumulate_workspace_bytes(n, t, dtype)
+    if nbytes:      # the channel-major call with a workspace repacks to the very same bytes: identical sums
+        H2 = _padded(n, n, torch.float32, 4)
+        ws2 = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        g.gptq_hessian_accumulate(H2, X, ws2)
+        g.gptq_hessian_accumulate(H2, X, ws2)
+        g.gptq_hessian_symmetrize(H2)
+        assert torch.equal(H2, H)
+    with pytest.raises(g.GptqError):
+        g.gptq_hessian_accumulate_token_major(H, Xt, torch.empty(256, dtype=torch.uint8, device="cuda")[:8])
+
+
 def test_hessian_exact_on_small_integers_and_chunked():
     # products and sums of small integers are exact in float32: the kernel must match bit for bit,
     # whatever the chunking of the token axis

@@ -41,6 +41,13 @@ def test_argument_validation_happens_on_the_host():
     assert L.gptq_hessian_accumulate(one, 8, one, 0, 8, 12, 12, None, 0, None) == INVALID        # ldx % 8
     assert "ldx" in _err()
     assert L.gptq_hessian_accumulate(one, 8, one, 0, 0, 8, 8, None, 0, None) == OK               # empty is a no-op
+    tm = L.gptq_hessian_accumulate_token_major
+    assert tm(one, 8, one, 0, 8, 16, 4, one, 1 << 30, None) == INVALID                           # ldx < n
+    assert tm(one, 8, one, 2, 8, 16, 8, one, 1 << 30, None) == UNSUPPORTED                       # float32
+    assert tm(one, 8, one, 0, 8, 16, 8, None, 0, None) == WORKSPACE
+    assert tm(one, 8, one, 0, 8, 16, 8, one, 64, None) == WORKSPACE
+    assert tm(one, 8, one, 0, 8, 0, 8, None, 0, None) == OK
+    assert g.gptq_hessian_accumulate_token_major_workspace_bytes(300, 100) == 512 * 160 * 2
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, -0.5, one, 1 << 30, one, None) == INVALID
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, one, 16, one, None) == WORKSPACE
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, None, 0, one, None) == WORKSPACE
