@@ -81,13 +81,13 @@ def cpu_baseline(lay, flops):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    n_h, t_h = min(lay.n, 4096), min(lay.x.m, 32768)
+    n_h, t_h = min(lay.n, 6144), min(lay.x.m, 32768)
     X = lay.x.tile(nrows=n_h, ncols=t_h).double().numpy()
     t0 = time.perf_counter(); H = O.hessian(X); th = time.perf_counter() - t0
     full_h = th * flops["hessian"] / (float(n_h) * (n_h + 1) * t_h)
     t0 = time.perf_counter(); U = O.hinv_cholesky_upper(O.damp(H, lay.percdamp)); tc = time.perf_counter() - t0
     full_c = tc * (lay.n / n_h) ** 3
-    r_q = min(lay.r, 64)
+    r_q = min(lay.r, 128)
     W = lay.weights(nrows=r_q).double().numpy()[:, :n_h]
     t0 = time.perf_counter(); out = O.gptq_quantize(W, U, lay.bits, lay.grid, lay.block, 0 if not lay.group else lay.group); tq = time.perf_counter() - t0
     full_q = tq * (lay.r / r_q) * (lay.n / n_h) ** 2
