@@ -220,7 +220,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) voi
 // MFMAs of an octet q consume element i = 0..3 of those reads -- the MFMA's k pairing becomes
 // (8q+i, 8q+4+i), the same for A and B, which is all a dot product needs.  For B given as [K x N] the
 // stage holds [16 k][128 n] linearly and the matching values are read with ds_read_b32.
-// While step k is multiplied the copies of steps k+1..k+3 are in flight; one bare s_barrier per step.
+// While step k is multiplied, step k+1 has landed (its first fragments are read before step k ends), step
+// k+2 is in flight and step k+3 is being issued; one bare s_barrier per step.
 constexpr int LM = 256, LN = 128, LK = 16;
 constexpr int LA_BYTES = LM * LK * 4, LB_BYTES = LN * LK * 4, LSTAGE = LA_BYTES + LB_BYTES;
 
