@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--layer", default="opt175b_fc2", help="opt175b_fc2 (headline) | opt175b_fc1 | opt6.7b_attn | bloom176b_qkv_2bit_g128 | "
-                         "bloom176b_out_ternary_g128 | opt175b_q | tiny")
+                         "bloom176b_out_ternary_g128 | opt175b_q | tiny | opt175b_block (all six linears of a block)")
     ap.add_argument("--tokens", type=int, default=0, help="calibration tokens (default: the layer's own, 262144)")
     ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptq_hessian_accumulate call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -102,11 +102,76 @@ def cpu_baseline(lay, flops):
     }
 
 
+def bench_block(a):
+    """--layer opt175b_block: the six linears of one OPT-175B-shaped decoder block in sequence (q, k, v share one
+    Hessian), 3-bit and 4-bit; prints per-layer times and the block total as one JSON line."""
+    import torch
+    import paper_2210_17323_amd as g
+    from paper_2210_17323_amd import solver as S
+    from workloads import configs
+    g.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    m = a.tokens or configs.TOKENS
+    layers = configs.config5(m)
+    by_x = {}
+    for lay in layers:
+        by_x.setdefault(lay.x.tensor_id, []).append(lay)
+    per_bits = {}
+    shared = {}
+    for bits in (3, 4):
+        timings = {}
+        for xid, lays in by_x.items():
+            _, X = configs.materialize(replace_rows(lays[0], 1), dev)          # X only; weights come per layer below
+            group = []
+            for lay in lays:
+                W = torch.empty((lay.r, lay.n), dtype=lay.dtype, device=dev)
+                rows = max(1, (1 << 27) // lay.n)
+                for r0 in range(0, lay.r, rows):
+                    W[r0:r0 + rows] = lay.weights(row0=r0, nrows=min(rows, lay.r - r0), device=dev)
+                group.append((lay.name, W, lay))
+            t = {}
+            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk, m), timings=t)     # warm-up
+            t = {}
+            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk, m), timings=t)
+            names = "+".join(l.name for l in lays)
+            timings[f"{names}:hessian"] = t["group0:hessian"]
+            timings[f"{names}:damp_cholesky_inverse"] = t["group0:damp_cholesky_inverse"]
+            for lay in lays:
+                timings[f"{lay.name}:quantize_pack"] = t[f"{lay.name}:quantize_pack"]
+            del X, group
+            torch.cuda.empty_cache()
+        per_bits[bits] = timings
+    hu = sum(v for k, v in per_bits[3].items() if not k.endswith("quantize_pack"))
+    q3 = sum(v for k, v in per_bits[3].items() if k.endswith("quantize_pack"))
+    q4 = sum(v for k, v in per_bits[4].items() if k.endswith("quantize_pack"))
+    total3 = hu + q3
+    out = {
+        "metric": "gptq_block_solve_ms", "value": total3, "unit": "ms", "n_gpus": 1, "steps": 1, "warmup": 1,
+        "ms_per_step": total3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1); u8 codes", "data": "synthetic",
+        "config": {"workload": f"one OPT-175B-shaped decoder block: q, k, v, out 12288x12288, fc1 49152x12288, fc2 12288x49152, "
+                               f"{m} tokens, per-row grids, B=128; q/k/v share one Hessian"},
+        "per_layer_ms_3bit": {k: round(v, 3) for k, v in per_bits[3].items()},
+        "per_layer_ms_4bit": {k: round(v, 3) for k, v in per_bits[4].items()},
+        "block_total_ms": {"3bit": total3, "4bit": hu + q4, "3bit_then_4bit_sharing_H_and_U": hu + q3 + q4,
+                           "3bit_then_4bit_redoing_H_and_U": 2 * hu + q3 + q4},
+    }
+    print(json.dumps(out))
+
+
+def replace_rows(lay, r):
+    from dataclasses import replace
+    return replace(lay, r=r)
+
+
 def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the solver is a single-GPU path; --gpus must be 1)", file=sys.stderr)
         sys.exit(2)
+    if a.layer == "opt175b_block":
+        return bench_block(a)
     import torch
     import paper_2210_17323_amd as g
     from paper_2210_17323_amd import solver as S

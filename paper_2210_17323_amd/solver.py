@@ -1,5 +1,6 @@
-"""Convenience driver: allocates the device buffers with PyTorch and walks one layer through the
-four C-ABI calls.  Every arithmetic step happens inside the library's HIP kernels."""
+"""Convenience driver: allocates the device buffers with PyTorch and walks one layer -- or the linear layers
+of one transformer block -- through the C-ABI calls.  Every arithmetic step happens inside the library's HIP
+kernels."""
 from __future__ import annotations
 
 from dataclasses import dataclass
@@ -64,3 +65,44 @@ def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", 
         packed = torch.empty((r, B.packed_words_per_row(n, pbits)), dtype=torch.int32, device=dev)
         B.gptq_pack(codes, pbits, packed)
     return LayerResult(codes, scales, zeros, half, Wq, packed)
+
+
+def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bool = False, timings: dict | None = None):
+    """The layers of one block, quantized in sequence (Section 4, Setup: a block's inputs are collected, its
+    layers quantized, then the next block).  `groups` is a list of (X, layers): X [n x m] are the input
+    activations shared by `layers`, a list of (name, W, settings) with settings an object carrying
+    bits / grid / block / group / percdamp (e.g. workloads.configs.Layer).  Layers that share an input share
+    one Hessian and one factor U.  Returns {name: LayerResult}; if `timings` is a dict it receives, per group,
+    the milliseconds of the Hessian and of the factorisation, and per layer those of Alg. 1 plus packing
+    (CUDA events on the current stream)."""
+    out = {}
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+    for gi, (X, layers) in enumerate(groups):
+        n = X.shape[0]
+        e = [ev(), ev(), ev()]
+        e[0].record()
+        H = new_hessian(n, X.device)
+        accumulate(H, X, chunk)
+        e[1].record()
+        U = cholesky_inverse(H, layers[0][2].percdamp)
+        e[2].record()
+        marks.append((f"group{gi}:hessian", e[0], e[1]))
+        marks.append((f"group{gi}:damp_cholesky_inverse", e[1], e[2]))
+        ws = None
+        for name, W, lay in layers:
+            b = lay.bits if bits is None else bits
+            need = B.gptq_quantize_layer_workspace_bytes(W.shape[0], n, lay.block, lay.group)
+            if ws is None or ws.numel() < need:
+                ws = torch.empty(need, dtype=torch.uint8, device=X.device)
+            q0, q1 = ev(), ev()
+            q0.record()
+            out[name] = quantize(W, U, b, lay.grid, lay.block, lay.group, want_Wq=want_Wq, pack=True, ws=ws)
+            q1.record()
+            marks.append((f"{name}:quantize_pack", q0, q1))
+        del H, U, ws
+    if timings is not None:
+        torch.cuda.synchronize()
+        for key, a, b in marks:
+            timings[key] = a.elapsed_time(b)
+    return out

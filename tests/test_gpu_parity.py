@@ -303,6 +303,30 @@ def test_whole_path_matches_oracle(which):
     assert ex_g < rtn
 
 
+def test_block_driver_shares_hessians_and_matches_oracle():
+    # a scaled twin of the decoder-block workload: q, k, v share one input (one Hessian, one U), out has its own
+    c5 = configs.config5()
+    n, m = 384, 6144
+    xa = type(c5[0].x)(**{**c5[0].x.__dict__, "n": n, "m": m, "n_outliers": 1})
+    xo = type(c5[3].x)(**{**c5[3].x.__dict__, "n": n, "m": m, "n_outliers": 1})
+    lays = [type(l)(**{**l.__dict__, "r": r, "n": n, "x": x}) for l, r, x in
+            ((c5[0], 96, xa), (c5[1], 64, xa), (c5[2], 130, xa), (c5[3], 72, xo))]
+    Xa, Xo = xa.tile(device="cuda"), xo.tile(device="cuda")
+    groups = [(Xa, [(l.name, l.weights(device="cuda"), l) for l in lays[:3]]), (Xo, [(lays[3].name, lays[3].weights(device="cuda"), lays[3])])]
+    timings = {}
+    res = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, timings=timings)
+    assert set(res) == {"q", "k", "v", "out"}
+    assert {"group0:hessian", "group0:damp_cholesky_inverse", "group1:hessian", "q:quantize_pack", "out:quantize_pack"} <= set(timings)
+    for X, ls in ((Xa, lays[:3]), (Xo, lays[3:])):
+        Hd = O.damp(O.hessian(X.double().cpu().numpy()))
+        U = O.hinv_cholesky_upper(Hd)
+        for l in ls:
+            W64 = l.weights().double().numpy()
+            ora = O.gptq_quantize(W64, U, 4, l.grid, l.block, l.group)
+            _compare_quant(res[l.name], ora, W64, Hd, l.group, n, f"block:{l.name}")
+            assert np.array_equal(res[l.name].packed.cpu().numpy().view(np.uint32), O.pack_codes(res[l.name].codes.cpu().numpy(), 4))
+
+
 def test_empty_inputs_are_no_ops():
     H = torch.zeros((0, 0), dtype=torch.float32, device="cuda")
     X = torch.zeros((0, 8), dtype=torch.float16, device="cuda")
