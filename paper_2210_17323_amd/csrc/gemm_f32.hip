@@ -210,8 +210,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) voi
     else          gemm_tile<B_IS_NK, true>(g, m0, n0, As, Bs);
 }
 
-// ---- large-tile variant: 256 x 128 tile, operands copied global -> LDS directly, 4 stages ---------------
-// Used when M % 256 == 0, N % 128 == 0 and K % 64 == 0.  8 wavefronts, each 64 x 64 = 2 x 2 MFMA tiles.
+// ---- large-tile variants: 256 x 128 or 256 x 256 tile, operands copied global -> LDS directly, 4 stages ----
+// Used when M % 256 == 0, N % 128 == 0 (256 for the wide tile) and K % 64 == 0.  8 wavefronts, each 64 x 64 = 2 x 2 MFMA tiles.
 // A stage holds 16 values of K: the A panel as [256 rows][16 floats] and, for B given as [N x K], the B
 // panel as [128 rows][16 floats]; rows are 64 bytes = 4 chunks of 16 bytes, and global_load_lds_dwordx4
 // lays 16 such rows down per instruction with the chunk index XOR-swizzled by (row / 2) % 4 on the global
@@ -223,14 +223,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) voi
 // While step k is multiplied, step k+1 has landed (its first fragments are read before step k ends), step
 // k+2 is in flight and step k+3 is being issued; one bare s_barrier per step.
 constexpr int LM = 256, LN = 128, LK = 16;
-constexpr int LA_BYTES = LM * LK * 4, LB_BYTES = LN * LK * 4, LSTAGE = LA_BYTES + LB_BYTES;
+constexpr int WIDE_MIN_TILES = 512;
+constexpr int LA_BYTES = LM * LK * 4;
 
-template <bool B_IS_NK>
+// WIDE: the tile is 256 x 256 and a wavefront owns 128 x 64 (4 x 2 MFMA tiles): a third fewer copy instructions and
+// a quarter fewer LDS reads per flop, and half as many tile prologues and C read-modify-writes per flop.
+template <bool B_IS_NK, bool WIDE>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_f32_dma_kernel(GemmArgs g) {
-    __shared__ __attribute__((aligned(16))) unsigned char st0[LSTAGE];
-    __shared__ __attribute__((aligned(16))) unsigned char st1[LSTAGE];
-    __shared__ __attribute__((aligned(16))) unsigned char st2[LSTAGE];
-    __shared__ __attribute__((aligned(16))) unsigned char st3[LSTAGE];
+    constexpr int TN_ = WIDE ? 256 : LN;                  // tile columns
+    constexpr int SM = WIDE ? 4 : 2;                      // 32-row MFMA tiles per wavefront
+    constexpr int NB = TN_ / 128;                         // B copies per wavefront per step
+    constexpr int CP = 2 + NB;                            // copies per wavefront per step
+    constexpr int LB_ = TN_ * LK * 4, LSTAGE_ = LA_BYTES + LB_;
+    __shared__ __attribute__((aligned(16))) unsigned char st0[LSTAGE_];
+    __shared__ __attribute__((aligned(16))) unsigned char st1[LSTAGE_];
+    __shared__ __attribute__((aligned(16))) unsigned char st2[LSTAGE_];
+    __shared__ __attribute__((aligned(16))) unsigned char st3[LSTAGE_];
 
     const int64_t w = blockIdx.x;
     const int64_t tile = (g.upper_only || g.a_upper_tri) ? w : (w % NXCD) * g.per_xcd + (w / NXCD);
@@ -238,51 +246,56 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int64_t per_group = (int64_t)GROUP_M * g.tiles_n;
     const int64_t grp = tile / per_group, rem = tile % per_group;
     const int rows_in_group = min(GROUP_M, g.tiles_m - (int)grp * GROUP_M);
-    const int64_t m0 = (grp * GROUP_M + rem % rows_in_group) * LM, n0 = (rem / rows_in_group) * LN;
-    if (g.upper_only && g.crow0 + m0 > g.ccol0 + n0 + (LN - 1)) return;
+    const int64_t m0 = (grp * GROUP_M + rem % rows_in_group) * LM, n0 = (rem / rows_in_group) * TN_;
+    if (g.upper_only && g.crow0 + m0 > g.ccol0 + n0 + (TN_ - 1)) return;
 
     // 8 wavefronts (two per SIMD, so one can issue MFMAs while the other waits on LDS or the barrier);
-    // wavefront (wm, wn) owns rows wm*64.., columns wn*64.. of the tile: 2 x 2 MFMA tiles.
+    // wavefront (wm, wn) owns rows wm*32*SM.., columns wn*64.. of the tile: SM x 2 MFMA tiles.
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = WIDE ? wave >> 2 : wave >> 1, wn = WIDE ? wave & 3 : wave & 1;
     const int l32 = lane & 31, lhi = lane >> 5;
 
-    // copies: A panel = 16 instructions of 16 rows (2 per wavefront); B panel = 8 instructions (1 per wavefront)
+    // copies: A panel = 16 instructions of 16 rows (2 per wavefront); B panel = 8 or 16 instructions (NB per wavefront):
+    // for B given as [N x K] 16 rows each, for [K x N] 1 KB of consecutive n (two k rows of 128, or one of 256)
     const int crow = lane >> 2, cchunk = (lane & 3) ^ ((lane >> 3) & 3);
     const float* srcA = g.A + (m0 + wave * 32 + crow) * g.lda + cchunk * 4;              // + i*16 rows, + k0
-    const float* srcB = B_IS_NK ? g.B + (n0 + wave * 16 + crow) * g.ldb + cchunk * 4       // + k0
-                                : g.B + (int64_t)(wave * 2 + lhi) * g.ldb + n0 + l32 * 4;   // + k0*ldb
+    const float* srcB = B_IS_NK ? g.B + (n0 + wave * 16 * NB + crow) * g.ldb + cchunk * 4  // + i*16 rows, + k0
+                      : WIDE    ? g.B + (int64_t)(wave * 2) * g.ldb + n0 + lane * 4        // + i k-rows, + k0*ldb
+                                : g.B + (int64_t)(wave * 2 + lhi) * g.ldb + n0 + l32 * 4;  // + k0*ldb
     auto issue_copies = [&](unsigned char* stage, int64_t k0) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcA + (int64_t)i * 16 * g.lda + k0),
                                              (__attribute__((address_space(3))) void*)(stage + (wave * 2 + i) * 1024), 16, 0, 0);
-        const float* sb = B_IS_NK ? srcB + k0 : srcB + k0 * g.ldb;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sb,
-                                         (__attribute__((address_space(3))) void*)(stage + LA_BYTES + wave * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const float* sb = B_IS_NK ? srcB + (int64_t)i * 16 * g.ldb + k0 : srcB + (k0 + i) * g.ldb;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sb,
+                                             (__attribute__((address_space(3))) void*)(stage + LA_BYTES + (wave * NB + i) * 1024), 16, 0, 0);
+        }
     };
 
-    floatx16 acc[2][2];
+    floatx16 acc[SM][2];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < SM; ++s)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[s][t][i] = 0.f;
 
-    const int rowA = (wm * 64 + l32) * 64;                       // + s * 2048
+    const int rowA = (wm * 32 * SM + l32) * 64;                  // + s * 2048
     const int rowB = LA_BYTES + (wn * 64 + l32) * 64;            // NK: + t * 2048
     const int swz = (l32 >> 1) & 3;
-    const int colB = LA_BYTES + (wn * 64 + l32) * 4;             // KN: + t * 128 + krow * 512
+    const int colB = LA_BYTES + (wn * 64 + l32) * 4;             // KN: + t * 128 + krow * TN_ * 4
     // One 16-deep step out of `cur`.  The fragments of its first 8 k are already in registers (fetched at the
-    // end of the previous step); those of the second 8 are read from LDS while the first 16 MFMAs run, and
-    // the first fragments of the next step (`nxt`, whose copies have landed) while the second 16 run.
-    float4 a[2][2];
+    // end of the previous step); those of the second 8 are read from LDS while the first half's MFMAs run, and
+    // the first fragments of the next step (`nxt`, whose copies have landed) while the second half's run.
+    float4 a[2][SM];
     float bv[2][2][4];
     auto fetch = [&](const unsigned char* st, int q) {
         const int co = ((2 * q + lhi) ^ swz) << 4;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) a[q][s] = *reinterpret_cast<const float4*>(st + rowA + s * 2048 + co);
+        for (int s = 0; s < SM; ++s) a[q][s] = *reinterpret_cast<const float4*>(st + rowA + s * 2048 + co);
         if (B_IS_NK) {
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -294,14 +307,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    bv[q][t][i] = *reinterpret_cast<const float*>(st + colB + t * 128 + (8 * q + 4 * lhi + i) * 512);
+                    bv[q][t][i] = *reinterpret_cast<const float*>(st + colB + t * 128 + (8 * q + 4 * lhi + i) * (TN_ * 4));
         }
     };
     auto mfmas = [&](int q) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
+            for (int s = 0; s < SM; ++s) {
                 const float av = i == 0 ? a[q][s].x : (i == 1 ? a[q][s].y : (i == 2 ? a[q][s].z : a[q][s].w));
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
@@ -313,24 +326,24 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         mfmas(0);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x008, SM, 0);  // SM MFMAs
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
         }
         fetch(nxt, 0);
         mfmas(1);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, SM, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
-    // 3 copies per wavefront per step.  A step's barrier publishes the stage of the FOLLOWING step (the one
-    // `multiply` prefetches from at its end): vmcnt(3) = only the copies of the step after that may be in flight.
+    // CP copies per wavefront per step.  A step's barrier publishes the stage of the FOLLOWING step (the one
+    // `multiply` prefetches from at its end): vmcnt(CP) = only the copies of the step after that may be in flight.
     // Past the last step the copies re-read the last panels into a stage nobody multiplies again.
     const int64_t ks0 = g.a_upper_tri ? m0 / LK : 0;             // A upper triangular: nothing left of the tile's rows
     const int64_t kend = g.K;
     auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur, const unsigned char* nxt) {
-        __builtin_amdgcn_s_waitcnt(0x0F73);                     // vmcnt(3)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | CP);                // vmcnt(CP)
         asm volatile("s_barrier" ::: "memory");
         issue_copies(refill, min(k_refill, kend - LK));
         multiply(cur, nxt);
@@ -338,7 +351,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     issue_copies(st0, ks0 * LK);
     issue_copies(st1, (ks0 + 1) * LK);
     issue_copies(st2, (ks0 + 2) * LK);
-    __builtin_amdgcn_s_waitcnt(0x0F76);                         // vmcnt(6): step 0 has landed
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * CP));              // vmcnt(2 CP): step 0 has landed
     asm volatile("s_barrier" ::: "memory");
     fetch(st0, 0);
     for (int64_t k = ks0 * LK; k < kend; k += 4 * LK) {
@@ -350,10 +363,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __builtin_amdgcn_s_waitcnt(0x0F70);                         // drain the surplus copies before LDS is released
 
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < SM; ++s)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            float* cbase = g.C + (m0 + wm * 64 + s * 32 + 4 * lhi) * g.ldc + n0 + wn * 64 + t * 32 + l32;
+            float* cbase = g.C + (m0 + wm * 32 * SM + s * 32 + 4 * lhi) * g.ldc + n0 + wn * 64 + t * 32 + l32;
             float cv[16];
             if (!g.overwrite) {
 #pragma unroll
@@ -371,21 +384,31 @@ int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
     if (p.M <= 0 || p.N <= 0) return GPTQ_OK;
     if (!aligned(p.A, 16) || !aligned(p.B, 16) || (p.lda % 4) || (p.ldb % 4))
         return fail(GPTQ_ERR_INVALID_ARG, "gemm_f32: operands must be 16-byte aligned with leading dimensions that are multiples of 4");
+    if (p.a_upper_tri && p.K < p.M)
+        return fail(GPTQ_ERR_INVALID_ARG, "gemm_f32: an upper-triangular A needs K >= M (the K loop of a tile starts at its first row)");
     GemmArgs g;
     g.A = p.A; g.lda = p.lda; g.B = p.B; g.ldb = p.ldb; g.C = p.C; g.ldc = p.ldc;
     g.M = p.M; g.N = p.N; g.K = p.K < 0 ? 0 : p.K; g.alpha = p.alpha;
     g.overwrite = p.overwrite; g.upper_only = p.upper_only; g.crow0 = p.crow0; g.ccol0 = p.ccol0;
     g.a_upper_tri = p.a_upper_tri;
     const bool large = (p.M % LM == 0) && (p.N % LN == 0) && (g.K % (4 * LK) == 0) && g.K > 0 && aligned(p.C, 4);
-    const int64_t tm = large ? p.M / LM : ceil_div(p.M, TM), tn = large ? p.N / LN : ceil_div(p.N, TN);
+    // 256 x 256 tiles when they still give every CU a couple of tiles (measured: 3-8 % faster on large rectangular
+    // and symmetric-update launches; not on the skinny triangular products, whose tiles differ in K length)
+    const bool wide = large && !p.a_upper_tri && (p.N % 256 == 0) && (p.M / LM) * (p.N / 256) >= WIDE_MIN_TILES;
+    const int64_t tm = large ? p.M / LM : ceil_div(p.M, TM), tn = wide ? p.N / 256 : (large ? p.N / LN : ceil_div(p.N, TN));
     if (tm * tn > 0x7ffffff0LL) return fail(GPTQ_ERR_UNSUPPORTED, "gemm_f32: too many tiles");
     g.tiles_m = (int)tm; g.tiles_n = (int)tn;
     g.total = tm * tn;
     g.per_xcd = ceil_div(g.total, NXCD);
     dim3 grid((unsigned)(g.per_xcd * NXCD));
     if (large) {
-        if (p.b_is_nk) hipLaunchKernelGGL(gemm_f32_dma_kernel<true>, grid, dim3(512), 0, s, g);
-        else           hipLaunchKernelGGL(gemm_f32_dma_kernel<false>, grid, dim3(512), 0, s, g);
+        if (wide) {
+            if (p.b_is_nk) hipLaunchKernelGGL((gemm_f32_dma_kernel<true, true>), grid, dim3(512), 0, s, g);
+            else           hipLaunchKernelGGL((gemm_f32_dma_kernel<false, true>), grid, dim3(512), 0, s, g);
+        } else {
+            if (p.b_is_nk) hipLaunchKernelGGL((gemm_f32_dma_kernel<true, false>), grid, dim3(512), 0, s, g);
+            else           hipLaunchKernelGGL((gemm_f32_dma_kernel<false, false>), grid, dim3(512), 0, s, g);
+        }
     } else {
         if (p.b_is_nk) hipLaunchKernelGGL(gemm_f32_kernel<true>, grid, dim3(256), 0, s, g);
         else           hipLaunchKernelGGL(gemm_f32_kernel<false>, grid, dim3(256), 0, s, g);
