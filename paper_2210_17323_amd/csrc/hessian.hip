@@ -21,6 +21,36 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int HK = 64;          // token step (halves)
 constexpr int STRIP = 8;        // tile columns per strip
+
+// Tile order of the upper triangle: strips of STRIP tile columns; a strip holds its full rows above the
+// diagonal block (STRIP tiles each) and then the rows of the diagonal block, row q with its STRIP - q valid
+// tiles.  Only valid tiles are numbered: the order is dealt to the XCDs in equal runs, and every XCD works
+// through its run on its own, so runs that contained returned-from tiles would leave some XCDs with up to
+// 20 % less work than others (on a 48-tile-row matrix) and the launch waiting for the fullest one.
+__host__ __device__ inline int64_t syrk_strip_tiles(int nt, int s) {
+    const int cols = (nt - s * STRIP) < STRIP ? (nt - s * STRIP) : STRIP;
+    return (int64_t)s * STRIP * cols + (int64_t)cols * (cols + 1) / 2;
+}
+__host__ inline int64_t syrk_total_tiles(int nt) {
+    int64_t total = 0;
+    for (int s = 0; s * STRIP < nt; ++s) total += syrk_strip_tiles(nt, s);
+    return total;
+}
+__device__ __forceinline__ void syrk_tile_of(int nt, int64_t L, int& bi, int& bj) {
+    int s = 0;
+    for (int64_t c = syrk_strip_tiles(nt, 0); L >= c; c = syrk_strip_tiles(nt, s)) { L -= c; ++s; }
+    const int cols = min(STRIP, nt - s * STRIP);
+    const int64_t above = (int64_t)s * STRIP * cols;
+    if (L < above) {
+        bi = (int)(L / cols);
+        bj = s * STRIP + (int)(L % cols);
+    } else {
+        int l = (int)(L - above), q = 0;
+        for (int c = cols; l >= c; c = cols - q) { l -= c; ++q; }
+        bi = s * STRIP + q;
+        bj = bi + l;
+    }
+}
 constexpr int NXCD = 8;
 
 struct SyrkArgs {
@@ -72,17 +102,7 @@ __global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
     int64_t L = (w % NXCD) * g.per_xcd + (w / NXCD);
     if (L >= g.total) return;
     int bi, bj;
-    {
-        int s = 0;
-        for (;; ++s) {
-            const int cols = min(STRIP, g.nt - s * STRIP);
-            const int rows = min((s + 1) * STRIP, g.nt);
-            const int64_t cnt = (int64_t)cols * rows;
-            if (L < cnt) { bi = (int)(L / cols); bj = s * STRIP + (int)(L % cols); break; }
-            L -= cnt;
-        }
-    }
-    if (bi > bj) return;
+    syrk_tile_of(g.nt, L, bi, bj);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -267,17 +287,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     int64_t L = ((slot / 32) * NXCD + xcd) * 32 + (slot % 32);
     if (L >= g.total) return;
     int bi, bj;
-    {
-        int s = 0;
-        for (;; ++s) {
-            const int cols = min(STRIP, g.nt - s * STRIP);
-            const int rows = min((s + 1) * STRIP, g.nt);
-            const int64_t cnt = (int64_t)cols * rows;
-            if (L < cnt) { bi = (int)(L / cols); bj = s * STRIP + (int)(L % cols); break; }
-            L -= cnt;
-        }
-    }
-    if (bi > bj) return;
+    syrk_tile_of(g.nt, L, bi, bj);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -429,11 +439,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 static void syrk_schedule(SyrkArgs& g, int BT) {
     g.nt = (int)ceil_div(g.n, BT);
-    int64_t total = 0;
-    for (int st = 0; st * STRIP < g.nt; ++st)
-        total += (int64_t)std::min(STRIP, g.nt - st * STRIP) * std::min((st + 1) * STRIP, g.nt);
-    g.total = total;
-    g.per_xcd = ceil_div(total, NXCD);
+    g.total = syrk_total_tiles(g.nt);
+    g.per_xcd = ceil_div(g.total, NXCD);
 }
 
 template <bool IS_BF16>
@@ -467,11 +474,8 @@ static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s, bool token_major
 template <bool IS_BF16, int BT, int WM, int WN>
 static int launch_syrk(SyrkArgs g, hipStream_t s) {
     g.nt = (int)ceil_div(g.n, BT);
-    int64_t total = 0;
-    for (int st = 0; st * STRIP < g.nt; ++st)
-        total += (int64_t)std::min(STRIP, g.nt - st * STRIP) * std::min((st + 1) * STRIP, g.nt);
-    g.total = total;
-    g.per_xcd = ceil_div(total, NXCD);
+    g.total = syrk_total_tiles(g.nt);
+    g.per_xcd = ceil_div(g.total, NXCD);
     const int64_t blocks = g.per_xcd * NXCD;
     if (blocks > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
     constexpr size_t lds = 2 * 2 * BT * 128;
