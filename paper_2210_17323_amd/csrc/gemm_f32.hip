@@ -367,10 +367,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto multiply = [&](const unsigned char* cur, const unsigned char* nxt) {
         fetch(cur, 1);
         mfmas(0);
+        // the step's copies (issued by the caller just before) are spread over the first half's MFMAs: the
+        // first MFMAs need nothing but registers, so they start right after the barrier instead of behind
+        // the copy instructions, each of which holds the wavefront for tens of cycles
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, SM, 0);  // SM MFMAs
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+            if (i < CP) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 copy
         }
         fetch(nxt, 0);
         mfmas(1);
