@@ -11,8 +11,8 @@
 //   factorisation, outer blocks last .. first, inner blocks last .. first:
 //     R_bb  = reverse-Cholesky of the 128x128 diagonal block (one workgroup, block in LDS),
 //             and its inverse R_bb^-1 kept in the workspace
-//     P     = H[0:j0, j0:j1] * R_bb^-T                  (GEMM; P is the panel of R above the block)
-//     H[0:j0, outer block columns left of j0] -= P P^T  (rank-128, confined to the outer block)
+//     R[0:j0, j0:j1] = H[0:j0, j0:j1] * R_bb^-T             (the panel of R above the block, in place)
+//     H[0:j0, outer block columns left of j0] -= R[0:j0, j0:j1] R[.., j0:j1]^T   (rank-128, confined to the outer block)
 //     after the outer block: H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T   (rank-1024, carries the flops)
 //   triangular inverse, outer block columns first .. last:
 //     the 1024x1024 diagonal block is inverted in place with rank-128 steps, then
@@ -183,14 +183,13 @@ using namespace gptq;
 namespace {
 constexpr int OB = 1024;     // outer block: rank-1024 updates keep the big GEMMs compute-bound and their tiles long
 
-struct CholWs { float* dinv; float* P; float* T; float* dense; size_t total; };
+struct CholWs { float* dinv; float* T; float* dense; size_t total; };
 CholWs chol_ws_layout(void* ws, int64_t n) {
     const size_t nblk = (size_t)ceil_div(std::max<int64_t>(n, 1), NB);
     size_t off = 0;
     CholWs l{};
     char* base = static_cast<char*>(ws);
     l.dinv = reinterpret_cast<float*>(base + off);  off += round_up(nblk * NB * NB * sizeof(float), 256);
-    l.P = reinterpret_cast<float*>(base + off);     off += round_up((size_t)std::max<int64_t>(n, 1) * NB * sizeof(float), 256);
     l.T = reinterpret_cast<float*>(base + off);     off += round_up((size_t)std::max<int64_t>(n, 1) * OB * sizeof(float), 256);
     l.dense = reinterpret_cast<float*>(base + off); off += (size_t)OB * OB * sizeof(float);
     l.total = off + 256;
@@ -217,7 +216,6 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
 
     const CholWs w = chol_ws_layout(ws, n);
     float* dinv = w.dinv;
-    float* P = w.P;
     constexpr size_t diag_lds = 2 * NB * DP * sizeof(float);
     GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(diag_block_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)diag_lds));
 
@@ -252,15 +250,15 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
             hipLaunchKernelGGL(diag_block_kernel, dim3(1), dim3(256), diag_lds, s, H + j0 * ld + j0, ld, nbk, dinv_b, info_dev, (int)j0);
             GPTQ_LAUNCH_CHECK();
             if (j0 == 0) break;
-            // P = H[0:j0, j0:j1] * R_bb^-T  (the panel of R above the block), then store it in place
-            int rc = gemm(H + j0, ld, dinv_b, NB, P, NB, j0, nbk, nbk, 1.f, true, true, false, 0, 0, false);
+            // R[0:j0, j0:j1] = H[0:j0, j0:j1] * R_bb^-T, the panel of R above the block.  In place: there is a
+            // single tile column, and a workgroup reads all of its own rows before it writes them.
+            int rc = gemm(H + j0, ld, dinv_b, NB, H + j0, ld, j0, nbk, nbk, 1.f, true, true, false, 0, 0, false);
             if (rc) return rc;
-            const int cb = (int)std::min<int64_t>(ceil_div(j0 * nbk, 256), 4096);
-            hipLaunchKernelGGL(copy_block_kernel, dim3(cb), dim3(256), 0, s, H + j0, ld, (const float*)P, (int64_t)NB, j0, nbk, 0);
-            GPTQ_LAUNCH_CHECK();
-            // H[0:j0, o0:j0] -= P * P[o0:j0]^T  (columns of this outer block only; tiles below the diagonal skipped)
+            // H[0:j0, o0:j0] -= R[0:j0, j0:j1] * R[o0:j0, j0:j1]^T  (columns of this outer block only; tiles below the
+            // diagonal skipped).  Right-looking: many short tiles, which keeps this serial chain short; a left-looking
+            // product per inner block (one tile column, K up to 896) measured slower on mid-size matrices.
             if (j0 > o0) {
-                rc = gemm(P, NB, P + o0 * NB, NB, H + o0, ld, j0, j0 - o0, nbk, -1.f, true, false, true, 0, o0, false);
+                rc = gemm(H + j0, ld, H + o0 * ld + j0, ld, H + o0, ld, j0, j0 - o0, nbk, -1.f, true, false, true, 0, o0, false);
                 if (rc) return rc;
             }
         }
