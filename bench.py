@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes of ONE syrk_f16_dma_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
 # what the same counter reads for a plain 1 GiB copy kernel (factors 2.000 and 1.000): see
 # profiles/layer_solve_opt175b_fc2_pmc_counters.txt.  Keyed by (n, tokens per call); other shapes: not measured.
-MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (1.2461e8 * 2.0 + 5.0879e6 * 1.0) * 1024}
+MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (7.7036e7 * 2.0 + 5.0914e6 * 1.0) * 1024}
 
 
 def parse():
