@@ -43,117 +43,188 @@ __global__ __launch_bounds__(1024) void damp_kernel(float* H, int64_t ld, int64_
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // ---- diagonal block: D = R R^T (R upper, from the last column backwards) and R^-1, 128 x 128 -----------
-// Two levels.  A 64 x 64 block is factored and inverted by ONE wavefront entirely in registers: lane i
-// owns row i (64 registers, all indices static because the loops are unrolled), and the one value every
-// lane needs at a step -- R[k][j] -- sits in lane k and is broadcast with v_readlane.  The 128 x 128
-// block combines two of those with 64 x 64 x 64 products on the matrix cores (4 wavefronts, one 32 x 32
-// output tile each, operands read from LDS):
-//     R22 = rchol(D22), X22 = R22^-1;   R12 = D12 X22^T;   D11 -= R12 R12^T;
-//     R11 = rchol(D11), X11 = R11^-1;   X12 = -X11 (R12 X22).
+// Two levels.  A 32 x 32 block is factored and inverted by ONE wavefront in registers: lane i owns row i
+// (32 registers, all indices static because the loops are unrolled); the one thing every lane needs at a
+// step -- column j of the block -- goes through a small LDS buffer that all lanes read back with uniform
+// (broadcast) addresses.  The 128 x 128 block combines four of those with 32 x 32 x 32 products on the
+// matrix cores (4 wavefronts, one output tile each, operands read from LDS).  With block indices
+// b = 3 .. 0 and R_bc, X_bc the tiles of R and of X = R^-1:
+//     step b, part 1:  wavefront 0: R_bb = rchol(D_bb), X_bb = R_bb^-1
+//                      the others:  S_bc' = sum_{b < c <= c'} R_bc X_cc'  for c' > b   (needs nothing of part 1)
+//     step b, part 2:  R_ab = D_ab X_bb^T for a < b;   X_bc' = -X_bb S_bc' for c' > b
+//     step b, part 3:  D_aa' -= R_ab R_a'b^T for a <= a' < b
 
-// C[64 x 64] = beta * C + alpha * A[64 x 64] * B, all in LDS with row pitch DP.  B is read as B[k][n] when
-// !BT and as B[n][k] when BT.  Called by all 4 wavefronts; wavefront w owns output tile (w / 2, w % 2).
+// acc += A[32 x 32] * B, operands in LDS with row pitch DP.  B is read as B[k][n] when !BT and as B[n][k]
+// when BT.  One wavefront.
 template <bool BT>
-__device__ __forceinline__ void mm64(const float* A, const float* B, float* C, float alpha, float beta, int lane, int wave) {
+__device__ __forceinline__ void mma32(floatx16& acc, const float* A, const float* B, int lane) {
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int tm = (wave >> 1) * 32, tn = (wave & 1) * 32;
-    floatx16 acc;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll 8
-    for (int k = 0; k < 64; k += 2) {
-        const float a = A[(tm + l32) * DP + k + lhi];
-        const float b = BT ? B[(tn + l32) * DP + k + lhi] : B[(k + lhi) * DP + tn + l32];
+    for (int k = 0; k < 32; k += 2) {
+        const float a = A[l32 * DP + k + lhi];
+        const float b = BT ? B[l32 * DP + k + lhi] : B[(k + lhi) * DP + l32];
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
     }
+}
+
+// C[32 x 32] = beta * C + alpha * acc (C in LDS, pitch DP).  One wavefront.
+__device__ __forceinline__ void store32(float* C, const floatx16& acc, float alpha, float beta, int lane) {
+    const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        float* c = C + (tm + 8 * (i >> 2) + 4 * lhi + (i & 3)) * DP + tn + l32;
+        float* c = C + (8 * (i >> 2) + 4 * lhi + (i & 3)) * DP + l32;
         *c = (beta == 0.f) ? alpha * acc[i] : beta * (*c) + alpha * acc[i];
     }
 }
 
-// One wavefront: factor the 64 x 64 block at Dm (LDS, pitch DP; upper triangle valid) in place into R and
-// write R^-1 to Xm.  Returns the 1-based index of a non-positive pivot inside the block, or 0.
-__device__ __forceinline__ int rchol_inv64(float* Dm, float* Xm, int lane) {
-    float x[64];
+__device__ __forceinline__ floatx16 zero16() {
+    floatx16 acc;
 #pragma unroll
-    for (int c = 0; c < 64; ++c) x[c] = Dm[lane * DP + c];
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    return acc;
+}
+
+// One wavefront: factor the 32 x 32 block at Dm (LDS, pitch DP; upper triangle valid) in place into R and
+// write R^-1 to Xm.  Ct is a 32 x 64 LDS buffer that receives the columns: Ct[j][k], k < 32, = the
+// finished, not yet scaled column j of the block, i.e. R[k][j] * R[j][j].  Lanes 32 .. 63 mirror lanes
+// 0 .. 31; their copies of a column land in the unused half of its row of Ct, nothing else is stored.  Below the diagonal Dm is left with values that mean nothing (nobody reads them: they
+// only ever combine with each other); Xm is a clean upper triangle.  Returns the 1-based index of the
+// first non-positive pivot met, or 0.
+__device__ __forceinline__ int rchol_inv32(float* Dm, float* Xm, float* Ct, int lane) {
+    int row = lane & 31;
+    asm volatile("" : "+v"(row));      // keeps the lane tests below next to their uses instead of hoisted and spilled
+    const bool owner = lane < 32;
+    float x[32], rinv[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) x[c] = Dm[row * DP + c];
     int bad = 0;
+    Ct[31 * 64 + lane] = x[31];
 #pragma unroll
-    for (int j = 63; j >= 0; --j) {
-        float dd = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[j]), j));
-        if (!(dd > 0.f)) { bad = j + 1; dd = 1.f; }
-        const float rj = sqrtf(dd);
-        const float inv = 1.0f / rj;
-        x[j] = (lane < j) ? x[j] * inv : ((lane == j) ? rj : 0.f);
+    for (int j = 31; j >= 0; --j) {
+        // column j is final: every lane reads all of it.  R[k][j] = col[k] / r, R[j][j] = r = sqrt(col[j]).
+        float col[32];
 #pragma unroll
-        for (int k = 0; k < j; ++k) {
-            const float rkj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[j]), k));
-            x[k] = fmaf(-x[j], rkj, x[k]);
+        for (int k = 0; k <= j; ++k) col[k] = Ct[j * 64 + k];
+        float dd = col[j];
+        if (!(dd > 0.f)) { if (!bad) bad = j + 1; dd = 1.f; }
+        float inv = __frsqrt_rn(dd);
+        inv = inv * fmaf(-0.5f * dd * inv, inv, 1.5f);       // one Newton step: 1 / sqrt(dd) to an ulp
+        rinv[j] = inv;
+        const float u = x[j] * inv * inv;                     // R[row][j] / r
+        x[j] *= inv;                                          // row j: dd / sqrt(dd) = r
+        // x[k] -= R[row][j] R[k][j]; the column needed next goes out first so that its round trip through
+        // LDS overlaps the rest of the update
+#pragma unroll
+        for (int k = j - 1; k >= 0; --k) {
+            x[k] = fmaf(-u, col[k], x[k]);
+            if (k == j - 1) Ct[(j - 1) * 64 + lane] = x[k];
         }
     }
+    if (owner) {
 #pragma unroll
-    for (int c = 0; c < 64; ++c) Dm[lane * DP + c] = x[c];
-    // X R = I, column by column: X[i][c] = (delta_ic - sum_{k<c} X[i][k] R[k][c]) / R[c][c]
-    float y[64];
-#pragma unroll
-    for (int c = 0; c < 64; ++c) {
-        float s = (lane == c) ? 1.f : 0.f;
-#pragma unroll
-        for (int k = 0; k < c; ++k) {
-            const float rkc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[c]), k));
-            s = fmaf(-y[k], rkc, s);
-        }
-        const float rcc = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[c]), c));
-        y[c] = (lane <= c) ? s / rcc : 0.f;
+        for (int c = 0; c < 32; ++c) Dm[row * DP + c] = x[c];
     }
+    // X R = I, column by column: X[i][c] = (delta_ic - sum_{k<c} X[i][k] R[k][c]) / R[c][c].  Rows below
+    // the diagonal come out as exact zeros: every term of their sums is one.
+    float y[32];
 #pragma unroll
-    for (int c = 0; c < 64; ++c) Xm[lane * DP + c] = y[c];
+    for (int c = 0; c < 32; ++c) {
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < c; ++k) s = fmaf(y[k], Ct[c * 64 + k], s);
+        const float d = (row == c) ? rinv[c] : 0.f;
+        y[c] = fmaf(-rinv[c] * rinv[c], s, d);
+    }
+    if (owner) {
+#pragma unroll
+        for (int c = 0; c < 32; ++c) Xm[row * DP + c] = y[c];
+    }
     return bad;
 }
 
 // Rows/columns beyond nbk are padded with the identity.  One workgroup of 256 threads.
 //   H block  <- R (upper part; strictly lower part of the block zeroed)
 //   dinv     <- R^-1 as a dense 128 x 128 block (zeros below the diagonal)
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(256)
 void diag_block_kernel(float* Hblk, int64_t ld, int nbk, float* dinv, int* info, int col_base) {
-    extern __shared__ float sm[];
-    float* D = sm;                  // [NB][DP]  D, then R
-    float* Xs = sm + NB * DP;       // [NB][DP]  R^-1
-    float* T = Xs + 64 * DP;        // scratch: the lower-left 64 x 64 block of R^-1, zeroed again at the end
+    extern __shared__ __align__(16) float sm[];
+    float* Ct = sm;                 // [32][64]  columns of the block being factored
+    float* D = sm + 32 * 64;        // [NB][DP]  D, then R
+    float* Xs = D + NB * DP;        // [NB][DP]  R^-1 (tiles right of the diagonal hold S until part 2)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int q = tid; q < NB * NB; q += 256) {
-        const int i = q / NB, k = q % NB;
-        float v = (i == k) ? 1.f : 0.f;
-        if (i < nbk && k < nbk) v = (k >= i) ? Hblk[(int64_t)i * ld + k] : 0.f;
-        D[i * DP + k] = v;
-        Xs[i * DP + k] = 0.f;
+    // 16 independent 16-byte loads per thread, all in flight together: the block arrives in one round trip
+    float4 in[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int q = tid + 256 * t, i = q >> 5, k = (q & 31) * 4;
+        const float* src = Hblk + (int64_t)i * ld + k;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < nbk && k + 4 <= nbk) v = *reinterpret_cast<const float4*>(src);
+        else if (i < nbk && k < nbk) { v.x = src[0]; if (k + 1 < nbk) v.y = src[1]; if (k + 2 < nbk) v.z = src[2]; }
+        in[t] = v;
+    }
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int q = tid + 256 * t, i = q >> 5, k = (q & 31) * 4;
+        const float e[4] = {in[t].x, in[t].y, in[t].z, in[t].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int kc = k + c;
+            const bool inside = i < nbk && kc < nbk;
+            D[i * DP + kc] = inside ? (kc >= i ? e[c] : 0.f) : (i == kc ? 1.f : 0.f);
+            Xs[i * DP + kc] = 0.f;
+        }
     }
     __syncthreads();
-    float* D11 = D; float* D12 = D + 64; float* D22 = D + 64 * DP + 64;
-    float* X11 = Xs; float* X12 = Xs + 64; float* X22 = Xs + 64 * DP + 64;
+    auto tile = [](float* base, int a, int c) { return base + a * 32 * DP + c * 32; };
     int bad = 0;
-    if (wave == 0) { bad = rchol_inv64(D22, X22, lane); if (bad) bad += 64; }
-    __syncthreads();
-    mm64<true>(D12, X22, T, 1.f, 0.f, lane, wave);              // T = D12 X22^T = R12
-    __syncthreads();
-    for (int q = tid; q < 64 * 64; q += 256) D12[(q >> 6) * DP + (q & 63)] = T[(q >> 6) * DP + (q & 63)];
-    __syncthreads();
-    mm64<true>(D12, D12, D11, -1.f, 1.f, lane, wave);           // D11 -= R12 R12^T
-    mm64<false>(D12, X22, T, 1.f, 0.f, lane, wave);             // T = R12 X22
-    __syncthreads();
-    if (wave == 0) { const int b1 = rchol_inv64(D11, X11, lane); if (b1) bad = b1; }
-    __syncthreads();
-    mm64<false>(X11, T, X12, -1.f, 0.f, lane, wave);            // X12 = -X11 (R12 X22)
+#pragma unroll 1
+    for (int b = 3; b >= 0; --b) {
+        if (wave == 0) {
+            const int b1 = rchol_inv32(tile(D, b, b), tile(Xs, b, b), Ct, lane);
+            if (b1 && !bad) bad = b * 32 + b1;
+        } else if (b + wave <= 3) {
+            const int cp = b + wave;                            // S_b,cp = sum_{b < c <= cp} R_bc X_c,cp
+            floatx16 acc = zero16();
+            for (int c = b + 1; c <= cp; ++c) mma32<false>(acc, tile(D, b, c), tile(Xs, c, cp), lane);
+            store32(tile(Xs, b, cp), acc, 1.f, 0.f, lane);
+        }
+        __syncthreads();
+        if (wave < 3) {
+            floatx16 acc = zero16();
+            if (wave < b) {                                     // R_ab = D_ab X_bb^T, in place
+                mma32<true>(acc, tile(D, wave, b), tile(Xs, b, b), lane);
+                store32(tile(D, wave, b), acc, 1.f, 0.f, lane);
+            } else {                                            // X_b,cp = -X_bb S_b,cp, in place
+                const int cp = wave + 1;
+                mma32<false>(acc, tile(Xs, b, b), tile(Xs, b, cp), lane);
+                store32(tile(Xs, b, cp), acc, -1.f, 0.f, lane);
+            }
+        }
+        __syncthreads();
+        // D_aa' -= R_ab R_a'b^T for a <= a' < b: b (b + 1) / 2 tiles dealt over the wavefronts
+        for (int t = wave; t < b * (b + 1) / 2; t += 4) {
+            int a = 0, rest = t;                                // tile number t in the order (0,0) .. (0,b-1) (1,1) ..
+            while (rest >= b - a) { rest -= b - a; ++a; }
+            const int ap = a + rest;
+            floatx16 acc = zero16();
+            mma32<true>(acc, tile(D, a, b), tile(D, ap, b), lane);
+            store32(tile(D, a, ap), acc, -1.f, 1.f, lane);
+        }
+        __syncthreads();
+    }
     if (tid == 0 && bad) atomicCAS(info, 0, col_base + bad);
-    __syncthreads();
-    for (int q = tid; q < 64 * 64; q += 256) T[(q >> 6) * DP + (q & 63)] = 0.f;
-    __syncthreads();
-    for (int q = tid; q < NB * NB; q += 256) {
-        const int i = q / NB, k = q % NB;
-        dinv[q] = Xs[i * DP + k];
-        if (i < nbk && k < nbk) Hblk[(int64_t)i * ld + k] = (k >= i) ? D[i * DP + k] : 0.f;
+#pragma unroll 4
+    for (int t = 0; t < 16; ++t) {
+        const int q = tid + 256 * t, i = q >> 5, k = (q & 31) * 4;
+        float4 xv, rv;
+        xv.x = Xs[i * DP + k]; xv.y = Xs[i * DP + k + 1]; xv.z = Xs[i * DP + k + 2]; xv.w = Xs[i * DP + k + 3];
+        rv.x = (k >= i) ? D[i * DP + k] : 0.f;         rv.y = (k + 1 >= i) ? D[i * DP + k + 1] : 0.f;
+        rv.z = (k + 2 >= i) ? D[i * DP + k + 2] : 0.f; rv.w = (k + 3 >= i) ? D[i * DP + k + 3] : 0.f;
+        reinterpret_cast<float4*>(dinv)[q] = xv;
+        float* dst = Hblk + (int64_t)i * ld + k;
+        if (i < nbk && k + 4 <= nbk) *reinterpret_cast<float4*>(dst) = rv;
+        else if (i < nbk && k < nbk) { dst[0] = rv.x; if (k + 1 < nbk) dst[1] = rv.y; if (k + 2 < nbk) dst[2] = rv.z; }
     }
 }
 
@@ -216,7 +287,7 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
 
     const CholWs w = chol_ws_layout(ws, n);
     float* dinv = w.dinv;
-    constexpr size_t diag_lds = 2 * NB * DP * sizeof(float);
+    constexpr size_t diag_lds = (2 * NB * DP + 32 * 64) * sizeof(float);
     GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(diag_block_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)diag_lds));
 
     hipLaunchKernelGGL(damp_kernel, dim3(1), dim3(1024), 0, s, H, ld, n, percdamp, info_dev);
