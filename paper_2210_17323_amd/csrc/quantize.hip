@@ -7,12 +7,16 @@
 //       registers and walks the columns in order: code = clamp(rint(w/scale) + zero), q = grid
 //       value, e = (w - q) / U[j][j], then w[k] -= e * U[j][k] for the later columns of the block.
 //       Rows are independent (the Hessian information U is shared by all rows), so there is no
-//       cross-lane traffic at all; the 128 x 128 block of U is the same for every lane and is read
-//       through uniform (scalar) loads.  The column loop is fully unrolled so every register index
-//       is static.  Outputs: codes, the block's error matrix E (r x 128), per-row sum of e^2.
+//       cross-lane traffic at all; the 128 x 128 block of U is the same for every lane: the workgroup
+//       copies it into LDS once and every lane reads it back with uniform (broadcast) addresses, four
+//       values per instruction and many rows ahead of their use.  The column loop is fully unrolled so
+//       every register index is static.  Outputs: codes, the block's error matrix E (r x 128), per-row
+//       sum of e^2.
 //   trailing update    : W[:, i+B:] -= E * U[i:i+B, i+B:], the float32 matrix-core GEMM, applied at once to
 //       the rest of the current 1024-column outer block and deferred (rank 1024) for the columns beyond.
 #include "common.h"
+
+#include <utility>
 
 namespace gptq {
 
@@ -91,20 +95,10 @@ __global__ __launch_bounds__(64) void group_grid_kernel(const float* Wk, int64_t
     }
 }
 
-// Dense, padded copy of the diagonal block of U: Ub[j][k] = U[j0+j][j0+k], identity outside the matrix.
-__global__ __launch_bounds__(256) void copy_u_block_kernel(const float* U, int64_t ldu, int64_t n, int64_t j0, float* Ub) {
-    for (int q = threadIdx.x + blockIdx.x * 256; q < QB * QB; q += gridDim.x * 256) {
-        const int j = q / QB, k = q % QB;
-        float v = (j == k) ? 1.f : 0.f;
-        if (j0 + j < n && j0 + k < n) v = (k >= j) ? U[(j0 + j) * ldu + j0 + k] : 0.f;
-        Ub[q] = v;
-    }
-}
-
 struct QuantArgs {
     float* Wk; int64_t ldk;         // working weights, points at column 0
-    const float* Ub;                // dense 128 x 128 block of U
-    int64_t r, j0; int nbk;
+    const float* U; int64_t ldu;    // the factor, points at U[0][0]
+    int64_t r, n, j0; int nbk;
     int grid; int maxq;
     float* scales; int32_t* zeros; int64_t ngroups;   // [r x ngroups]
     int64_t group;                  // 0 or the group size
@@ -114,15 +108,167 @@ struct QuantArgs {
     int first_block;
 };
 
+// ---- the stream of U values ------------------------------------------------------------------------------
+// Row j of the block of U is needed from the aligned quad (4 floats) that holds column j: the diagonal
+// element and the elements right of it.  All rows' quads, in the order of their
+// use, form one stream; it is read from LDS through a ring of RING register quads: the quad at stream position
+// t + RING is requested right after the one at position t has been used, so a request runs RING quads -- a few
+// hundred cycles -- ahead of its use, also across the serial arithmetic at a column.  Rows, quads and ring
+// slots are template parameters: every register index is a constant by construction.
+namespace ustream {
+constexpr int RING = 16;
+constexpr int first_col(int j) { return (j / 4) * 4; }
+constexpr int quads(int j) { return (QB - first_col(j)) / 4; }
+constexpr int start(int j) { int s = 0; for (int i = 0; i < j; ++i) s += quads(i); return s; }
+constexpr int TOTAL = start(QB);
+constexpr int row_at(int t) { int j = 0; while (t >= quads(j)) { t -= quads(j); ++j; } return j; }
+}  // namespace ustream
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(3))) float* lds_floats;
+typedef const __attribute__((address_space(3))) f32x4* lds_quads;
+
+struct QuantState {
+    float w[QB];                        // working weights of the block; e_j once column j is done
+    f32x4 ring[ustream::RING];
+    uint32_t packed[QB / 4];            // codes, four to a word
+    float e2, scale, zf;
+    int zero;
+    float* edst;                        // this row of the block's error matrix
+    bool active;                        // row inside the matrix
+};
+
+typedef const volatile __attribute__((address_space(3))) f32x4* lds_quads_ordered;
+
+// Volatile on purpose: volatile accesses and asm statements keep their program order, which is what places
+// each request RING quads ahead of its use.  An ordinary load has no such order: with the whole column loop
+// one straight line, the compiler either hoists all requests to the top (and spills them) or sinks each one
+// down to its use (and then waits for it).
+template <int T>
+__device__ __forceinline__ void request_quad(QuantState& st, lds_floats ubs) {
+    if constexpr (T < ustream::TOTAL) {
+        constexpr int j = ustream::row_at(T), q = T - ustream::start(j);
+        st.ring[T % ustream::RING] = *reinterpret_cast<lds_quads_ordered>(ubs + j * QB + ustream::first_col(j) + 4 * q);
+    }
+}
+
+template <int... T>
+__device__ __forceinline__ void request_first(QuantState& st, lds_floats ubs, std::integer_sequence<int, T...>) {
+    (request_quad<T>(st, ubs), ...);
+}
+
+// w[kq .. kq+3] -= e * U[J][kq .. kq+3] for the columns right of J, then the request that refills the slot.
+// The empty asm statement takes the quad's results as operands, which puts it -- and with it the request
+// that follows -- behind this quad's arithmetic, so the request can reuse the quad's registers; it hands -e
+// on to the next quad, which puts that quad's arithmetic behind it.
+template <int J, int Q>
+__device__ __forceinline__ void update_quad(QuantState& st, lds_floats ubs, float& ne) {
+    constexpr int t = ustream::start(J) + Q, kq = ustream::first_col(J) + 4 * Q;
+    const f32x4 u = st.ring[t % ustream::RING];
+    if constexpr (kq + 0 > J) st.w[kq + 0] = fmaf(ne, u.x, st.w[kq + 0]);
+    if constexpr (kq + 1 > J) st.w[kq + 1] = fmaf(ne, u.y, st.w[kq + 1]);
+    if constexpr (kq + 2 > J) st.w[kq + 2] = fmaf(ne, u.z, st.w[kq + 2]);
+    if constexpr (kq + 3 > J) st.w[kq + 3] = fmaf(ne, u.w, st.w[kq + 3]);
+    if constexpr (t + ustream::RING < ustream::TOTAL) {
+        if constexpr (kq > J) asm volatile("" : "+v"(st.w[kq]), "+v"(st.w[kq + 1]), "+v"(st.w[kq + 2]), "+v"(st.w[kq + 3]), "+v"(ne));
+        else asm volatile("" : "+v"(st.w[kq + 1]), "+v"(st.w[kq + 2]), "+v"(st.w[kq + 3]), "+v"(ne));
+        request_quad<t + ustream::RING>(st, ubs);
+    }
+}
+
+template <int J, int... Q>
+__device__ __forceinline__ void update_row(QuantState& st, lds_floats ubs, float ne, std::integer_sequence<int, Q...>) {
+    (update_quad<J, Q>(st, ubs, ne), ...);
+}
+
+// Column J of the block: its grid if a group starts here, the code, the error, the update of the columns right of it.
+template <int G, int J>
+__device__ __forceinline__ void quantize_column(QuantState& st, lds_floats ubs, const QuantArgs& a, int64_t row, float maxq) {
+    if constexpr (G > 0 && J % (G > 0 ? G : 1) == 0) {
+        float lo = st.w[J], hi = st.w[J], am = fabsf(st.w[J]);
+#pragma unroll
+        for (int k = 1; k < G; ++k) {
+            lo = fminf(lo, st.w[J + k]); hi = fmaxf(hi, st.w[J + k]); am = fmaxf(am, fabsf(st.w[J + k]));
+        }
+        grid_from_range(a.grid, maxq, lo, hi, am, st.scale, st.zero);
+        st.zf = (float)st.zero;
+        if (J < a.nbk) {                                    // same for all lanes; lanes past the last row: see the stores of E
+            const int64_t gi = (a.j0 + J) / (G > 0 ? G : 1);
+            a.scales[row * a.ngroups + gi] = st.scale;
+            a.zeros[row * a.ngroups + gi] = st.zero;
+        }
+    }
+    const float x = st.w[J] / st.scale;
+    float c = rintf(x) + st.zf;
+    c = fminf(fmaxf(c, 0.f), maxq);
+    const float q = __fmul_rn(st.scale, c - st.zf);        // the grid value, rounded on its own (never fused into w - q)
+    // e = (w - q) / U[J][J]: reciprocal estimate, then one correction step with the exact remainder -- the
+    // rounded quotient at a third of the instructions of the general division (no range scaling: U[J][J] is
+    // the square root of a diagonal element of the inverse Hessian, far from the ends of the float range)
+    constexpr int diag_slot = ustream::start(J) % ustream::RING;        // row J's first quad holds U[J][J]
+    const float ujj = st.ring[diag_slot][J % 4];
+    const float rcp = __builtin_amdgcn_rcpf(ujj);
+    const float d = st.w[J] - q;
+    const float e0 = d * rcp;
+    const float e = fmaf(fmaf(-e0, ujj, d), rcp, e0);
+    const uint32_t ci = (uint32_t)c;
+    if constexpr ((J & 3) == 0) st.packed[J >> 2] = ci; else st.packed[J >> 2] |= ci << (8 * (J & 3));
+    st.e2 = fmaf(e, e, st.e2);
+    st.w[J] = e;
+    // Finished columns of E leave four at a time, which frees their registers.  No test of `active` here (it
+    // would cut the straight line into pieces): lanes past the last row work on a copy of the last row and
+    // store the same values to the same place as that row's own lane.
+    if constexpr ((J & 3) == 3)
+        *reinterpret_cast<float4*>(st.edst + J - 3) = make_float4(st.w[J - 3], st.w[J - 2], st.w[J - 1], st.w[J]);
+    update_row<J>(st, ubs, -e, std::make_integer_sequence<int, ustream::quads(J)>{});
+}
+
+template <int G, int... J>
+__device__ __forceinline__ void quantize_columns(QuantState& st, lds_floats ubs, const QuantArgs& a, int64_t row, float maxq,
+                                                 std::integer_sequence<int, J...>) {
+    (quantize_column<G, J>(st, ubs, a, row, maxq), ...);
+}
+
 // G = 0: the grid of this block's columns is already in scales/zeros (per-row grid, or a group that
-//        is a multiple of 128).  G in {8,16,32,64,128}: groups inside the block, grid taken from the
+//        is a multiple of 128).  G in {8,16,32,64}: groups inside the block, grid taken from the
 //        current register values at each group start.
 template <int G>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void quant_block_kernel(QuantArgs a) {
-    const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x;
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void quant_block_kernel(QuantArgs a) {
+    // ---- the diagonal block of U into LDS: ubs[j][k] = U[j0+j][j0+k] for k >= j, identity outside the
+    //      matrix.  16 independent 16-byte loads per thread.
+    __shared__ __align__(16) float ubs[QB * QB];
+    {
+        const int tid = threadIdx.x;
+        float4 in[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
+            const int64_t gj = a.j0 + j, gk = a.j0 + k;
+            const float* src = a.U + gj * a.ldu + gk;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gj < a.n && gk + 4 <= a.n) v = *reinterpret_cast<const float4*>(src);
+            else if (gj < a.n && gk < a.n) { v.x = src[0]; if (gk + 1 < a.n) v.y = src[1]; if (gk + 2 < a.n) v.z = src[2]; }
+            in[t] = v;
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
+            const int64_t gj = a.j0 + j, gk = a.j0 + k;
+            float e[4] = {in[t].x, in[t].y, in[t].z, in[t].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool inside = gj < a.n && gk + c < a.n;
+                e[c] = inside ? (k + c >= j ? e[c] : 0.f) : (k + c == j ? 1.f : 0.f);
+            }
+            *reinterpret_cast<float4*>(&ubs[j * QB + k]) = make_float4(e[0], e[1], e[2], e[3]);
+        }
+        __syncthreads();
+    }
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const bool active = row < a.r;
-    const int64_t rr = active ? row : 0;
-    float w[QB];
+    const int64_t rr = active ? row : a.r - 1;
+    QuantState st;
+    float (&w)[QB] = st.w;
     {
         const float* src = a.Wk + rr * a.ldk + a.j0;
         if (a.nbk == QB) {
@@ -137,49 +283,22 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         }
     }
     const float maxq = (float)a.maxq;
-    float scale = 1.f; int zero = 0;
+    st.scale = 1.f; st.zero = 0;
     if (G == 0) {
         const int64_t gi = a.group ? (a.j0 / a.group) : 0;
-        scale = a.scales[rr * a.ngroups + gi];
-        zero = a.zeros[rr * a.ngroups + gi];
+        st.scale = a.scales[rr * a.ngroups + gi];
+        st.zero = a.zeros[rr * a.ngroups + gi];
     }
-    float zf = (float)zero;
-    uint32_t packed[QB / 4];
-    float e2 = 0.f;
-    const float* __restrict__ ub = a.Ub;
-#pragma unroll
-    for (int j = 0; j < QB; ++j) {
-        if (G > 0 && (j % (G > 0 ? G : 1)) == 0) {
-            float lo = w[j], hi = w[j], am = fabsf(w[j]);
-#pragma unroll
-            for (int k = 1; k < (G > 0 ? G : 1); ++k) {
-                lo = fminf(lo, w[j + k]); hi = fmaxf(hi, w[j + k]); am = fmaxf(am, fabsf(w[j + k]));
-            }
-            grid_from_range(a.grid, maxq, lo, hi, am, scale, zero);
-            zf = (float)zero;
-            if (active && j < a.nbk) {
-                const int64_t gi = (a.j0 + j) / (G > 0 ? G : 1);
-                a.scales[row * a.ngroups + gi] = scale;
-                a.zeros[row * a.ngroups + gi] = zero;
-            }
-        }
-        const float x = w[j] / scale;
-        float c = rintf(x) + zf;
-        c = fminf(fmaxf(c, 0.f), maxq);
-        const float q = __fmul_rn(scale, c - zf);          // the grid value, rounded on its own (never fused into w - q)
-        const float e = (w[j] - q) / ub[j * QB + j];
-        const uint32_t ci = (uint32_t)c;
-        if ((j & 3) == 0) packed[j >> 2] = ci; else packed[j >> 2] |= ci << (8 * (j & 3));
-        e2 = fmaf(e, e, e2);
-        w[j] = e;
-#pragma unroll
-        for (int k = j + 1; k < QB; ++k) w[k] = fmaf(-e, ub[j * QB + k], w[k]);
-    }
+    st.zf = (float)st.zero;
+    st.e2 = 0.f;
+    lds_floats ub = (lds_floats)ubs;
+    request_first(st, ub, std::make_integer_sequence<int, ustream::RING>{});
+    st.active = active;
+    st.edst = a.E + rr * a.lde;
+    quantize_columns<G>(st, ub, a, rr, maxq, std::make_integer_sequence<int, QB>{});
+    const float e2 = st.e2;
     if (!active) return;
-    // ---- outputs: E row (the registers now hold e_j), codes, per-row error
-    float* edst = a.E + row * a.lde;
-#pragma unroll
-    for (int k = 0; k < QB; k += 4) *reinterpret_cast<float4*>(edst + k) = make_float4(w[k], w[k + 1], w[k + 2], w[k + 3]);
+    uint32_t (&packed)[QB / 4] = st.packed;
     uint8_t* cdst = a.codes + row * a.ldc + a.j0;
     if (a.nbk == QB && (reinterpret_cast<uintptr_t>(cdst) & 15) == 0) {
 #pragma unroll
@@ -217,14 +336,13 @@ static bool group_supported(int64_t group) {
 
 constexpr int QOB = 1024;   // outer block: trailing updates beyond it are deferred and applied as one rank-1024 GEMM
 
-struct QuantWs { size_t wk, e, ub, total; int64_t ldk; };
+struct QuantWs { size_t wk, e, total; int64_t ldk; };
 static QuantWs quant_ws_layout(int64_t r, int64_t n) {
     QuantWs l;
     l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
     l.wk = 0;
     size_t off = round_up((size_t)std::max<int64_t>(r, 1) * l.ldk * sizeof(float), 256);
     l.e = off; off += 2 * round_up((size_t)std::max<int64_t>(r, 1) * QOB * sizeof(float), 256);   // two error panels (look-ahead)
-    l.ub = off; off += QB * QB * sizeof(float);
     l.total = off + 256;
     return l;
 }
@@ -268,7 +386,6 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     float* Wk = reinterpret_cast<float*>(base + lay.wk);
     float* Ebuf[2] = {reinterpret_cast<float*>(base + lay.e),
                       reinterpret_cast<float*>(base + lay.e + round_up((size_t)r * QOB * sizeof(float), 256))};
-    float* Ub = reinterpret_cast<float*>(base + lay.ub);
     const int maxq = (grid == GPTQ_GRID_TERNARY) ? 2 : ((1 << bits) - 1);
     const int64_t ngroups = group ? n / group : 1;
     const int want_grid = group == 0;
@@ -285,7 +402,7 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     }
     GPTQ_LAUNCH_CHECK();
 
-    const unsigned qblocks = (unsigned)ceil_div(r, 64);
+    const unsigned qblocks = (unsigned)ceil_div(r, 256);
     // Lazy batching at two levels (Section 3, Step 2 applied twice): inside an outer block of 1024 columns
     // each 128-column block updates only the rest of the outer block (rank 128); the columns beyond it
     // get one rank-1024 update per outer block.  Same sums as Alg. 1, associated differently.
@@ -308,23 +425,24 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
         for (int64_t j0 = o0; j0 < o1; j0 += QB) {
             const int nbk = (int)std::min<int64_t>(QB, n - j0);
             const int64_t j1 = j0 + nbk;
-            hipLaunchKernelGGL(copy_u_block_kernel, dim3(16), dim3(256), 0, s, U, ldu, n, j0, Ub);
-            GPTQ_LAUNCH_CHECK();
             if (group >= QB && j0 % group == 0) {
+                // The grid is taken from all columns of the group as they stand now.  Those beyond this outer
+                // block are kept current by the helper stream: its last update has to be in.
+                if (rest_done && j0 + group > o1) GPTQ_HIP_CHECK(hipStreamWaitEvent(s, rest_done, 0));
                 hipLaunchKernelGGL(group_grid_kernel, dim3((unsigned)r), dim3(64), 0, s, (const float*)Wk, lay.ldk, j0, group, grid, (float)maxq, scales, zeros, ngroups, j0 / group);
                 GPTQ_LAUNCH_CHECK();
             }
             QuantArgs a{};
-            a.Wk = Wk; a.ldk = lay.ldk; a.Ub = Ub; a.r = r; a.j0 = j0; a.nbk = nbk; a.grid = grid; a.maxq = maxq;
+            a.Wk = Wk; a.ldk = lay.ldk; a.U = U; a.ldu = ldu; a.r = r; a.n = n; a.j0 = j0; a.nbk = nbk; a.grid = grid; a.maxq = maxq;
             a.scales = scales; a.zeros = zeros; a.ngroups = ngroups; a.group = group;
             a.codes = codes; a.ldc = ldc; a.E = E + (j0 - o0); a.lde = QOB; a.half_e2 = half_E2_rows; a.first_block = (j0 == 0);
             const int G = (group > 0 && group < QB) ? (int)group : 0;
             switch (G) {
-                case 0:  hipLaunchKernelGGL(quant_block_kernel<0>,  dim3(qblocks), dim3(64), 0, s, a); break;
-                case 8:  hipLaunchKernelGGL(quant_block_kernel<8>,  dim3(qblocks), dim3(64), 0, s, a); break;
-                case 16: hipLaunchKernelGGL(quant_block_kernel<16>, dim3(qblocks), dim3(64), 0, s, a); break;
-                case 32: hipLaunchKernelGGL(quant_block_kernel<32>, dim3(qblocks), dim3(64), 0, s, a); break;
-                default: hipLaunchKernelGGL(quant_block_kernel<64>, dim3(qblocks), dim3(64), 0, s, a); break;
+                case 0:  hipLaunchKernelGGL(quant_block_kernel<0>,  dim3(qblocks), dim3(256), 0, s, a); break;
+                case 8:  hipLaunchKernelGGL(quant_block_kernel<8>,  dim3(qblocks), dim3(256), 0, s, a); break;
+                case 16: hipLaunchKernelGGL(quant_block_kernel<16>, dim3(qblocks), dim3(256), 0, s, a); break;
+                case 32: hipLaunchKernelGGL(quant_block_kernel<32>, dim3(qblocks), dim3(256), 0, s, a); break;
+                default: hipLaunchKernelGGL(quant_block_kernel<64>, dim3(qblocks), dim3(256), 0, s, a); break;
             }
             GPTQ_LAUNCH_CHECK();
             if (j1 < o1) {
