@@ -263,8 +263,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 3))) voi
 // Used when M % 256 == 0, N % 128 == 0 (256 for the wide tile) and K % 64 == 0.  8 wavefronts, each 64 x 64 = 2 x 2 MFMA tiles.
 // A stage holds 16 values of K: the A panel as [256 rows][16 floats] and, for B given as [N x K], the B
 // panel as [128 rows][16 floats]; rows are 64 bytes = 4 chunks of 16 bytes, and global_load_lds_dwordx4
-// lays 16 such rows down per instruction with the chunk index XOR-swizzled by (row / 2) % 4 on the global
-// side, so that a ds_read_b128 of one chunk by 32 consecutive rows is bank-conflict free.  One 16-byte
+// lays 16 such rows down per instruction with the chunk index XOR-swizzled by (row / 4) % 4 on the global
+// side: the 16 lanes that a ds_read_b128 serves together read one chunk of 16 consecutive rows, and rows
+// 4 apart (256 bytes, the same banks) then sit at different chunk positions -- no bank conflicts.  One 16-byte
 // read hands a lane four consecutive k of its row; the half-wavefront h uses chunk 2q+h, and the four
 // MFMAs of an octet q consume element i = 0..3 of those reads -- the MFMA's k pairing becomes
 // (8q+i, 8q+4+i), the same for A and B, which is all a dot product needs.  For B given as [K x N] the
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     // copies: A panel = 16 instructions of 16 rows (2 per wavefront); B panel = 8 or 16 instructions (NB per wavefront):
     // for B given as [N x K] 16 rows each, for [K x N] 1 KB of consecutive n (two k rows of 128, or one of 256)
-    const int crow = lane >> 2, cchunk = (lane & 3) ^ ((lane >> 3) & 3);
+    const int crow = lane >> 2, cchunk = (lane & 3) ^ ((lane >> 4) & 3);
     const float* srcA = g.A + (m0 + wave * 32 + crow) * g.lda + cchunk * 4;              // + i*16 rows, + k0
     const float* srcB = B_IS_NK ? g.B + (n0 + wave * 16 * NB + crow) * g.ldb + cchunk * 4  // + i*16 rows, + k0
                       : WIDE    ? g.B + (int64_t)(wave * 2) * g.ldb + n0 + lane * 4        // + i k-rows, + k0*ldb
@@ -328,7 +329,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const int rowA = (wm * 32 * SM + l32) * 64;                  // + s * 2048
     const int rowB = LA_BYTES + (wn * 64 + l32) * 64;            // NK: + t * 2048
-    const int swz = (l32 >> 1) & 3;
+    const int swz = (l32 >> 2) & 3;
     const int colB = LA_BYTES + (wn * 64 + l32) * 4;             // KN: + t * 128 + krow * TN_ * 4
     // One 16-deep step out of `cur`.  The fragments of its first 8 k are already in registers (fetched at the
     // end of the previous step); those of the second 8 are read from LDS while the first half's MFMAs run, and

@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint16_t* X, int64_t 
         if (row < n) v = load8h_guard(X + row * ldx + tok, t - tok);     // zeros past the last token
         const int64_t panel = row >> 8;
         const int r = (int)(row & 255);
-        const int pos = (c64 & 3) ^ ((r >> 1) & 3);
+        const int pos = (c64 & 3) ^ ((r >> 2) & 3);
         *reinterpret_cast<uint4*>(Xb + (panel * nsteps + step) * 16384 + r * 64 + pos * 16) = v;
     }
 }
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void repack_token_major_kernel(const uint16_t*
         uint32_t wds[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) wds[e] = (uint32_t)tile[r][c * 8 + 2 * e] | ((uint32_t)tile[r][c * 8 + 2 * e + 1] << 16);
-        const int pos = c ^ ((r >> 1) & 3);
+        const int pos = c ^ ((r >> 2) & 3);
         *reinterpret_cast<uint4*>(Xb + (panel * nsteps + step) * 16384 + r * 64 + pos * 16) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
     }
 }
@@ -259,7 +259,9 @@ __global__ __launch_bounds__(256) void repack_token_major_kernel(const uint16_t*
 // straight from global memory into LDS with global_load_lds_dwordx4 (no staging registers, no
 // ds_write): one such instruction moves 16 rows x 64 bytes and lays the 64 lanes down linearly in LDS,
 // so the XOR swizzle of the 16-byte chunks is applied on the global side (lane l fetches chunk
-// (l % 4) ^ ((l / 8) % 4) of row l / 4).  Five stages (all 160 KB of LDS): while step k is multiplied the
+// (l % 4) ^ ((l / 16) % 4) of row l / 4).  Rows are 64 bytes, so 16 consecutive rows -- what 16 lanes of a
+// 16-byte LDS read touch together -- fall on all 16 bank quads exactly when rows 4 apart get different chunk
+// positions: the swizzle term is (row / 4) % 4.  Five stages (all 160 KB of LDS): while step k is multiplied the
 // copies of steps k+1 .. k+4 are in flight, which is what hides the memory latency with one wavefront per SIMD; one
 // barrier per step.  Requires t % 160 == 0 (the caller splits off the tail).
 constexpr int DK = 32;                                  // tokens per stage
@@ -296,7 +298,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // this lane's part of the 4 + 4 copies of a step: row (wave*4 + i)*16 + lane/4 of each panel, chunk
     // (lane%4) ^ ((lane/8)%4).  Rows past n are clamped: they only feed outputs that are never stored.
-    const int lrow = lane >> 2, lchunk = (lane & 3) ^ ((lane >> 3) & 3);
+    const int lrow = lane >> 2, lchunk = (lane & 3) ^ ((lane >> 4) & 3);
     const uint16_t* xcol = g.X + lchunk * 8;
     const unsigned char* blkA = BLOCKED ? g.Xb + (int64_t)bi * g.nsteps * 16384 + wave * 4096 + lane * 16 : nullptr;
     const unsigned char* blkB = BLOCKED ? g.Xb + (int64_t)bj * g.nsteps * 16384 + wave * 4096 + lane * 16 : nullptr;
@@ -334,9 +336,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int i = 0; i < 16; ++i) acc[s][u][i] = 0.f;
 
     // This lane's operand rows are wm*128 + s*32 + lane%32 (A) and wn*128 + u*32 + lane%32 (B): the swizzle
-    // term (row / 2) % 4 is (lane / 2) % 4 for all of them, and s / u only add a constant 2048 bytes.
+    // term (row / 4) % 4 is (lane / 4) % 4 for all of them, and s / u only add a constant 2048 bytes.
     const int rowA = (wm * 128 + l32) * 64, rowB = PANEL + (wn * 128 + l32) * 64;
-    const int co0 = (lhi ^ ((l32 >> 1) & 3)) << 4;      // chunk offset of sub-step 0; sub-step 1 flips bit 5
+    const int co0 = (lhi ^ ((l32 >> 2) & 3)) << 4;      // chunk offset of sub-step 0; sub-step 1 flips bit 5
     // One 32-token step out of `cur`.  The operand fragments of its first 16 tokens are already in fa[0]/fb[0]
     // (fetched at the end of the previous step); those of the second 16 tokens are fetched from LDS while the
     // first 16 MFMAs run, and the first fragments of the NEXT step (`nxt`, whose copies have landed) while
