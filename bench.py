@@ -4,7 +4,8 @@
 One step = one pass of the whole hot path over one synthetic layer: zero H, accumulate
 H += 2 X X^T over all calibration tokens (in chunks), damp + Cholesky of the inverse, Algorithm 1
 (block quantizer + trailing updates), bit packing.  Inputs are resident in HBM before timing starts.
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (TFLOP/s over the algorithmic flops of the whole solve), ms_per_step, per-phase
+times and rates, the roofline of the dominant kernel and the CPU oracle baseline.
 """
 from __future__ import annotations
 
@@ -61,7 +62,7 @@ def pick_layer(name: str, tokens: int):
 
 
 def flop_model(r: int, n: int, m: int, B: int = 128):
-    """Algorithmic flops of each step (the conventions are stated in the design doc)."""
+    """Algorithmic flops of each step: what the mathematics needs, not what the kernels execute."""
     trailing = sum(2 * r * min(B, n - i) * (n - i - min(B, n - i)) for i in range(0, n, B))
     inblock = sum(r * min(B, n - i) * (min(B, n - i) - 1) for i in range(0, n, B))
     return {
