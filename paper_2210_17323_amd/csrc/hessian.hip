@@ -285,23 +285,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // one XCD so that its 32 CUs share the patch's panels in that XCD's L2; consecutive patches go to
     // consecutive XCDs, so at any time the 8 XCDs work on neighbouring row groups of the same strip and find
     // each other's column panels in the memory-side cache instead of HBM.
-    const int64_t xcd = w % NXCD, slot = w / NXCD;
-    int64_t L = ((slot / 32) * NXCD + xcd) * 32 + (slot % 32);
-    if (L >= g.total) return;
-    int bi, bj;
-    syrk_tile_of(g.nt, L, bi, bj);
+    // The launch is persistent: 32 workgroups per XCD (one per CU: a workgroup takes all of the LDS), each
+    // walking slots w / 8, w / 8 + 32, ... of its XCD, so that the first copies of a workgroup's next tile
+    // are on their way while it writes the finished tile out.
+    const int64_t xcd = w % NXCD, slot_step = gridDim.x / NXCD;
+    int64_t slot = w / NXCD;
+    auto tile_at = [&](int64_t sl) { return ((sl / 32) * NXCD + xcd) * 32 + (sl % 32); };
+    if (tile_at(slot) >= g.total) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lhi = lane >> 5;
-    const int64_t r0 = (int64_t)bi * BT, c0 = (int64_t)bj * BT;
 
     // this lane's part of the 4 + 4 copies of a step: row (wave*4 + i)*16 + lane/4 of each panel, chunk
-    // (lane%4) ^ ((lane/8)%4).  Rows past n are clamped: they only feed outputs that are never stored.
+    // (lane%4) ^ ((lane/16)%4).  Rows past n are clamped: they only feed outputs that are never stored.
     const int lrow = lane >> 2, lchunk = (lane & 3) ^ ((lane >> 4) & 3);
     const uint16_t* xcol = g.X + lchunk * 8;
-    const unsigned char* blkA = BLOCKED ? g.Xb + (int64_t)bi * g.nsteps * 16384 + wave * 4096 + lane * 16 : nullptr;
-    const unsigned char* blkB = BLOCKED ? g.Xb + (int64_t)bj * g.nsteps * 16384 + wave * 4096 + lane * 16 : nullptr;
+    int64_t r0 = 0, c0 = 0;                              // origin of the tile whose panels are being copied
+    const unsigned char* blkA = nullptr;
+    const unsigned char* blkB = nullptr;
+    auto set_tile = [&](int64_t L) {
+        int bi, bj;
+        syrk_tile_of(g.nt, L, bi, bj);
+        r0 = (int64_t)bi * BT; c0 = (int64_t)bj * BT;
+        if (BLOCKED) {
+            blkA = g.Xb + (int64_t)bi * g.nsteps * 16384 + wave * 4096 + lane * 16;
+            blkB = g.Xb + (int64_t)bj * g.nsteps * 16384 + wave * 4096 + lane * 16;
+        }
+    };
     auto issue_copies = [&](unsigned char* stage, int64_t k0) {
         unsigned char* base = stage + wave * 4 * 1024;
         if (BLOCKED) {
@@ -328,12 +339,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
 
     floatx16 acc[4][4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[s][u][i] = 0.f;
 
     // This lane's operand rows are wm*128 + s*32 + lane%32 (A) and wn*128 + u*32 + lane%32 (B): the swizzle
     // term (row / 4) % 4 is (lane / 4) % 4 for all of them, and s / u only add a constant 2048 bytes.
@@ -393,46 +398,69 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         multiply(cur, nxt);
     };
     const int64_t ksteps = g.t / DK;                    // a multiple of 5 (the caller passes t % 160 == 0)
+    set_tile(tile_at(slot));
     issue_copies(stage0, 0);
     issue_copies(stage1, DK);
     issue_copies(stage2, 2 * DK);
     issue_copies(stage3, 3 * DK);
-    __builtin_amdgcn_s_waitcnt(0x4F78);                 // vmcnt(24): step 0 has landed
-    asm volatile("s_barrier" ::: "memory");
-    fetch(stage0, 0);
-    for (int64_t ks = 0; ks < ksteps; ks += 5) {
-        next_stage(stage4, (ks + 4) * DK, stage0, stage1);
-        next_stage(stage0, (ks + 5) * DK, stage1, stage2);
-        next_stage(stage1, (ks + 6) * DK, stage2, stage3);
-        next_stage(stage2, (ks + 7) * DK, stage3, stage4);
-        next_stage(stage3, (ks + 8) * DK, stage4, stage0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);                 // drain the dummy copies before the LDS is released
+    for (;;) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[s][u][i] = 0.f;
+        __builtin_amdgcn_s_waitcnt(0x4F78);             // vmcnt(24): step 0 has landed (and, from the second tile
+                                                        // on, the previous tile's updates of H have left)
+        asm volatile("s_barrier" ::: "memory");
+        fetch(stage0, 0);
+        for (int64_t ks = 0; ks < ksteps; ks += 5) {
+            next_stage(stage4, (ks + 4) * DK, stage0, stage1);
+            next_stage(stage0, (ks + 5) * DK, stage1, stage2);
+            next_stage(stage1, (ks + 6) * DK, stage2, stage3);
+            next_stage(stage2, (ks + 7) * DK, stage3, stage4);
+            next_stage(stage3, (ks + 8) * DK, stage4, stage0);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // this wavefront's surplus copies have landed: its parts of the stages are free
 
-    // ---- H += 2 * acc with the memory system's float add (no value comes back, so nothing waits for a round
-    // trip: the workgroup issues its 256 KB of updates and leaves the CU to the next tile; reading H first cost
-    // ~25 us of exposed latency per 760 us tile).  Each element of H belongs to exactly one workgroup of the
-    // launch, so the sum is the same float32 add in the same order as a load-add-store.
-    const bool inside = (r0 + BT <= g.n) && (c0 + BT <= g.n);
+        // The next tile's first four steps start now.  Another wavefront may still be in its last multiply:
+        // that one reads stage 4, which is not refilled here, and prefetches fragments from stage 0 that nobody uses.
+        const int64_t er0 = r0, ec0 = c0;
+        slot += slot_step;
+        const bool more = tile_at(slot) < g.total;
+        if (more) {
+            set_tile(tile_at(slot));
+            issue_copies(stage0, 0);
+            issue_copies(stage1, DK);
+            issue_copies(stage2, 2 * DK);
+            issue_copies(stage3, 3 * DK);
+        }
+
+        // ---- H += 2 * acc with the memory system's float add (no value comes back, so nothing waits for a round
+        // trip; reading H first cost ~25 us of exposed latency per 760 us tile).  Each element of H belongs to
+        // exactly one tile of the launch, so the sum is the same float32 add in the same order as a load-add-store.
+        const bool inside = (er0 + BT <= g.n) && (ec0 + BT <= g.n);
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t col = c0 + wn * 128 + u * 32 + l32;
-            const int64_t rbase = r0 + wm * 128 + s * 32 + 4 * lhi;
-            if (inside) {
-                float* hb = g.H + rbase * g.ldh + col;
+            for (int u = 0; u < 4; ++u) {
+                const int64_t col = ec0 + wn * 128 + u * 32 + l32;
+                const int64_t rbase = er0 + wm * 128 + s * 32 + 4 * lhi;
+                if (inside) {
+                    float* hb = g.H + rbase * g.ldh + col;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) unsafeAtomicAdd(hb + (int64_t)(8 * (i >> 2) + (i & 3)) * g.ldh, 2.0f * acc[s][u][i]);
-            } else {
-                if (col >= g.n) continue;
+                    for (int i = 0; i < 16; ++i) unsafeAtomicAdd(hb + (int64_t)(8 * (i >> 2) + (i & 3)) * g.ldh, 2.0f * acc[s][u][i]);
+                } else {
+                    if (col >= g.n) continue;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int64_t row = rbase + 8 * (i >> 2) + (i & 3);
-                    if (row < g.n) unsafeAtomicAdd(g.H + row * g.ldh + col, 2.0f * acc[s][u][i]);
+                    for (int i = 0; i < 16; ++i) {
+                        const int64_t row = rbase + 8 * (i >> 2) + (i & 3);
+                        if (row < g.n) unsafeAtomicAdd(g.H + row * g.ldh + col, 2.0f * acc[s][u][i]);
+                    }
                 }
             }
-        }
+        if (!more) break;
+    }
 }
 
 static void syrk_schedule(SyrkArgs& g, int BT) {
@@ -445,8 +473,8 @@ template <bool IS_BF16>
 static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s, bool token_major = false) {
     syrk_schedule(g, 256);
     g.per_xcd = ceil_div(ceil_div(g.total, 32), NXCD) * 32;      // whole patches of 32 slots per XCD
-    const int64_t blocks = g.per_xcd * NXCD;
-    if (blocks > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
+    if (g.per_xcd * NXCD > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
+    const int64_t blocks = std::min<int64_t>(g.per_xcd, 32) * NXCD;   // persistent: one workgroup per CU walks its slots
     g.Xb = static_cast<const unsigned char*>(ws);
     if (ws) {
         g.nsteps = ceil_div(ceil_div(g.t, DK), 5) * 5;           // zero-padded to whole trips of the 5-stage loop
