@@ -408,7 +408,12 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
             // dense copy of the inverted diagonal block with an explicit zero lower triangle
             hipLaunchKernelGGL(copy_block_kernel, dim3(256), dim3(256), 0, s, w.dense, (int64_t)OB, (const float*)(H + o0 * ld + o0), ld, (int64_t)ow, ow, 1);
             GPTQ_LAUNCH_CHECK();
-            int rc = gemm(H + o0, ld, w.dense, OB, w.T, OB, o0, ow, ow, 1.f, false, true, false, 0, 0, false);
+            // T = R[0:o0, o] * U_oo; U_oo is upper triangular (zeros below the diagonal in the dense copy), so a tile's
+            // K loop ends at its last column
+            GemmF32 gt{};
+            gt.A = H + o0; gt.lda = ld; gt.B = w.dense; gt.ldb = OB; gt.C = w.T; gt.ldc = OB; gt.M = o0; gt.N = ow; gt.K = ow;
+            gt.alpha = 1.f; gt.b_is_nk = false; gt.overwrite = true; gt.b_upper_tri = true;
+            int rc = launch_gemm_f32(gt, s);
             if (rc) return rc;
             rc = gemm(H, ld, w.T, OB, H + o0, ld, o0, ow, o0, -1.f, false, true, false, 0, 0, true);
             if (rc) return rc;

@@ -57,6 +57,9 @@ int lookahead_get(Lookahead** out);     // for the current device; GPTQ_OK or an
 //               with (crow0, ccol0) the global offset of C's first element inside its parent matrix.
 //   a_upper_tri: A[M x K] is the top-left part of an upper-triangular matrix (A[i][k] == 0 for k < i
 //               rounded down to 128): the K loop of a tile starts at the tile's first row.
+//   b_upper_tri: B given as [K x N] is the top-left part of an upper-triangular matrix with explicit zeros
+//               below the diagonal: the K loop of a tile may end at the tile's last column (the large-tile
+//               kernels do that; where it is not done the zeros give the same result).
 // All pointers 16-byte aligned, leading dimensions multiples of 4.
 struct GemmF32 {
     const float* A; int64_t lda;
@@ -69,6 +72,7 @@ struct GemmF32 {
     bool upper_only;
     int64_t crow0, ccol0;
     bool a_upper_tri;   // A is upper triangular with zeros below its diagonal blocks: skip k < first row of the tile
+    bool b_upper_tri;   // B [K x N] is upper triangular with zeros below the diagonal: skip k > last column of the tile
 };
 int launch_gemm_f32(const GemmF32& g, hipStream_t s);
 

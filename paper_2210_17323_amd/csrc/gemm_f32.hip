@@ -25,6 +25,7 @@ struct GemmArgs {
     int overwrite, upper_only;
     int64_t crow0, ccol0;
     int a_upper_tri;
+    int b_upper_tri;
     int tiles_m, tiles_n;
     int64_t per_xcd, total;
     int tri_ratio;      // > 0: exactly the upper tiles of a square C are enumerated; value = tile rows / tile columns
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // `multiply` prefetches from at its end): vmcnt(CP) = only the copies of the step after that may be in flight.
     // Past the last step the copies re-read the last panels into a stage nobody multiplies again.
     const int64_t ks0 = g.a_upper_tri ? m0 / LK : 0;             // A upper triangular: nothing left of the tile's rows
-    const int64_t kend = g.K;
+    const int64_t kend = g.b_upper_tri ? min(g.K, n0 + (int64_t)TN_) : g.K;      // B upper triangular: nothing below the tile's last column
     auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur, const unsigned char* nxt) {
         __builtin_amdgcn_s_waitcnt(0x0F70 | CP);                // vmcnt(CP)
         asm volatile("s_barrier" ::: "memory");
@@ -439,6 +440,7 @@ int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
     g.M = p.M; g.N = p.N; g.K = p.K < 0 ? 0 : p.K; g.alpha = p.alpha;
     g.overwrite = p.overwrite; g.upper_only = p.upper_only; g.crow0 = p.crow0; g.ccol0 = p.ccol0;
     g.a_upper_tri = p.a_upper_tri;
+    g.b_upper_tri = p.b_upper_tri && !p.b_is_nk;
     const bool large = (p.M % LM == 0) && (p.N % LN == 0) && (g.K % (4 * LK) == 0) && g.K > 0 && aligned(p.C, 4);
     // 256 x 256 tiles when they still give every CU a couple of tiles (measured: 3-8 % faster on large rectangular
     // and symmetric-update launches; not on the skinny triangular products, whose tiles differ in K length)
