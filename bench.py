@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 # what the same counter reads for a plain 1 GiB copy kernel (factors 2.000 and 1.000): see
 # profiles/layer_solve_opt175b_fc2_pmc_counters.txt (the fetch reading varies between 7.7e7 and 1.35e8 KiB from one
 # collection to the next; this is the one tabulated there).  Keyed by (n, tokens per call); other shapes: not measured.
-MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (1.3475e8 * 2.0 + 5.0918e6 * 1.0) * 1024}
+MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (6.8303e7 * 2.0 + 5.1301e6 * 1.0) * 1024}
 
 
 def parse():
