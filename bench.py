@@ -38,7 +38,9 @@ def parse():
     ap.add_argument("--layer", default="opt175b_fc2", help="opt175b_fc2 (headline) | opt175b_fc1 | opt6.7b_attn | bloom176b_qkv_2bit_g128 | "
                          "bloom176b_out_ternary_g128 | opt175b_q | tiny | opt175b_block (all six linears of a block)")
     ap.add_argument("--tokens", type=int, default=0, help="calibration tokens (default: the layer's own, 262144)")
-    ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptq_hessian_accumulate call")
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="tokens per gptq_hessian_accumulate call (default: 32768; all tokens at once for layers of up to "
+                         "6144 input channels, whose few tiles make the library split the token range of a call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the timed region, run one plain 1 GiB device-to-device copy kernel (dst = src * 1: known "
@@ -133,9 +135,9 @@ def bench_block(a):
                     W[r0:r0 + rows] = lay.weights(row0=r0, nrows=min(rows, lay.r - r0), device=dev)
                 group.append((lay.name, W, lay))
             t = {}
-            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk, m), timings=t)     # warm-up
+            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk or 32768, m), timings=t)     # warm-up
             t = {}
-            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk, m), timings=t)
+            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk or 32768, m), timings=t)
             names = "+".join(l.name for l in lays)
             timings[f"{names}:hessian"] = t["group0:hessian"]
             timings[f"{names}:damp_cholesky_inverse"] = t["group0:damp_cholesky_inverse"]
@@ -199,7 +201,7 @@ def main():
     pbits = 2 if lay.grid == "ternary" else lay.bits
     packed = torch.empty((r, g.packed_words_per_row(n, pbits)), dtype=torch.int32, device=dev)
     grid = g.GPTQ_GRID_TERNARY if lay.grid == "ternary" else g.GPTQ_GRID_MINMAX
-    chunk = min(a.chunk, m)
+    chunk = min(a.chunk or (m if n <= 6144 else 32768), m)
     chunks = [(c0, min(c0 + chunk, m)) for c0 in range(0, m, chunk)]
     h_bytes = g.gptq_hessian_accumulate_workspace_bytes(n, chunk, lay.x.dtype)
     h_ws = torch.empty(h_bytes, dtype=torch.uint8, device=dev) if h_bytes else None

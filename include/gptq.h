@@ -58,10 +58,14 @@ GPTQ_API const char* gptq_last_error(void);
  *       matrix cores; GPTQ_F32: float32 matrix-core products).
  *       X must be 16-byte aligned and ldx a multiple of 8 (f16/bf16) or 4 (f32) elements.
  *   ws  optional workspace (may be NULL) of gptq_hessian_accumulate_workspace_bytes(n, t, xdtype) bytes,
- *       256-byte aligned.  With it, large 16-bit chunks are first repacked so that every 256-channel x
- *       32-token panel step is one contiguous 16 KB block, which the matrix-core kernel copies with far
- *       better cache-line and DRAM-page locality; without it the kernel reads X in place (same result bit
- *       for bit, lower speed).  The size is 0 where the repack is not used.
+ *       256-byte aligned.  With it, 16-bit chunks of layers with at least 2048 channels are first repacked
+ *       so that every 256-channel x 32-token panel step is one contiguous 16 KB block, which the
+ *       matrix-core kernel copies with far better cache-line and DRAM-page locality; for layers whose H has
+ *       few 256 x 256 tiles (up to ~8000 channels) the token range of the call is also split in up to 8
+ *       parts whose partial tiles (held in the workspace) are added in a fixed order, so that all CUs have
+ *       work -- pass such layers long chunks, whole calibration sets if they fit.  Without the workspace
+ *       the kernels read X in place: the same sums up to float32 summation order, at lower speed.
+ *       Repeating a call gives the same bits either way.  The size is 0 where the workspace is not used.
  *   No normalisation by the token count is applied (the quantization result is invariant to the
  *   scale of H).  n == 0 or t == 0 is a valid no-op.
  */

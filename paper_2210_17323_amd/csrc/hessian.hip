@@ -62,6 +62,13 @@ struct SyrkArgs {
     int64_t per_xcd;
     const unsigned char* Xb;    // repacked copy of the chunk (see repack_kernel), or null: copy straight from X
     int64_t nsteps;             // 32-token steps in the repacked chunk
+    // Split token range (direct-to-LDS kernel with a workspace, matrices with few tiles): work item q * total + L
+    // is tile L over steps [q * spp, (q + 1) * spp); with splits > 1 an item writes its partial tile to P and
+    // syrk_reduce_kernel adds the partials of a tile to H in a fixed order.
+    int splits;
+    int64_t spp;                // steps per split (a multiple of 5)
+    int64_t items;              // total * splits
+    float* P;                   // [items][256][256] partial tiles, or null
 };
 
 template <bool IS_BF16>
@@ -291,7 +298,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int64_t xcd = w % NXCD, slot_step = gridDim.x / NXCD;
     int64_t slot = w / NXCD;
     auto tile_at = [&](int64_t sl) { return ((sl / 32) * NXCD + xcd) * 32 + (sl % 32); };
-    if (tile_at(slot) >= g.total) return;
+    if (tile_at(slot) >= g.items) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -304,13 +311,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     int64_t r0 = 0, c0 = 0;                              // origin of the tile whose panels are being copied
     const unsigned char* blkA = nullptr;
     const unsigned char* blkB = nullptr;
-    auto set_tile = [&](int64_t L) {
+    float* part = nullptr;                               // where this item's partial tile goes (split token range)
+    auto set_tile = [&](int64_t item) {
+        const int64_t q = item / g.total, L = item - q * g.total;
         int bi, bj;
         syrk_tile_of(g.nt, L, bi, bj);
         r0 = (int64_t)bi * BT; c0 = (int64_t)bj * BT;
         if (BLOCKED) {
-            blkA = g.Xb + (int64_t)bi * g.nsteps * 16384 + wave * 4096 + lane * 16;
-            blkB = g.Xb + (int64_t)bj * g.nsteps * 16384 + wave * 4096 + lane * 16;
+            blkA = g.Xb + ((int64_t)bi * g.nsteps + q * g.spp) * 16384 + wave * 4096 + lane * 16;
+            blkB = g.Xb + ((int64_t)bj * g.nsteps + q * g.spp) * 16384 + wave * 4096 + lane * 16;
+            part = g.P ? g.P + item * (int64_t)(BT * BT) : nullptr;
         }
     };
     auto issue_copies = [&](unsigned char* stage, int64_t k0) {
@@ -394,10 +404,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     auto next_stage = [&](unsigned char* refill, int64_t k_refill, const unsigned char* cur, const unsigned char* nxt) {
         __builtin_amdgcn_s_waitcnt(0x4F70);             // vmcnt(16)
         asm volatile("s_barrier" ::: "memory");         // the next step's stage is complete; everybody left `refill`
-        issue_copies(refill, min(k_refill, g.t - DK));
+        issue_copies(refill, min(k_refill, (g.spp - 1) * DK));
         multiply(cur, nxt);
     };
-    const int64_t ksteps = g.t / DK;                    // a multiple of 5 (the caller passes t % 160 == 0)
+    const int64_t ksteps = g.spp;                       // a multiple of 5 (the caller pads or splits off the tail)
     set_tile(tile_at(slot));
     issue_copies(stage0, 0);
     issue_copies(stage1, DK);
@@ -426,8 +436,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // The next tile's first four steps start now.  Another wavefront may still be in its last multiply:
         // that one reads stage 4, which is not refilled here, and prefetches fragments from stage 0 that nobody uses.
         const int64_t er0 = r0, ec0 = c0;
+        float* const epart = part;
         slot += slot_step;
-        const bool more = tile_at(slot) < g.total;
+        const bool more = tile_at(slot) < g.items;
         if (more) {
             set_tile(tile_at(slot));
             issue_copies(stage0, 0);
@@ -439,6 +450,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // ---- H += 2 * acc with the memory system's float add (no value comes back, so nothing waits for a round
         // trip; reading H first cost ~25 us of exposed latency per 760 us tile).  Each element of H belongs to
         // exactly one tile of the launch, so the sum is the same float32 add in the same order as a load-add-store.
+        if (BLOCKED && epart) {
+            // split token range: the partial tile as it is, whole (rows and columns past n hold zeros)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float* pb = epart + (wm * 128 + s * 32 + 4 * lhi) * BT + wn * 128 + u * 32 + l32;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) pb[(8 * (i >> 2) + (i & 3)) * BT] = acc[s][u][i];
+                }
+            if (!more) break;
+            continue;
+        }
         const bool inside = (er0 + BT <= g.n) && (ec0 + BT <= g.n);
 #pragma unroll
         for (int s = 0; s < 4; ++s)
@@ -463,6 +487,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
 }
 
+// H tile += 2 * (P[0] + P[1] + ... + P[splits-1]), the partial tiles of one tile in the order of their token
+// ranges.  One workgroup per tile and 32-row slab, one thread per column.
+__global__ __launch_bounds__(256) void syrk_reduce_kernel(SyrkArgs g) {
+    const int64_t L = blockIdx.x;
+    int bi, bj;
+    syrk_tile_of(g.nt, L, bi, bj);
+    const int64_t col = (int64_t)bj * 256 + threadIdx.x;
+    for (int r = 0; r < 32; ++r) {
+        const int rt = blockIdx.y * 32 + r;
+        const int64_t row = (int64_t)bi * 256 + rt;
+        float sum = 0.f;
+        for (int q = 0; q < g.splits; ++q) sum += g.P[((int64_t)q * g.total + L) * 65536 + rt * 256 + threadIdx.x];
+        if (row < g.n && col < g.n) g.H[row * g.ldh + col] += 2.0f * sum;
+    }
+}
+
+// How a chunk of t tokens of an n-channel layer goes through the direct-to-LDS kernel with a workspace.
+// Matrices with fewer than four 256 x 256 tiles per CU leave much of the chip idle at the end of a launch (or
+// all along: n = 4096 has 136 tiles for 256 CUs), so their token range is split into up to 8 parts: the split
+// count that fills whole rounds of 256 workgroups best, at a small charge per split for the partial tiles.
+struct SyrkPlan { int splits; int64_t nsteps; size_t repack_bytes, partial_bytes; };
+static SyrkPlan syrk_plan(int64_t n, int64_t t) {
+    const int64_t nt = ceil_div(n, 256), tiles = nt * (nt + 1) / 2, steps = ceil_div(t, DK);
+    int best = 1;
+    if (tiles < 1024) {
+        double best_score = -1.0;
+        for (int S = 1; S <= 8; ++S) {
+            if (S > 1 && steps < 20 * (int64_t)S) break;             // a part should be at least 20 steps long
+            const int64_t items = tiles * S;
+            const double score = (double)items / (double)(ceil_div(items, 256) * 256) - 0.01 * (S - 1);
+            if (score > best_score + 1e-9) { best_score = score; best = S; }
+        }
+    }
+    SyrkPlan p;
+    p.splits = best;
+    p.nsteps = ceil_div(steps, 5 * (int64_t)best) * 5 * best;         // zero-padded to whole trips of the 5-stage loop per part
+    p.repack_bytes = round_up((size_t)nt * 256 * (size_t)p.nsteps * DK * 2, 256);
+    p.partial_bytes = best > 1 ? (size_t)best * tiles * 65536 * sizeof(float) : 0;
+    return p;
+}
+
 static void syrk_schedule(SyrkArgs& g, int BT) {
     g.nt = (int)ceil_div(g.n, BT);
     g.total = syrk_total_tiles(g.nt);
@@ -472,12 +537,23 @@ static void syrk_schedule(SyrkArgs& g, int BT) {
 template <bool IS_BF16>
 static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s, bool token_major = false) {
     syrk_schedule(g, 256);
-    g.per_xcd = ceil_div(ceil_div(g.total, 32), NXCD) * 32;      // whole patches of 32 slots per XCD
+    g.Xb = static_cast<const unsigned char*>(ws);
+    g.splits = 1; g.P = nullptr;
+    if (ws) {
+        const SyrkPlan plan = syrk_plan(g.n, g.t);
+        g.splits = plan.splits;
+        g.nsteps = plan.nsteps;
+        g.spp = g.nsteps / g.splits;
+        if (plan.partial_bytes) g.P = reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + plan.repack_bytes);
+    } else {
+        g.nsteps = g.t / DK;
+        g.spp = g.nsteps;
+    }
+    g.items = g.total * g.splits;
+    g.per_xcd = ceil_div(ceil_div(g.items, 32), NXCD) * 32;      // whole patches of 32 slots per XCD
     if (g.per_xcd * NXCD > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
     const int64_t blocks = std::min<int64_t>(g.per_xcd, 32) * NXCD;   // persistent: one workgroup per CU walks its slots
-    g.Xb = static_cast<const unsigned char*>(ws);
     if (ws) {
-        g.nsteps = ceil_div(ceil_div(g.t, DK), 5) * 5;           // zero-padded to whole trips of the 5-stage loop
         const int64_t rgroups = (int64_t)g.nt * 16, tgroups = ceil_div(g.nsteps, 16);
         if (tgroups > 65535 || g.nsteps > 65535) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: chunk too long for the repack grid (split the call)");
         if (token_major)
@@ -489,8 +565,11 @@ static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s, bool token_major
         GPTQ_LAUNCH_CHECK();
         g.t = g.nsteps * DK;
         hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, true>), dim3((unsigned)blocks), dim3(256), 0, s, g);
+        if (g.P) {
+            GPTQ_LAUNCH_CHECK();
+            hipLaunchKernelGGL(syrk_reduce_kernel, dim3((unsigned)g.total, 8), dim3(256), 0, s, g);
+        }
     } else {
-        g.nsteps = g.t / DK;
         hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, false>), dim3((unsigned)blocks), dim3(256), 0, s, g);
     }
     GPTQ_LAUNCH_CHECK();
@@ -533,9 +612,13 @@ __global__ __launch_bounds__(256) void symmetrize_kernel(float* H, int64_t ld, i
 
 using namespace gptq;
 
+constexpr int64_t SYRK_DMA_MIN_N = 2048;        // below this even a split token range leaves most CUs without a tile
+
 static size_t syrk_ws_bytes(int64_t n, int64_t t, int xdtype) {
-    if (xdtype == GPTQ_F32 || n <= 6144) return 0;
-    return (size_t)ceil_div(n, 256) * 256 * (size_t)(ceil_div(t, DMA_TOKENS) * DMA_TOKENS) * 2;
+    if (xdtype == GPTQ_F32 || n < SYRK_DMA_MIN_N) return 0;
+    const SyrkPlan p = syrk_plan(n, t);
+    if (n <= 6144 && p.splits == 1) return 0;       // too few tokens to split: the 128-tile kernel does better
+    return p.repack_bytes + p.partial_bytes;
 }
 
 extern "C" size_t gptq_hessian_accumulate_workspace_bytes(int64_t n, int64_t t, int xdtype) {
@@ -567,12 +650,14 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
     SyrkArgs g{};
     g.H = H; g.ldh = ldh; g.X = static_cast<const uint16_t*>(X); g.ldx = ldx; g.n = n; g.t = t;
     const bool bf = xdtype == GPTQ_BF16;
+    // With a workspace the chunk is first repacked into contiguous, zero-padded panel steps (much better
+    // DRAM-page and cache-line locality for the copies) and the direct-to-LDS kernel takes all of it; matrices
+    // with few tiles get their token range split (see syrk_plan).
+    const size_t need = syrk_ws_bytes(n, t, xdtype);
+    if (need && ws && aligned(ws, 256) && ws_bytes >= need)
+        return bf ? launch_syrk_dma<true>(g, ws, s) : launch_syrk_dma<false>(g, ws, s);
     if (n <= 6144)                  // 256-wide tiles only fill the chip when there are enough of them
         return bf ? launch_syrk<true, 128, 2, 2>(g, s) : launch_syrk<false, 128, 2, 2>(g, s);
-    // With a workspace the chunk is first repacked into contiguous, zero-padded panel steps (much better
-    // DRAM-page and cache-line locality for the copies) and the direct-to-LDS kernel takes all of it.
-    if (ws && aligned(ws, 256) && ws_bytes >= syrk_ws_bytes(n, t, xdtype))
-        return bf ? launch_syrk_dma<true>(g, ws, s) : launch_syrk_dma<false>(g, ws, s);
     // Without one the kernel copies straight from X: whole trips of its 5-stage loop (160 tokens) go through
     // it, the tail through the guarded kernel.
     const int64_t t_main = t / DMA_TOKENS * DMA_TOKENS;
@@ -592,7 +677,8 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
 }
 
 static size_t syrk_token_major_ws_bytes(int64_t n, int64_t t) {
-    return (size_t)ceil_div(n, 256) * 256 * (size_t)(ceil_div(t, DMA_TOKENS) * DMA_TOKENS) * 2;
+    const SyrkPlan p = syrk_plan(n, t);
+    return p.repack_bytes + p.partial_bytes;
 }
 
 extern "C" size_t gptq_hessian_accumulate_token_major_workspace_bytes(int64_t n, int64_t t, int xdtype) {

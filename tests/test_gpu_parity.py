@@ -46,7 +46,7 @@ def _rel_fro(a, b):
 
 # ------------------------------------------------------------------ step 1: Hessian
 
-@pytest.mark.parametrize("case", ["cfg1_f32", "f16_ragged_small", "bf16_small", "f16_big_tiles"])
+@pytest.mark.parametrize("case", ["cfg1_f32", "f16_ragged_small", "bf16_small", "f16_big_tiles", "f16_split_tokens", "bf16_split_tokens"])
 def test_hessian_matches_oracle(case):
     _say(f"hessian case={case}")
     if case == "cfg1_f32":
@@ -55,6 +55,10 @@ def test_hessian_matches_oracle(case):
         X = _layer(configs.config2()[0], 320, 8, 1000).x.tile(device="cuda")
     elif case == "bf16_small":
         X = _layer(configs.config3()[1], 200, 8, 264).x.tile(device="cuda").to(torch.bfloat16)
+    elif case == "f16_split_tokens":        # 45 tiles: with a workspace the token range is split and partial tiles are reduced
+        X = _layer(configs.config3()[1], 2300, 8, 4000).x.tile(device="cuda")
+    elif case == "bf16_split_tokens":       # 105 tiles, ragged in n and in t
+        X = _layer(configs.config3()[1], 3500, 8, 3000).x.tile(device="cuda").to(torch.bfloat16)
     else:
         X = _layer(configs.config3()[1], 6416, 8, 2056).x.tile(device="cuda")
     n = X.shape[0]
@@ -76,11 +80,15 @@ def test_hessian_matches_oracle(case):
         H2 = _padded(n, n, torch.float32, 4)
         g.gptq_hessian_accumulate(H2, X, ws)
         g.gptq_hessian_symmetrize(H2)
-        assert torch.allclose(H2, H, rtol=2e-6, atol=0)
+        assert torch.allclose(H2, H, rtol=2e-6, atol=1e-30)
         assert _rel_fro(H2.double().cpu().numpy(), want) <= 1e-5
+        H3 = _padded(n, n, torch.float32, 4)          # the same call again: the same bits (partial tiles are summed in a fixed order)
+        g.gptq_hessian_accumulate(H3, X, ws)
+        g.gptq_hessian_symmetrize(H3)
+        assert torch.equal(H3, H2)
 
 
-@pytest.mark.parametrize("n,t,dtype", [(6416, 2056, torch.float16), (320, 1000, torch.float16), (200, 264, torch.bfloat16), (1, 1, torch.float16)])
+@pytest.mark.parametrize("n,t,dtype", [(6416, 2056, torch.float16), (2300, 4000, torch.float16), (320, 1000, torch.float16), (200, 264, torch.bfloat16), (1, 1, torch.float16)])
 def test_hessian_token_major_matches_oracle(n, t, dtype):
     # activations given as [tokens x channels], the layout of a layer input
     _say(f"hessian token-major n={n} t={t} {dtype}")
