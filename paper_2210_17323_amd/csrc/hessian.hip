@@ -505,19 +505,20 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(SyrkArgs g) {
 
 // How a chunk of t tokens of an n-channel layer goes through the direct-to-LDS kernel with a workspace.
 // Matrices with fewer than four 256 x 256 tiles per CU leave much of the chip idle at the end of a launch (or
-// all along: n = 4096 has 136 tiles for 256 CUs), so their token range is split into up to 8 parts: the split
-// count that fills whole rounds of 256 workgroups best, at a small charge per split for the partial tiles.
+// all along: n = 4096 has 136 tiles for 256 CUs), so their token range is split into up to 8 parts.  The split
+// count minimises a simple cost: rounds of 256 workgroups x (steps per part x 0.76 us + a fixed cost per work
+// item: ~8 us to start and to add a tile to H, ~30 us when a partial tile is written, read back and reduced).
 struct SyrkPlan { int splits; int64_t nsteps; size_t repack_bytes, partial_bytes; };
 static SyrkPlan syrk_plan(int64_t n, int64_t t) {
     const int64_t nt = ceil_div(n, 256), tiles = nt * (nt + 1) / 2, steps = ceil_div(t, DK);
     int best = 1;
     if (tiles < 1024) {
-        double best_score = -1.0;
+        double best_cost = 0.0;
         for (int S = 1; S <= 8; ++S) {
             if (S > 1 && steps < 20 * (int64_t)S) break;             // a part should be at least 20 steps long
-            const int64_t items = tiles * S;
-            const double score = (double)items / (double)(ceil_div(items, 256) * 256) - 0.01 * (S - 1);
-            if (score > best_score + 1e-9) { best_score = score; best = S; }
+            const double rounds = (double)ceil_div(tiles * S, 256);
+            const double cost = rounds * ((double)ceil_div(steps, S) * 0.76 + (S > 1 ? 30.0 : 8.0));
+            if (S == 1 || cost < best_cost * 0.98) { best_cost = cost; best = S; }
         }
     }
     SyrkPlan p;

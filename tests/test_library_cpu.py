@@ -24,8 +24,8 @@ def test_workspace_sizes():
     assert 12288 * 49152 * 4 < big < 12288 * 49152 * 4 * 1.05 + (1 << 24)      # W copy + two r x 1024 error panels
     assert g.gptq_quantize_layer_workspace_bytes(0, 0) > 0
     assert g.gptq_hessian_accumulate_workspace_bytes(49152, 32768) == 49152 * 32800 * 2
-    # few tiles (136 for 256 CUs): the token range is split in 7, repacked chunk + 7 partial tiles per tile
-    assert g.gptq_hessian_accumulate_workspace_bytes(4096, 32768) == 4096 * 33600 * 2 + 7 * 136 * 65536 * 4
+    # few tiles (136 for 256 CUs): the token range is split in 5, repacked chunk + 5 partial tiles per tile
+    assert g.gptq_hessian_accumulate_workspace_bytes(4096, 32768) == 4096 * 32800 * 2 + 5 * 136 * 65536 * 4
     assert g.gptq_hessian_accumulate_workspace_bytes(1024, 32768) == 0       # small matrices: the 128-tile kernel, no workspace
     assert g.gptq_hessian_accumulate_workspace_bytes(4096, 256) == 0         # too few tokens to split
 
