@@ -131,7 +131,8 @@ def test_hessian_exact_on_small_integers_and_chunked():
 
 # ------------------------------------------------------------------ step 2: damp + Cholesky of the inverse
 
-@pytest.mark.parametrize("n,kind", [(256, "cfg1"), (1000, "lognormal"), (2048, "relu"), (3200, "lognormal"), (100, "lognormal"), (4, "lognormal")])
+@pytest.mark.parametrize("n,kind", [(256, "cfg1"), (1000, "lognormal"), (2048, "relu"), (3200, "lognormal"), (100, "lognormal"), (4, "lognormal"),
+                                    (129, "lognormal"), (1153, "relu")])      # one row past a diagonal block / past an outer block
 def test_cholesky_inverse_matches_oracle(n, kind):
     _say(f"cholesky n={n} kind={kind}")
     if kind == "cfg1":
@@ -211,6 +212,9 @@ QUANT_CASES = [
     (3, "minmax", 0, torch.float16, 72, 3328),        # four outer blocks: the trailing update runs on two streams
     (2, "minmax", 128, torch.float16, 64, 3072),
     (3, "minmax", 0, torch.float16, 1, 8),
+    (2, "minmax", 0, torch.float16, 257, 384),        # one row past a workgroup of the block kernel
+    (4, "minmax", 0, torch.bfloat16, 300, 129),       # one column past a block
+    (4, "minmax", 64, torch.bfloat16, 300, 192),      # a block and a half, groups inside the block
 ]
 
 
