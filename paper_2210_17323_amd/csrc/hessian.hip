@@ -6,9 +6,10 @@
 //
 // Kernel layout (fp16/bf16): a workgroup owns a BT x BT tile of H and walks the token axis in steps
 // of 64.  Per step it stages BT x 64 halves of the row panel and of the column panel in LDS (row
-// pitch 128 bytes; the 16-byte chunk index is XOR-swizzled with the row so that both the
-// row-wise stores and the 32-rows-at-one-chunk MFMA operand reads are bank-conflict free), with
-// the next step prefetched into registers.  Tiles are enumerated in strips of 8 tile columns
+// pitch 128 bytes; the 16-byte chunk index is XOR-swizzled with (row / 2) % 8: a 16-byte access is
+// served 16 lanes at a time and rows 2 apart share banks, so both the row-wise stores and the
+// one-chunk-of-16-consecutive-rows MFMA operand reads are bank-conflict free), with the next step
+// prefetched into registers.  Tiles are enumerated in strips of 8 tile columns
 // walked top to bottom and each XCD gets a contiguous range of that order, so the 32 workgroups
 // resident on one XCD form a ~4 x 8 patch of tiles that shares its row and column panels in L2.
 #include "common.h"
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
         for (int i = 0; i < CH; ++i) {
             const int q = tid + NT * i;
             const int row = q >> 3, ch = q & 7;
-            const int off = row * 128 + ((ch ^ (row & 7)) << 4);
+            const int off = row * 128 + ((ch ^ ((row >> 1) & 7)) << 4);
             *reinterpret_cast<uint4*>(base + off) = ra[i];
             *reinterpret_cast<uint4*>(base + PANEL + off) = rb[i];
         }
@@ -165,12 +166,12 @@ __global__ __launch_bounds__(64 * WM * WN) void syrk_f16_kernel(SyrkArgs g) {
 #pragma unroll
             for (int s = 0; s < SM; ++s) {
                 const int row = wm * (BT / WM) + s * 32 + l32;
-                fa[s] = *reinterpret_cast<const uint4*>(pa + row * 128 + ((ch ^ (row & 7)) << 4));
+                fa[s] = *reinterpret_cast<const uint4*>(pa + row * 128 + ((ch ^ ((row >> 1) & 7)) << 4));
             }
 #pragma unroll
             for (int u = 0; u < SN; ++u) {
                 const int row = wn * (BT / WN) + u * 32 + l32;
-                fb[u] = *reinterpret_cast<const uint4*>(pb + row * 128 + ((ch ^ (row & 7)) << 4));
+                fb[u] = *reinterpret_cast<const uint4*>(pb + row * 128 + ((ch ^ ((row >> 1) & 7)) << 4));
             }
 #pragma unroll
             for (int s = 0; s < SM; ++s)
