@@ -7,11 +7,11 @@
 //       registers and walks the columns in order: code = clamp(rint(w/scale) + zero), q = grid
 //       value, e = (w - q) / U[j][j], then w[k] -= e * U[j][k] for the later columns of the block.
 //       Rows are independent (the Hessian information U is shared by all rows), so there is no
-//       cross-lane traffic at all; the 128 x 128 block of U is the same for every lane: the workgroup
-//       copies it into LDS once and every lane reads it back with uniform (broadcast) addresses, four
-//       values per instruction and many rows ahead of their use.  The column loop is fully unrolled so
-//       every register index is static.  Outputs: codes, the block's error matrix E (r x 128), per-row
-//       sum of e^2.
+//       cross-lane traffic between rows; the 128 x 128 block of U is the same for every lane: the
+//       workgroup copies it into LDS once, 16 consecutive values of a row of U are read into one
+//       register spread over 16 lanes, and each multiply-add picks its value out of that register with
+//       the DPP row broadcast.  The column loop is unrolled by template recursion so every register
+//       index is static.  Outputs: codes, the block's error matrix E (r x 128), per-row sum of e^2.
 //   trailing update    : W[:, i+B:] -= E * U[i:i+B, i+B:], the float32 matrix-core GEMM, applied at once to
 //       the rest of the current 1024-column outer block and deferred (rank 1024) for the columns beyond.
 #include "common.h"
@@ -109,28 +109,32 @@ struct QuantArgs {
 };
 
 // ---- the stream of U values ------------------------------------------------------------------------------
-// Row j of the block of U is needed from the aligned quad (4 floats) that holds column j: the diagonal
-// element and the elements right of it.  All rows' quads, in the order of their
-// use, form one stream; it is read from LDS through a ring of RING register quads: the quad at stream position
-// t + RING is requested right after the one at position t has been used, so a request runs RING quads -- a few
-// hundred cycles -- ahead of its use, also across the serial arithmetic at a column.  Rows, quads and ring
-// slots are template parameters: every register index is a constant by construction.
+// Row j of the block of U is needed from the aligned chunk of 16 floats that holds column j: the diagonal
+// element and the elements right of it.  A chunk sits in ONE register: lane l holds element l % 16 (the same
+// 16 values in each of the wavefront's four rows of 16 lanes), and the multiply-add that needs element c reads
+// it from lane c of its own row through the DPP row broadcast -- v_fmac_f32_dpp ... row_newbcast:c -- so a value
+// of U reaches all 64 lanes inside the instruction that uses it.  (Reading each value into every lane with
+// 16-byte LDS reads cost as many issue cycles per value as the multiply-add itself.)
+// All rows' chunks, in the order of their use, form one stream; it is read from LDS through a ring of RING
+// registers: the chunk at stream position t + RING is requested right after the one at position t has been used,
+// so a request runs well over a thousand cycles ahead of its use, also across the serial arithmetic at a column.
+// Rows, chunks and ring slots are template parameters: every register index is a constant by construction.
 namespace ustream {
-constexpr int RING = 16;
-constexpr int first_col(int j) { return (j / 4) * 4; }
-constexpr int quads(int j) { return (QB - first_col(j)) / 4; }
-constexpr int start(int j) { int s = 0; for (int i = 0; i < j; ++i) s += quads(i); return s; }
+constexpr int RING = 8;
+constexpr int CHUNK = 16;
+constexpr int first_chunk(int j) { return j / CHUNK; }
+constexpr int chunks(int j) { return QB / CHUNK - first_chunk(j); }
+constexpr int start(int j) { int s = 0; for (int i = 0; i < j; ++i) s += chunks(i); return s; }
 constexpr int TOTAL = start(QB);
-constexpr int row_at(int t) { int j = 0; while (t >= quads(j)) { t -= quads(j); ++j; } return j; }
+constexpr int row_at(int t) { int j = 0; while (t >= chunks(j)) { t -= chunks(j); ++j; } return j; }
 }  // namespace ustream
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(3))) float* lds_floats;
-typedef const __attribute__((address_space(3))) f32x4* lds_quads;
+typedef const volatile __attribute__((address_space(3))) float* lds_floats_ordered;
 
 struct QuantState {
     float w[QB];                        // working weights of the block; e_j once column j is done
-    f32x4 ring[ustream::RING];
+    float ring[ustream::RING];
     uint32_t packed[QB / 4];            // codes, four to a word
     float e2, scale, zf;
     int zero;
@@ -138,47 +142,51 @@ struct QuantState {
     bool active;                        // row inside the matrix
 };
 
-typedef const volatile __attribute__((address_space(3))) f32x4* lds_quads_ordered;
-
-// Volatile on purpose: volatile accesses and asm statements keep their program order, which is what places
-// each request RING quads ahead of its use.  An ordinary load has no such order: with the whole column loop
-// one straight line, the compiler either hoists all requests to the top (and spills them) or sinks each one
-// down to its use (and then waits for it).
+// Volatile on purpose: volatile accesses and volatile asm statements (the multiply-adds below) keep their
+// program order, which is what places each request RING chunks ahead of its use.  An ordinary load has no such
+// order: with the whole column loop one straight line, the compiler either hoists all requests to the top or
+// sinks each one down to its use and then waits for it.  `ubl` is the block in LDS offset by lane % 16.
 template <int T>
-__device__ __forceinline__ void request_quad(QuantState& st, lds_floats ubs) {
+__device__ __forceinline__ void request_chunk(QuantState& st, lds_floats ubl) {
     if constexpr (T < ustream::TOTAL) {
-        constexpr int j = ustream::row_at(T), q = T - ustream::start(j);
-        st.ring[T % ustream::RING] = *reinterpret_cast<lds_quads_ordered>(ubs + j * QB + ustream::first_col(j) + 4 * q);
+        constexpr int j = ustream::row_at(T), q = ustream::first_chunk(j) + (T - ustream::start(j));
+        st.ring[T % ustream::RING] = *static_cast<lds_floats_ordered>(ubl + j * QB + ustream::CHUNK * q);
     }
 }
 
 template <int... T>
-__device__ __forceinline__ void request_first(QuantState& st, lds_floats ubs, std::integer_sequence<int, T...>) {
-    (request_quad<T>(st, ubs), ...);
+__device__ __forceinline__ void request_first(QuantState& st, lds_floats ubl, std::integer_sequence<int, T...>) {
+    (request_chunk<T>(st, ubl), ...);
 }
 
-// w[kq .. kq+3] -= e * U[J][kq .. kq+3] for the columns right of J, then the request that refills the slot.
-// The empty asm statement takes the quad's results as operands, which puts it -- and with it the request
-// that follows -- behind this quad's arithmetic, so the request can reuse the quad's registers; it hands -e
-// on to the next quad, which puts that quad's arithmetic behind it.
+// w[k] += ne * (element C of the chunk in `u`), for all lanes.  The s_nop covers the two wait states a DPP read
+// needs after a vector-ALU write of the same register, should the compiler ever have moved the chunk there.
+template <int C, bool FIRST>
+__device__ __forceinline__ void fma_bcast(float& w, float u, float ne) {
+    if constexpr (FIRST)
+        asm volatile("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(w) : "v"(u), "v"(ne), "n"(C));
+    else
+        asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(w) : "v"(u), "v"(ne), "n"(C));
+}
+
+template <int J, int K0, int... C>
+__device__ __forceinline__ void update_chunk_columns(QuantState& st, float u, float ne, std::integer_sequence<int, C...>) {
+    // columns K0 + C right of J; the first one issued carries the s_nop
+    constexpr int first = (J >= K0) ? J - K0 + 1 : 0;
+    ((K0 + C > J ? fma_bcast<C, C == first>(st.w[K0 + C], u, ne) : (void)0), ...);
+}
+
+// w[k] -= e * U[J][k] for the columns of chunk Q right of J, then the request that refills the slot
 template <int J, int Q>
-__device__ __forceinline__ void update_quad(QuantState& st, lds_floats ubs, float& ne) {
-    constexpr int t = ustream::start(J) + Q, kq = ustream::first_col(J) + 4 * Q;
-    const f32x4 u = st.ring[t % ustream::RING];
-    if constexpr (kq + 0 > J) st.w[kq + 0] = fmaf(ne, u.x, st.w[kq + 0]);
-    if constexpr (kq + 1 > J) st.w[kq + 1] = fmaf(ne, u.y, st.w[kq + 1]);
-    if constexpr (kq + 2 > J) st.w[kq + 2] = fmaf(ne, u.z, st.w[kq + 2]);
-    if constexpr (kq + 3 > J) st.w[kq + 3] = fmaf(ne, u.w, st.w[kq + 3]);
-    if constexpr (t + ustream::RING < ustream::TOTAL) {
-        if constexpr (kq > J) asm volatile("" : "+v"(st.w[kq]), "+v"(st.w[kq + 1]), "+v"(st.w[kq + 2]), "+v"(st.w[kq + 3]), "+v"(ne));
-        else asm volatile("" : "+v"(st.w[kq + 1]), "+v"(st.w[kq + 2]), "+v"(st.w[kq + 3]), "+v"(ne));
-        request_quad<t + ustream::RING>(st, ubs);
-    }
+__device__ __forceinline__ void update_chunk(QuantState& st, lds_floats ubl, float ne) {
+    constexpr int t = ustream::start(J) + Q, k0 = ustream::CHUNK * (ustream::first_chunk(J) + Q);
+    update_chunk_columns<J, k0>(st, st.ring[t % ustream::RING], ne, std::make_integer_sequence<int, ustream::CHUNK>{});
+    request_chunk<t + ustream::RING>(st, ubl);
 }
 
 template <int J, int... Q>
-__device__ __forceinline__ void update_row(QuantState& st, lds_floats ubs, float ne, std::integer_sequence<int, Q...>) {
-    (update_quad<J, Q>(st, ubs, ne), ...);
+__device__ __forceinline__ void update_row(QuantState& st, lds_floats ubl, float ne, std::integer_sequence<int, Q...>) {
+    (update_chunk<J, Q>(st, ubl, ne), ...);
 }
 
 // Column J of the block: its grid if a group starts here, the code, the error, the update of the columns right of it.
@@ -205,8 +213,9 @@ __device__ __forceinline__ void quantize_column(QuantState& st, lds_floats ubs, 
     // e = (w - q) / U[J][J]: reciprocal estimate, then one correction step with the exact remainder -- the
     // rounded quotient at a third of the instructions of the general division (no range scaling: U[J][J] is
     // the square root of a diagonal element of the inverse Hessian, far from the ends of the float range)
-    constexpr int diag_slot = ustream::start(J) % ustream::RING;        // row J's first quad holds U[J][J]
-    const float ujj = st.ring[diag_slot][J % 4];
+    constexpr int diag_slot = ustream::start(J) % ustream::RING;        // row J's first chunk holds U[J][J]
+    const float ujj = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, st.ring[diag_slot]),
+                                                                            0x150 + J % ustream::CHUNK, 0xf, 0xf, true));   // row_newbcast
     const float rcp = __builtin_amdgcn_rcpf(ujj);
     const float d = st.w[J] - q;
     const float e0 = d * rcp;
@@ -220,7 +229,7 @@ __device__ __forceinline__ void quantize_column(QuantState& st, lds_floats ubs, 
     // store the same values to the same place as that row's own lane.
     if constexpr ((J & 3) == 3)
         *reinterpret_cast<float4*>(st.edst + J - 3) = make_float4(st.w[J - 3], st.w[J - 2], st.w[J - 1], st.w[J]);
-    update_row<J>(st, ubs, -e, std::make_integer_sequence<int, ustream::quads(J)>{});
+    update_row<J>(st, ubs, -e, std::make_integer_sequence<int, ustream::chunks(J)>{});
 }
 
 template <int G, int... J>
@@ -234,6 +243,26 @@ __device__ __forceinline__ void quantize_columns(QuantState& st, lds_floats ubs,
 //        current register values at each group start.
 template <int G>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void quant_block_kernel(QuantArgs a) {
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool active = row < a.r;
+    const int64_t rr = active ? row : a.r - 1;
+    // This lane's 128 working weights first: 32 scattered 16-byte loads (lanes are a whole row apart) whose round
+    // trips then overlap the staging of U below.
+    QuantState st;
+    float (&w)[QB] = st.w;
+    {
+        const float* src = a.Wk + rr * a.ldk + a.j0;
+        if (a.nbk == QB) {
+#pragma unroll
+            for (int k = 0; k < QB; k += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(src + k);
+                w[k] = v.x; w[k + 1] = v.y; w[k + 2] = v.z; w[k + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < QB; ++k) w[k] = (k < a.nbk) ? src[k] : 0.f;
+        }
+    }
     // ---- the diagonal block of U into LDS: ubs[j][k] = U[j0+j][j0+k] for k >= j, identity outside the
     //      matrix.  16 independent 16-byte loads per thread.
     __shared__ __align__(16) float ubs[QB * QB];
@@ -264,24 +293,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
         __syncthreads();
     }
-    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const bool active = row < a.r;
-    const int64_t rr = active ? row : a.r - 1;
-    QuantState st;
-    float (&w)[QB] = st.w;
-    {
-        const float* src = a.Wk + rr * a.ldk + a.j0;
-        if (a.nbk == QB) {
-#pragma unroll
-            for (int k = 0; k < QB; k += 4) {
-                const float4 v = *reinterpret_cast<const float4*>(src + k);
-                w[k] = v.x; w[k + 1] = v.y; w[k + 2] = v.z; w[k + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < QB; ++k) w[k] = (k < a.nbk) ? src[k] : 0.f;
-        }
-    }
     const float maxq = (float)a.maxq;
     st.scale = 1.f; st.zero = 0;
     if (G == 0) {
@@ -291,7 +302,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     st.zf = (float)st.zero;
     st.e2 = 0.f;
-    lds_floats ub = (lds_floats)ubs;
+    lds_floats ub = (lds_floats)ubs + (threadIdx.x & 15);           // this lane's element of every chunk
     request_first(st, ub, std::make_integer_sequence<int, ustream::RING>{});
     st.active = active;
     st.edst = a.E + rr * a.lde;
