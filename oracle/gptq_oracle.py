@@ -17,10 +17,11 @@ oracle follows the algorithm's steps in the paper's order and notation:
   minmax_grid / ternary_grid   the quantization grids           (Section 4, Setup; "Extreme Quantization")
   pack_codes / unpack_codes    dense b-bit stream               (layout is this build's; the paper gives none)
 
-Arithmetic is float64, except the one place where floating point decides an integer: the grid
-parameters (scale, zero point) and the rounding w -> code are evaluated in float32, the precision
-in which the GPU kernel takes the same decision (`decision_dtype`; pass np.float64 to take it in
-float64 instead).
+Arithmetic is float64 throughout, including the one place where floating point decides an integer:
+the grid parameters (scale, zero point) and the rounding w -> code.  `decision_dtype=np.float32`
+evaluates just that decision (the grid parameters and w/scale) in float32 instead, the precision in
+which a float32 implementation takes it; everything else stays float64.  Tests compare the GPU path
+with both variants.
 
 Pins (tests/test_oracle_*.py): diagonal H reduces to RTN exactly; the blocked Cholesky form equals
 the naive Eq. 2 + Eq. 3 procedure; codes lie on the grid; brute force on <= 6 columns is never
@@ -84,7 +85,7 @@ def hinv_cholesky_upper_reverse(Hd) -> np.ndarray:
 # Grids
 # --------------------------------------------------------------------------------------------
 
-def minmax_grid(w, bits: int, decision_dtype=np.float32):
+def minmax_grid(w, bits: int, decision_dtype=np.float64):
     """Uniform asymmetric min-max grid for each row of w (Section 4, Setup).
 
     The range is widened to contain 0 so that an integer zero point in [0, maxq] exists:
@@ -103,7 +104,7 @@ def minmax_grid(w, bits: int, decision_dtype=np.float32):
     return scale.astype(decision_dtype), zero.astype(np.int64)
 
 
-def ternary_grid(w, decision_dtype=np.float32):
+def ternary_grid(w, decision_dtype=np.float64):
     """Levels {-s, 0, +s} with s = max|w| per row (s = 1 for an all-zero row), stored as codes
     {0, 1, 2} with zero point 1 ("Extreme Quantization" names the levels; the scale is our reading)."""
     w = np.asarray(w).astype(decision_dtype)
@@ -112,7 +113,7 @@ def ternary_grid(w, decision_dtype=np.float32):
     return s.astype(decision_dtype), np.ones(w.shape[0], dtype=np.int64)
 
 
-def grid_params(w, bits: int, grid: str, decision_dtype=np.float32):
+def grid_params(w, bits: int, grid: str, decision_dtype=np.float64):
     if grid == "minmax":
         return minmax_grid(w, bits, decision_dtype)
     if grid == "ternary":
@@ -124,7 +125,7 @@ def grid_maxq(bits: int, grid: str) -> int:
     return 2 if grid == "ternary" else 2 ** bits - 1
 
 
-def quant_codes(w, scale, zero, maxq: int, decision_dtype=np.float32) -> np.ndarray:
+def quant_codes(w, scale, zero, maxq: int, decision_dtype=np.float64) -> np.ndarray:
     """quant(w): index of the nearest grid value, code = clamp(rint(w/scale) + zero, 0, maxq),
     ties to even (Section 2: quant rounds to the nearest value on the grid)."""
     x = np.asarray(w).astype(decision_dtype) / np.asarray(scale, dtype=decision_dtype)
@@ -141,7 +142,7 @@ def dequant(codes, scale, zero) -> np.ndarray:
 # --------------------------------------------------------------------------------------------
 
 def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group: int = 0,
-                  decision_dtype=np.float32, teacher_codes=None):
+                  decision_dtype=np.float64, teacher_codes=None, teacher_levels=None):
     """Algorithm 1: quantize W (d_row x d_col) given U = Cholesky(H^-1)^T and block size B.
 
     group == 0: one grid per row, fixed from the original weights before the process starts
@@ -156,6 +157,9 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
     for each column is still computed from the current weights and returned as `codes`, but the
     algorithm then continues with the teacher's code (Q, E and all updates use it), so every decision
     is taken on the teacher's history.  In grouped mode the grids are still computed here.
+    teacher_levels gives the teacher's decisions as grid levels (code - zero point) instead: the forced
+    code is level + this function's own zero point, so the forced grid VALUE is the teacher's even where
+    the two zero points differ by a tie of rint(-lo/scale).
 
     Returns a dict with codes (int64), scale (rows x groups, decision_dtype), zero (int64),
     Q (float64 dequantised weights), E (d_row x d_col, every column's scaled error),
@@ -192,7 +196,12 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
                 scales[:, j // group], zeros[:, j // group] = scale, zero
             codes[:, j] = quant_codes(Wk[:, j], scale, zero, maxq, decision_dtype)
             frac[:, j] = Wk[:, j].astype(decision_dtype) / scale
-            used = codes[:, j] if teacher_codes is None else np.asarray(teacher_codes)[:, j].astype(np.int64)
+            if teacher_levels is not None:
+                used = np.asarray(teacher_levels)[:, j].astype(np.int64) + zero
+            elif teacher_codes is not None:
+                used = np.asarray(teacher_codes)[:, j].astype(np.int64)
+            else:
+                used = codes[:, j]
             Q[:, j] = dequant(used, scale, zero)
             E[:, j - i] = (Wk[:, j] - Q[:, j]) / Ub[j - i, j]
             Wk[:, j:iend] -= np.outer(E[:, j - i], Ub[j - i, j:iend])
@@ -201,7 +210,7 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
     return dict(codes=codes, scale=scales, zero=zeros, Q=Q, E=E_all, W_final=Wk, frac=frac)
 
 
-def naive_obs_quantize(W, Hd, bits: int, grid: str = "minmax", group: int = 0, decision_dtype=np.float32):
+def naive_obs_quantize(W, Hd, bits: int, grid: str = "minmax", group: int = 0, decision_dtype=np.float64):
     """Fixed-order OBQ without Cholesky and without blocks (Section 3, Step 1): for each column q in
     natural order, quantize it, apply Eq. 2's update with column q of the explicit inverse Hessian of
     the remaining set F, then remove q from the inverse by the Gaussian-elimination step of Eq. 3."""
@@ -231,7 +240,7 @@ def naive_obs_quantize(W, Hd, bits: int, grid: str = "minmax", group: int = 0, d
     return dict(codes=codes, scale=scales, zero=zeros, Q=Q)
 
 
-def rtn_quantize(W, bits: int, grid: str = "minmax", group: int = 0, decision_dtype=np.float32):
+def rtn_quantize(W, bits: int, grid: str = "minmax", group: int = 0, decision_dtype=np.float64):
     """Round every weight to the nearest value of the same grid (Section 4, Baselines)."""
     W = np.asarray(W, dtype=np.float64)
     r, n = W.shape

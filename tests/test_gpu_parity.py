@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from oracle import gptq_oracle as O
+from parity_util import audit_alg1, levels
 from workloads import configs
 
 pytestmark = pytest.mark.gpu
@@ -170,29 +171,32 @@ def test_cholesky_reports_a_non_positive_pivot():
 
 # ------------------------------------------------------------------ step 3: Algorithm 1
 
-def _compare_quant(res, ora, W64, Hd, group, n, tag):
+def _compare_quant(res, W64, U64, Hd, bits, grid, group, n, tag, tie_tol=1e-3):
+    """The GPU result against the oracle's Alg. 1 on (W64, U64), with the decision w -> code taken in float64
+    (the oracle proper) and in float32 (the precision of the kernel): at least 99.9 % of the levels equal and every
+    difference a one-step rounding tie, audited on the GPU's own history (tests/parity_util.py); layer error within
+    1 %; the kernel's closed-form (1/2) sum e^2 within 1 % of the real error."""
     codes = res.codes.cpu().numpy().astype(np.int64)
     zero = res.zeros.cpu().numpy().astype(np.int64)
     scale = res.scales.cpu().numpy()
     gsz = group if group else n
-    lev_g = codes - np.repeat(zero, gsz, axis=1)
-    lev_o = ora["codes"] - np.repeat(ora["zero"], gsz, axis=1)
-    diff = np.abs(lev_g - lev_o)
-    agree = float((diff == 0).mean())
+    lev_g = levels(codes, zero, gsz)
     Qg = np.repeat(scale.astype(np.float64), gsz, axis=1) * lev_g
     eg = O.layer_error_H(W64, Qg, Hd)
-    eo = O.layer_error_H(W64, ora["Q"], Hd)
     half = float(res.half_E2_rows.sum().item())
-    _say(f"  {tag}: agree={agree:.5f} maxdiff={diff.max()} err_gpu={eg:.6e} err_oracle={eo:.6e} halfE2={half:.6e}")
-    assert agree >= 0.999
-    assert diff.max() <= 1
-    assert abs(eg - eo) <= 0.01 * eo
-    assert abs(half - 0.5 * np.sum(ora["E"] ** 2)) <= 0.01 * 0.5 * np.sum(ora["E"] ** 2)
+    raws = []
+    for dd in (np.float64, np.float32):
+        a = audit_alg1(W64, U64, bits, grid, 128, group, codes, zero, scale, dd, tie_tol=tie_tol, say=_say, tag=tag)
+        ora = a["free"]
+        eo = O.layer_error_H(W64, ora["Q"], Hd)
+        _say(f"  {tag}: err_gpu={eg:.6e} err_oracle={eo:.6e} halfE2={half:.6e}")
+        assert abs(eg - eo) <= 0.01 * eo
+        assert abs(half - 0.5 * np.sum(ora["E"] ** 2)) <= 0.01 * 0.5 * np.sum(ora["E"] ** 2)
+        raws.append(a["raw"])
     assert abs(half - eg) <= 0.01 * eg                       # the kernel's closed-form error is the real one
-    assert np.allclose(scale, ora["scale"], rtol=1e-5)
     if res.Wq is not None:
         assert np.allclose(res.Wq.double().cpu().numpy(), Qg, rtol=1e-6, atol=1e-12)
-    return agree
+    return min(raws)
 
 
 QUANT_CASES = [
@@ -226,14 +230,13 @@ def test_quantize_layer_matches_oracle(bits, grid, group, dtype, r, n):
     X = lay.x.tile().double().numpy()
     Hd = O.damp(O.hessian(X))
     U32 = O.hinv_cholesky_upper(Hd).astype(np.float32)
-    ora = O.gptq_quantize(W.double().numpy(), U32.astype(np.float64), bits, grid, 128, group)
     Wd = _padded(r, n, dtype, 8)
     Wd.copy_(W)
     Ud = _padded(n, n, torch.float32, 4)
     Ud.copy_(torch.from_numpy(U32))
     res = S.quantize(Wd, Ud, bits, grid, 128, group, want_Wq=True)
     torch.cuda.synchronize()
-    _compare_quant(res, ora, W.double().numpy(), Hd, group, n, "quant")
+    _compare_quant(res, W.double().numpy(), U32.astype(np.float64), Hd, bits, grid, group, n, "quant")
     maxq = O.grid_maxq(bits, grid)
     assert int(res.codes.max()) <= maxq
     assert torch.equal(Wd.cpu(), W)             # the input weights are not modified
@@ -246,11 +249,14 @@ def test_quantize_all_zero_rows_and_diagonal_hessian():
     W[5] = 0
     Hd = np.diag(np.linspace(0.5, 3.0, 256))
     U32 = O.hinv_cholesky_upper(Hd).astype(np.float32)
-    rt = O.rtn_quantize(W.double().numpy(), 3)
+    rt = O.rtn_quantize(W.double().numpy(), 3, decision_dtype=np.float32)      # scale and zero point bit for bit
+    rt64 = O.rtn_quantize(W.double().numpy(), 3)
     res = S.quantize(W.cuda(), torch.from_numpy(U32).cuda(), 3)
     assert np.array_equal(res.codes.cpu().numpy(), rt["codes"])
     assert np.array_equal(res.zeros.cpu().numpy()[:, 0], rt["zero"][:, 0])
     assert np.array_equal(res.scales.cpu().numpy(), rt["scale"])
+    far = np.abs(np.abs((W.double().numpy() / rt64["scale"]) % 1.0) - 0.5) > 1e-6       # float64 RTN: equal away from exact ties
+    assert np.array_equal(res.codes.cpu().numpy()[far], rt64["codes"][far]) and far.mean() > 0.99
     assert res.scales[5, 0].item() == 1.0 and res.zeros[5, 0].item() == 0 and int(res.codes[5].max()) == 0
 
 
@@ -292,7 +298,6 @@ def test_whole_path_matches_oracle(which):
     Ho = O.hessian(X64)
     Hdo = O.damp(Ho, lay.percdamp)
     Uo = O.hinv_cholesky_upper(Hdo)
-    ora = O.gptq_quantize(W64, Uo, lay.bits, lay.grid, lay.block, lay.group)
     # GPU
     H = S.new_hessian(lay.n)
     S.accumulate(H, X.cuda(), chunk=4096)
@@ -304,7 +309,10 @@ def test_whole_path_matches_oracle(which):
     torch.cuda.synchronize()
     _say(f"  hessian rel_fro={herr:.3e}  U rel_fro={uerr:.3e}")
     assert herr <= 1e-5
-    _compare_quant(res, ora, W64, Hdo, lay.group, lay.n, which)
+    # here the oracle runs on its own float64 U while the kernel used the GPU's float32 factor of the GPU's H: the
+    # working weights differ by that much more, so decisions a little farther from a tie may flip
+    _compare_quant(res, W64, Uo, Hdo, lay.bits, lay.grid, lay.group, lay.n, which, tie_tol=2e-3)
+    ora = O.gptq_quantize(W64, Uo, lay.bits, lay.grid, lay.block, lay.group)
     pbits = 2 if lay.grid == "ternary" else lay.bits
     assert np.array_equal(res.packed.cpu().numpy().view(np.uint32), O.pack_codes(res.codes.cpu().numpy(), pbits))
     # error of Eq. 1 measured directly on the activations, GPU result vs oracle result
@@ -335,8 +343,7 @@ def test_block_driver_shares_hessians_and_matches_oracle():
         U = O.hinv_cholesky_upper(Hd)
         for l in ls:
             W64 = l.weights().double().numpy()
-            ora = O.gptq_quantize(W64, U, 4, l.grid, l.block, l.group)
-            _compare_quant(res[l.name], ora, W64, Hd, l.group, n, f"block:{l.name}")
+            _compare_quant(res[l.name], W64, U, Hd, 4, l.grid, l.group, n, f"block:{l.name}", tie_tol=2e-3)
             assert np.array_equal(res[l.name].packed.cpu().numpy().view(np.uint32), O.pack_codes(res[l.name].codes.cpu().numpy(), 4))
 
 
