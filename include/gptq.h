@@ -15,9 +15,13 @@
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
  *     enqueues work on that stream and returns; it never synchronises.
- *   - Return value: GPTQ_OK or an error code.  On error nothing has been enqueued and
- *     gptq_last_error() (thread-local) describes the problem.  Arguments are validated on the host
- *     before any launch; no C++ exception crosses this boundary.
+ *   - Return value: GPTQ_OK or an error code; gptq_last_error() (thread-local) describes the problem.
+ *     Arguments are validated on the host before any launch: GPTQ_ERR_INVALID_ARG, GPTQ_ERR_UNSUPPORTED and
+ *     GPTQ_ERR_WORKSPACE mean that nothing has been enqueued.  GPTQ_ERR_HIP (a launch or runtime call failed
+ *     part way through) may leave earlier kernels of the call enqueued: the outputs are then undefined, but
+ *     all of that work is ordered on `stream` (the library's helper stream is joined back on every return
+ *     path), so synchronising `stream` is enough before the buffers are reused or freed.  No C++ exception
+ *     crosses this boundary.
  *   - Not re-entrant on the same workspace: two calls sharing a workspace must be on the same stream.
  */
 #ifndef GPTQ_MI355_H
@@ -65,7 +69,8 @@ GPTQ_API const char* gptq_last_error(void);
  *       parts whose partial tiles (held in the workspace) are added in a fixed order, so that all CUs have
  *       work -- pass such layers long chunks, whole calibration sets if they fit.  Without the workspace
  *       the kernels read X in place: the same sums up to float32 summation order, at lower speed.
- *       Repeating a call gives the same bits either way.  The size is 0 where the workspace is not used.
+ *       Repeating a call gives the same bits either way.  The size is 0 where the workspace is not used (ws is
+ *       then ignored).  A non-NULL ws that is misaligned or smaller than that size is GPTQ_ERR_WORKSPACE.
  *   No normalisation by the token count is applied (the quantization result is invariant to the
  *   scale of H).  n == 0 or t == 0 is a valid no-op.
  */

@@ -64,7 +64,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_dequantize_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, i64, vp]
     L.gptq_matvec_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, vp, vp]
     for name in ("gptq_hessian_accumulate", "gptq_hessian_symmetrize", "gptq_damp_cholesky_inverse", "gptq_check_info",
-                 "gptq_quantize_layer", "gptq_pack", "gptq_unpack"):
+                 "gptq_quantize_layer", "gptq_pack", "gptq_unpack",
+                 "gptq_hessian_accumulate_token_major", "gptq_dequantize_packed", "gptq_matvec_packed"):
         getattr(L, name).restype = ci
     if path == LIB_PATH:
         _lib = L

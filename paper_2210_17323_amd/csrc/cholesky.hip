@@ -272,19 +272,24 @@ extern "C" size_t gptq_damp_cholesky_inverse_workspace_bytes(int64_t n) {
     return chol_ws_layout(nullptr, n < 0 ? 0 : n).total;
 }
 
-extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float percdamp,
-                                          void* ws, size_t ws_bytes, int* info_dev, void* stream) {
-    if (n < 0) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: negative size");
-    if (!info_dev) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: info_dev is null");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (n == 0) return GPTQ_OK;
-    if (!H) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: H is null");
-    if (ld < n || ld % 4 || !aligned(H, 16))
-        return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: need ld >= n, ld %% 4 == 0 and a 16-byte aligned H");
-    if (!(percdamp >= 0.f)) return fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: percdamp must be >= 0");
-    if (!ws || !aligned(ws, 256) || ws_bytes < gptq_damp_cholesky_inverse_workspace_bytes(n))
-        return fail(GPTQ_ERR_WORKSPACE, "damp_cholesky_inverse: workspace missing, misaligned or too small");
+// Host-side checks shared by the entry points; 1 = nothing to do (n == 0).
+static int chol_check_args(const float* H, int64_t ld, int64_t n, float percdamp, const int* info_dev, int* rc) {
+    *rc = GPTQ_OK;
+    if (n < 0) { *rc = fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: negative size"); return 1; }
+    if (!info_dev) { *rc = fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: info_dev is null"); return 1; }
+    if (n == 0) return 1;
+    if (!H) { *rc = fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: H is null"); return 1; }
+    if (ld < n || ld % 4 || !aligned(H, 16)) {
+        *rc = fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: need ld >= n, ld %% 4 == 0 and a 16-byte aligned H");
+        return 1;
+    }
+    if (!(percdamp >= 0.f)) { *rc = fail(GPTQ_ERR_INVALID_ARG, "damp_cholesky_inverse: percdamp must be >= 0"); return 1; }
+    return 0;
+}
 
+// The whole of step 2 on validated arguments.  `ws` holds chol_ws_layout(n).total bytes; nothing in it has to be
+// initialised (every region is written in this call before it is read).  lookahead = false keeps all work on `s`.
+static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, int* info_dev, hipStream_t s, bool lookahead) {
     const CholWs w = chol_ws_layout(ws, n);
     float* dinv = w.dinv;
     constexpr size_t diag_lds = (2 * NB * DP + 32 * 64) * sizeof(float);
@@ -305,9 +310,9 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
         return gemm_on(s, A, lda, B, ldb, C, ldc, M, N, K, alpha, nk, overwrite, upper, crow0, ccol0, atri);
     };
     const int64_t nouter = ceil_div(n, OB);
-    Lookahead* la = nullptr;
-    if (int rc = lookahead_get(&la)) return rc;
-    hipStream_t s2 = la->stream;
+    TwoStreams ts;
+    if (int rc = ts.open(s, lookahead)) return rc;
+    hipStream_t s2 = ts.side;
 
     // ---- H + lambda I = R R^T, from the last column backwards.  Two levels: inside an outer block of
     //      1024 columns the rank-128 updates touch only that block's columns; the rest of the matrix gets
@@ -340,17 +345,16 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
         // the next block's own column update waits for the helper's, which wrote the same region.
         if (o0 > 0) {
             const int64_t p0 = o0 - OB;                  // outer blocks start at multiples of OB
-            hipEvent_t factored = la->event();
-            GPTQ_HIP_CHECK(hipEventRecord(factored, s));
-            if (rest_done) GPTQ_HIP_CHECK(hipStreamWaitEvent(s, rest_done, 0));
+            hipEvent_t factored = nullptr;
+            if (int rc = ts.mark(s, &factored)) return rc;
+            if (int rc = ts.wait(s, rest_done)) return rc;
             int rc = gemm(H + o0, ld, H + p0 * ld + o0, ld, H + p0, ld, o0, o0 - p0, o1 - o0, -1.f, true, false, true, 0, p0, false);
             if (rc) return rc;
             if (p0 > 0) {
-                GPTQ_HIP_CHECK(hipStreamWaitEvent(s2, factored, 0));
+                if ((rc = ts.wait(s2, factored))) return rc;
                 rc = gemm_on(s2, H + o0, ld, H + o0, ld, H, ld, p0, p0, o1 - o0, -1.f, true, false, true, 0, 0, false);
                 if (rc) return rc;
-                rest_done = la->event();
-                GPTQ_HIP_CHECK(hipEventRecord(rest_done, s2));
+                if ((rc = ts.mark(s2, &rest_done))) return rc;
             } else {
                 rest_done = nullptr;
             }
@@ -363,9 +367,9 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
     GPTQ_LAUNCH_CHECK();
     {
-        hipEvent_t cleared = la->event();
-        GPTQ_HIP_CHECK(hipEventRecord(cleared, s));
-        GPTQ_HIP_CHECK(hipStreamWaitEvent(s2, cleared, 0));
+        hipEvent_t cleared = nullptr;
+        if (int rc = ts.mark(s, &cleared)) return rc;
+        if (int rc = ts.wait(s2, cleared)) return rc;
     }
 
     // ---- U = R^-1 in place, one outer block column at a time (left to right):
@@ -399,9 +403,9 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
             GPTQ_LAUNCH_CHECK();
         }
         {
-            hipEvent_t inverted = la->event();
-            GPTQ_HIP_CHECK(hipEventRecord(inverted, s2));
-            GPTQ_HIP_CHECK(hipStreamWaitEvent(s, inverted, 0));
+            hipEvent_t inverted = nullptr;
+            if (int rc = ts.mark(s2, &inverted)) return rc;
+            if (int rc = ts.wait(s, inverted)) return rc;
         }
         if (o0 > 0) {
             const int ow = (int)(o1 - o0);
@@ -420,6 +424,15 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
         }
     }
     return GPTQ_OK;
+}
+
+extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float percdamp,
+                                          void* ws, size_t ws_bytes, int* info_dev, void* stream) {
+    int rc;
+    if (chol_check_args(H, ld, n, percdamp, info_dev, &rc)) return rc;
+    if (!ws || !aligned(ws, 256) || ws_bytes < gptq_damp_cholesky_inverse_workspace_bytes(n))
+        return fail(GPTQ_ERR_WORKSPACE, "damp_cholesky_inverse: workspace missing, misaligned or too small");
+    return chol_run(H, ld, n, percdamp, ws, info_dev, static_cast<hipStream_t>(stream), true);
 }
 
 extern "C" int gptq_check_info(const int* info_dev, int* host_info, void* stream) {

@@ -48,6 +48,42 @@ struct Lookahead {
 };
 int lookahead_get(Lookahead** out);     // for the current device; GPTQ_OK or an error code
 
+// The two streams of one entry point.  open(s, true) forks onto the library's helper stream; open(s, false) keeps
+// everything on the caller's stream (side == main, no events: the same kernels in an order that respects every
+// dependence, without overlap) -- for callers that must not create streams or events.  The destructor joins the
+// helper stream back into the caller's on EVERY return path, so also after a launch failed half way through a call
+// nothing is left running unordered beside the caller's stream.
+struct TwoStreams {
+    hipStream_t main = nullptr, side = nullptr;
+    Lookahead* la = nullptr;
+    int open(hipStream_t s, bool lookahead) {
+        main = side = s;
+        if (!lookahead) return GPTQ_OK;
+        if (int rc = lookahead_get(&la)) return rc;
+        side = la->stream;
+        return GPTQ_OK;
+    }
+    // *ev = a point on `on` that wait() can order another stream behind; stays null in single-stream mode
+    int mark(hipStream_t on, hipEvent_t* ev) {
+        *ev = nullptr;
+        if (!la) return GPTQ_OK;
+        hipEvent_t e = la->event();
+        GPTQ_HIP_CHECK(hipEventRecord(e, on));
+        *ev = e;
+        return GPTQ_OK;
+    }
+    int wait(hipStream_t who, hipEvent_t ev) {
+        if (!la || !ev) return GPTQ_OK;
+        GPTQ_HIP_CHECK(hipStreamWaitEvent(who, ev, 0));
+        return GPTQ_OK;
+    }
+    ~TwoStreams() {
+        if (!la) return;
+        hipEvent_t e = la->event();
+        if (hipEventRecord(e, side) == hipSuccess) (void)hipStreamWaitEvent(main, e, 0);
+    }
+};
+
 // ---- float32 matrix-core GEMM used by several steps (gemm_f32.hip) --------------------------
 // C[M x N] += alpha * A[M x K] * op(B), A row-major (K contiguous).
 //   b_is_nk = true : B is [N x K] row-major (K contiguous)  -> C += alpha * A * B^T

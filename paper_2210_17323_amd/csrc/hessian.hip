@@ -656,7 +656,10 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
     // DRAM-page and cache-line locality for the copies) and the direct-to-LDS kernel takes all of it; matrices
     // with few tiles get their token range split (see syrk_plan).
     const size_t need = syrk_ws_bytes(n, t, xdtype);
-    if (need && ws && aligned(ws, 256) && ws_bytes >= need)
+    if (need && ws && (!aligned(ws, 256) || ws_bytes < need))
+        return fail(GPTQ_ERR_WORKSPACE, "hessian_accumulate: workspace misaligned or smaller than the %zu bytes this call needs "
+                                        "(pass NULL to read X in place)", need);
+    if (need && ws)
         return bf ? launch_syrk_dma<true>(g, ws, s) : launch_syrk_dma<false>(g, ws, s);
     if (n <= 6144)                  // 256-wide tiles only fill the chip when there are enough of them
         return bf ? launch_syrk<true, 128, 2, 2>(g, s) : launch_syrk<false, 128, 2, 2>(g, s);

@@ -425,9 +425,9 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     // beyond are updated on the helper stream meanwhile.  The two updates and the next block's kernels touch
     // disjoint columns of the weights; the error panel E alternates between two buffers because the helper's
     // GEMM still reads one while the next block fills the other.
-    Lookahead* la = nullptr;
-    if (int rc = lookahead_get(&la)) return rc;
-    hipStream_t s2 = la->stream;
+    TwoStreams ts;
+    if (int rc = ts.open(s, true)) return rc;
+    hipStream_t s2 = ts.side;
     hipEvent_t rest_done = nullptr;         // the helper stream's last trailing update, if one is pending
     int eb = 0;
     for (int64_t o0 = 0; o0 < n; o0 += ob, eb ^= 1) {
@@ -439,7 +439,7 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
             if (group >= QB && j0 % group == 0) {
                 // The grid is taken from all columns of the group as they stand now.  Those beyond this outer
                 // block are kept current by the helper stream: its last update has to be in.
-                if (rest_done && j0 + group > o1) GPTQ_HIP_CHECK(hipStreamWaitEvent(s, rest_done, 0));
+                if (j0 + group > o1) { if (int rc = ts.wait(s, rest_done)) return rc; }
                 hipLaunchKernelGGL(group_grid_kernel, dim3((unsigned)r), dim3(64), 0, s, (const float*)Wk, lay.ldk, j0, group, grid, (float)maxq, scales, zeros, ngroups, j0 / group);
                 GPTQ_LAUNCH_CHECK();
             }
@@ -466,9 +466,9 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
         }
         if (o1 < n) {
             const int64_t o2 = std::min<int64_t>(o1 + ob, n);
-            hipEvent_t quantized = la->event();
-            GPTQ_HIP_CHECK(hipEventRecord(quantized, s));
-            if (rest_done) GPTQ_HIP_CHECK(hipStreamWaitEvent(s, rest_done, 0));    // it wrote the columns from o1 on
+            hipEvent_t quantized = nullptr;
+            if (int rc = ts.mark(s, &quantized)) return rc;
+            if (int rc = ts.wait(s, rest_done)) return rc;      // it wrote the columns from o1 on
             GemmF32 g{};
             g.A = E; g.lda = QOB; g.B = U + o0 * ldu + o1; g.ldb = ldu; g.C = Wk + o1; g.ldc = lay.ldk;
             g.M = r; g.N = o2 - o1; g.K = o1 - o0; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
@@ -476,12 +476,11 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
             if (rc) return rc;
             rest_done = nullptr;
             if (o2 < n) {
-                GPTQ_HIP_CHECK(hipStreamWaitEvent(s2, quantized, 0));
+                if ((rc = ts.wait(s2, quantized))) return rc;
                 g.B = U + o0 * ldu + o2; g.C = Wk + o2; g.N = n - o2;
                 rc = launch_gemm_f32(g, s2);
                 if (rc) return rc;
-                rest_done = la->event();
-                GPTQ_HIP_CHECK(hipEventRecord(rest_done, s2));
+                if ((rc = ts.mark(s2, &rest_done))) return rc;
             }
         }
     }

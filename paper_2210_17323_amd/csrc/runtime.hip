@@ -29,7 +29,14 @@ int lookahead_get(Lookahead** out) {
     if (!l.stream) {
         hipStream_t st = nullptr;
         GPTQ_HIP_CHECK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
-        for (hipEvent_t& e : l.ev) GPTQ_HIP_CHECK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        for (hipEvent_t& e : l.ev) {
+            const hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+            if (err != hipSuccess) {            // give back what was created: the next call starts from nothing
+                for (hipEvent_t& d : l.ev) { if (d) (void)hipEventDestroy(d); d = nullptr; }
+                (void)hipStreamDestroy(st);
+                return fail(GPTQ_ERR_HIP, "hipEventCreateWithFlags failed: %s", hipGetErrorString(err));
+            }
+        }
         l.stream = st;
     }
     *out = &l;

@@ -28,7 +28,7 @@ def accumulate(H: torch.Tensor, X: torch.Tensor, chunk: int | None = None) -> No
     """H += 2 X X^T, optionally walking the token axis in chunks (multiples of 8 tokens)."""
     n, t = X.shape
     step = t if chunk is None or chunk >= t else chunk
-    nbytes = B.gptq_hessian_accumulate_workspace_bytes(n, step, X.dtype)
+    nbytes = max(B.gptq_hessian_accumulate_workspace_bytes(n, c, X.dtype) for c in {step, t % step or step})
     ws = torch.empty(nbytes, dtype=torch.uint8, device=X.device) if nbytes else None
     for c0 in range(0, t, step):
         B.gptq_hessian_accumulate(H, X[:, c0:min(c0 + step, t)], ws)

@@ -44,6 +44,10 @@ def test_argument_validation_happens_on_the_host():
     assert L.gptq_hessian_accumulate(one, 8, one, 0, 8, 12, 12, None, 0, None) == INVALID        # ldx % 8
     assert "ldx" in _err()
     assert L.gptq_hessian_accumulate(one, 8, one, 0, 0, 8, 8, None, 0, None) == OK               # empty is a no-op
+    # a workspace that is given must be usable: too small or misaligned is an error, not a silent slow path
+    assert L.gptq_hessian_accumulate(one, 49152, one, 0, 49152, 32768, 32768, one, 1024, None) == WORKSPACE
+    assert L.gptq_hessian_accumulate(one, 49152, one, 0, 49152, 32768, 32768, ctypes.c_void_p(264), 1 << 40, None) == WORKSPACE
+    assert "workspace" in _err()
     tm = L.gptq_hessian_accumulate_token_major
     assert tm(one, 8, one, 0, 8, 16, 4, one, 1 << 30, None) == INVALID                           # ldx < n
     assert tm(one, 8, one, 2, 8, 16, 8, one, 1 << 30, None) == UNSUPPORTED                       # float32
