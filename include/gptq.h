@@ -11,7 +11,8 @@
  * Conventions
  *   - Every data pointer is a DEVICE pointer to memory owned by the caller, valid on the current
  *     HIP device; the library never allocates or frees device memory.  Scratch space comes from a
- *     caller-provided workspace whose size the matching *_workspace_bytes call returns.
+ *     caller-provided workspace whose size the matching *_workspace_bytes call returns (one variant,
+ *     gptq_damp_cholesky_inverse_noalloc, uses a fixed array that is part of the library instead).
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
  *     enqueues work on that stream and returns; it never synchronises.
@@ -115,6 +116,26 @@ GPTQ_API int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* str
 GPTQ_API size_t gptq_damp_cholesky_inverse_workspace_bytes(int64_t n);
 GPTQ_API int gptq_damp_cholesky_inverse(float* H_U, int64_t ld, int64_t n, float percdamp,
                                void* ws, size_t ws_bytes, int* info_dev, void* stream);
+
+/*
+ * Step 2 for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc) and therefore cannot bring a workspace: the same kernels and the same
+ * result as gptq_damp_cholesky_inverse, with the scratch space in a fixed device array that is part of the
+ * library image (about 22 MiB, resident on every GPU the library runs on until the process ends).
+ *
+ *   n <= GPTQ_NOALLOC_MAX_N (gptq_noalloc_max_n() returns it); a larger n is GPTQ_ERR_UNSUPPORTED and nothing is
+ *   enqueued.  H_U, ld, percdamp, info_dev and the result are as for gptq_damp_cholesky_inverse.
+ *   The call allocates nothing and creates no stream or event: all kernels are enqueued on `stream` alone (no
+ *   helper stream).  The first call on a device looks the array's address up once (hipGetSymbolAddress); make
+ *   that call outside a graph capture.
+ *   All calls on one GPU share that GPU's array: two such calls that overlap in time on one GPU (different
+ *   streams, different threads) race and give undefined results -- order them.  Nothing in the array has to
+ *   survive between calls and nothing has to be cleared: every region is written before it is read.
+ */
+#define GPTQ_NOALLOC_MAX_N 4096
+GPTQ_API int64_t gptq_noalloc_max_n(void);
+GPTQ_API int gptq_damp_cholesky_inverse_noalloc(float* H_U, int64_t ld, int64_t n, float percdamp,
+                                       int* info_dev, void* stream);
 
 /* Synchronises `stream`, reads *info_dev and returns GPTQ_OK or GPTQ_ERR_NOT_POSDEF
  * (the failing 1-based column index is stored in *host_info if host_info is not NULL). */

@@ -55,6 +55,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_damp_cholesky_inverse_workspace_bytes.argtypes = [i64]
     L.gptq_damp_cholesky_inverse_workspace_bytes.restype = sz
     L.gptq_damp_cholesky_inverse.argtypes = [vp, i64, i64, f32, vp, sz, vp, vp]
+    L.gptq_damp_cholesky_inverse_noalloc.argtypes = [vp, i64, i64, f32, vp, vp]
+    L.gptq_noalloc_max_n.restype = i64
     L.gptq_check_info.argtypes = [vp, ctypes.POINTER(ci), vp]
     L.gptq_quantize_layer_workspace_bytes.argtypes = [i64, i64, ci, i64]
     L.gptq_quantize_layer_workspace_bytes.restype = sz
@@ -64,7 +66,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_dequantize_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, i64, vp]
     L.gptq_matvec_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, vp, vp]
     for name in ("gptq_hessian_accumulate", "gptq_hessian_symmetrize", "gptq_damp_cholesky_inverse", "gptq_check_info",
-                 "gptq_quantize_layer", "gptq_pack", "gptq_unpack",
+                 "gptq_quantize_layer", "gptq_pack", "gptq_unpack", "gptq_damp_cholesky_inverse_noalloc",
                  "gptq_hessian_accumulate_token_major", "gptq_dequantize_packed", "gptq_matvec_packed"):
         getattr(L, name).restype = ci
     if path == LIB_PATH:
@@ -160,6 +162,19 @@ def gptq_damp_cholesky_inverse(H_U: torch.Tensor, percdamp: float, ws: torch.Ten
         raise ValueError("info must be a GPU int32 tensor and ws a GPU uint8 tensor")
     n = H_U.shape[0]
     _check(lib().gptq_damp_cholesky_inverse(_ptr(H_U), _ld(H_U), n, percdamp, _ptr(ws), ws.numel(), _ptr(info), _stream()))
+
+
+def gptq_noalloc_max_n() -> int:
+    return lib().gptq_noalloc_max_n()
+
+
+def gptq_damp_cholesky_inverse_noalloc(H_U: torch.Tensor, percdamp: float, info: torch.Tensor) -> None:
+    """gptq_damp_cholesky_inverse without a workspace argument: scratch lives in the library's own fixed device
+    array (n <= gptq_noalloc_max_n()); allocates nothing."""
+    _dev2d(H_U, "H_U", (torch.float32,))
+    if info.dtype != torch.int32 or not info.is_cuda:
+        raise ValueError("info must be a GPU int32 tensor")
+    _check(lib().gptq_damp_cholesky_inverse_noalloc(_ptr(H_U), _ld(H_U), H_U.shape[0], percdamp, _ptr(info), _stream()))
 
 
 def gptq_check_info(info: torch.Tensor) -> int:

@@ -19,6 +19,8 @@
 //     U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1)           (K = o0, carries the flops)
 #include "common.h"
 
+#include <mutex>
+
 namespace gptq {
 
 constexpr int NB = 128;
@@ -433,6 +435,53 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     if (!ws || !aligned(ws, 256) || ws_bytes < gptq_damp_cholesky_inverse_workspace_bytes(n))
         return fail(GPTQ_ERR_WORKSPACE, "damp_cholesky_inverse: workspace missing, misaligned or too small");
     return chol_run(H, ld, n, percdamp, ws, info_dev, static_cast<hipStream_t>(stream), true);
+}
+
+// ---- the variant that allocates nothing -------------------------------------------------------------------
+// Same kernels, their workspace in a library-owned device array of fixed size.  Each GPU holds its own copy of the
+// array at its own address: the address is looked up once per device, with that device current, and only that
+// pointer -- never the array's name, which in host code is a stand-in and no device address -- is handed to kernels.
+namespace {
+constexpr int64_t NOALLOC_MAX_N = GPTQ_NOALLOC_MAX_N;
+constexpr size_t NOALLOC_BYTES = (size_t)(NOALLOC_MAX_N / NB) * NB * NB * sizeof(float)      // inverses of the diagonal blocks
+                                 + (size_t)NOALLOC_MAX_N * OB * sizeof(float)                // one n x 1024 product
+                                 + (size_t)OB * OB * sizeof(float) + 512;                    // one dense 1024 x 1024 block
+static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
+
+constexpr int MAXDEV = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAXDEV] = {};
+
+int scratch_for_current_device(void** out) {
+    int dev = 0;
+    GPTQ_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAXDEV) return fail(GPTQ_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        GPTQ_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned(p, 256)) return fail(GPTQ_ERR_HIP, "hipGetSymbolAddress gave an unusable address for the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return GPTQ_OK;
+}
+}  // namespace
+
+extern "C" int64_t gptq_noalloc_max_n(void) { return NOALLOC_MAX_N; }
+
+extern "C" int gptq_damp_cholesky_inverse_noalloc(float* H, int64_t ld, int64_t n, float percdamp, int* info_dev, void* stream) {
+    int rc;
+    if (chol_check_args(H, ld, n, percdamp, info_dev, &rc)) return rc;
+    if (n > NOALLOC_MAX_N)
+        return fail(GPTQ_ERR_UNSUPPORTED, "damp_cholesky_inverse_noalloc: n = %lld exceeds the %lld channels the library's static scratch "
+                                          "array holds; use gptq_damp_cholesky_inverse with a caller workspace",
+                    (long long)n, (long long)NOALLOC_MAX_N);
+    static_assert(NOALLOC_MAX_N % OB == 0, "layout below assumes whole outer blocks");
+    if (chol_ws_layout(nullptr, n).total > NOALLOC_BYTES) return fail(GPTQ_ERR_UNSUPPORTED, "damp_cholesky_inverse_noalloc: scratch layout exceeds the static array");
+    void* ws = nullptr;
+    if ((rc = scratch_for_current_device(&ws))) return rc;
+    return chol_run(H, ld, n, percdamp, ws, info_dev, static_cast<hipStream_t>(stream), false);
 }
 
 extern "C" int gptq_check_info(const int* info_dev, int* host_info, void* stream) {

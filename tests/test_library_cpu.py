@@ -59,6 +59,11 @@ def test_argument_validation_happens_on_the_host():
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, one, 16, one, None) == WORKSPACE
     assert L.gptq_damp_cholesky_inverse(one, 8, 8, 0.01, None, 0, one, None) == WORKSPACE
     assert L.gptq_damp_cholesky_inverse(one, 6, 6, 0.01, one, 1 << 30, one, None) == INVALID   # ld % 4
+    na = L.gptq_damp_cholesky_inverse_noalloc
+    assert L.gptq_noalloc_max_n() == 4096
+    assert na(one, 4100, 4100, 0.01, one, None) == UNSUPPORTED and "4096" in _err()       # beyond the library's fixed scratch array
+    assert na(one, 8, 8, -1.0, one, None) == INVALID and na(one, 8, 8, 0.01, None, None) == INVALID
+    assert na(one, 6, 6, 0.01, one, None) == INVALID and na(one, 8, 0, 0.01, one, None) == OK
     q = lambda **kw: L.gptq_quantize_layer(one, kw.get("wd", 0), 256, kw.get("r", 4), 256, one, 256, kw.get("bits", 4),
                                            kw.get("grid", 0), kw.get("block", 128), kw.get("group", 0), one, 256, one, one,
                                            None, 0, None, kw.get("ws", one), kw.get("wsb", 1 << 30), None)

@@ -1,0 +1,61 @@
+"""The entry point that allocates nothing (gptq_damp_cholesky_inverse_noalloc: scratch in a fixed device array of the
+library) against gptq_damp_cholesky_inverse with a caller workspace: same kernels, so the same bits, on two calls in
+a row, the second with a smaller input (the shared array then still holds the first call's contents).  Also against
+the float64 oracle at the bar of the workspace variant (relative Frobenius error <= 2e-5)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gptq_oracle as O
+from workloads import configs
+
+pytestmark = pytest.mark.gpu
+
+
+def _hessian(n, shift):
+    lay = configs.scaled_twin(configs.config2()[0], n, r=8, m=4 * n)
+    x = type(lay.x)(**{**lay.x.__dict__, "tensor_id": lay.x.tensor_id + shift})
+    X = x.tile().double().numpy()
+    return O.hessian(X).astype(np.float32)
+
+
+def test_noalloc_matches_workspace_variant_twice():
+    import paper_2210_17323_amd as g
+    g.lib()
+    assert g.gptq_noalloc_max_n() == 4096
+    for n, shift in ((2304, 0), (1153, 1), (300, 2)):          # three calls in a row, each smaller than the one before
+        print(f"noalloc n={n}", flush=True)
+        H32 = _hessian(n, shift)
+        ld = (n + 3) // 4 * 4
+        A = torch.zeros((n, ld), dtype=torch.float32, device="cuda")[:, :n]
+        B = torch.zeros((n, ld), dtype=torch.float32, device="cuda")[:, :n]
+        A.copy_(torch.from_numpy(H32)); B.copy_(torch.from_numpy(H32))
+        ws = torch.empty(g.gptq_damp_cholesky_inverse_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        ia = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        ib = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        g.gptq_damp_cholesky_inverse(A, 0.01, ws, ia)
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_allocated()
+        g.gptq_damp_cholesky_inverse_noalloc(B, 0.01, ib)
+        torch.cuda.synchronize()
+        assert torch.cuda.memory_allocated() == before
+        assert g.gptq_check_info(ia) == 0 and g.gptq_check_info(ib) == 0
+        assert torch.equal(A, B)
+        want = O.hinv_cholesky_upper(O.damp(H32.astype(np.float64), 0.01))
+        got = B.double().cpu().numpy()
+        err = np.linalg.norm(got - want) / np.linalg.norm(want)
+        print(f"  equal to the workspace variant; rel_fro vs oracle {err:.3e}", flush=True)
+        assert err <= 2e-5
+        assert np.array_equal(np.tril(got, -1), np.zeros_like(got))
+    # a non-positive pivot is reported the same way
+    H = torch.eye(300, device="cuda")
+    H[170, 170] = -2.0
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    g.gptq_damp_cholesky_inverse_noalloc(H, 0.0, info)
+    with pytest.raises(g.GptqError) as ei:
+        g.gptq_check_info(info)
+    assert ei.value.code == 2 and "171" in str(ei.value)
+    # sizes beyond the fixed array are refused before anything is enqueued
+    big = torch.zeros((8, 8), dtype=torch.float32, device="cuda")
+    rc = g.lib().gptq_damp_cholesky_inverse_noalloc(big.data_ptr(), 4100, 4100, 0.01, info.data_ptr(), None)
+    assert rc == 4 and "4096" in g.lib().gptq_last_error().decode()
