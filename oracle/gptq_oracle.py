@@ -85,12 +85,13 @@ def hinv_cholesky_upper_reverse(Hd) -> np.ndarray:
 # Grids
 # --------------------------------------------------------------------------------------------
 
-def minmax_grid(w, bits: int, decision_dtype=np.float64):
+def minmax_grid(w, bits: int, decision_dtype=np.float64, with_real_zero: bool = False):
     """Uniform asymmetric min-max grid for each row of w (Section 4, Setup).
 
     The range is widened to contain 0 so that an integer zero point in [0, maxq] exists:
       lo = min(min w, 0), hi = max(max w, 0), scale = (hi - lo)/maxq, zero = rint(-lo/scale),
-    and an all-zero row gets scale 1, zero 0.  Returns (scale[rows] decision_dtype, zero[rows] int64).
+    and an all-zero row gets scale 1, zero 0.  Returns (scale[rows] decision_dtype, zero[rows] int64), and with
+    with_real_zero also the value -lo/scale before it is rounded (for reporting how close to a tie it was).
     """
     w = np.asarray(w).astype(decision_dtype)
     maxq = decision_dtype(2 ** bits - 1)
@@ -99,8 +100,11 @@ def minmax_grid(w, bits: int, decision_dtype=np.float64):
     dead = hi == lo
     scale = (hi - lo) / maxq
     scale[dead] = decision_dtype(1)
-    zero = np.rint(-lo / scale)
+    real_zero = -lo / scale
+    zero = np.rint(real_zero)
     zero[dead] = 0
+    if with_real_zero:
+        return scale.astype(decision_dtype), zero.astype(np.int64), np.asarray(real_zero, dtype=np.float64)
     return scale.astype(decision_dtype), zero.astype(np.int64)
 
 
@@ -163,7 +167,8 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
 
     Returns a dict with codes (int64), scale (rows x groups, decision_dtype), zero (int64),
     Q (float64 dequantised weights), E (d_row x d_col, every column's scaled error),
-    W_final (the working copy after all updates), and frac (the pre-rounding values w/scale).
+    W_final (the working copy after all updates), frac (the pre-rounding values w/scale) and zero_real
+    (rows x groups, the pre-rounding zero points -lo/scale of the min-max grid).
     U may be float32 (it is widened to float64 block row by block row).
     """
     Wk = np.array(W, dtype=np.float64, copy=True)
@@ -182,9 +187,12 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
     Q = np.zeros((r, n))
     codes = np.zeros((r, n), dtype=np.int64)
     E_all = np.zeros((r, n))
+    zero_real = np.full((r, ngroups), np.nan)        # -lo/scale before rounding (min-max grid; reporting only)
     if not group:
         scale, zero = grid_params(Wk, bits, grid, decision_dtype)
         scales[:, 0], zeros[:, 0] = scale, zero
+        if grid == "minmax":
+            zero_real[:, 0] = minmax_grid(Wk, bits, decision_dtype, with_real_zero=True)[2]
     frac = np.zeros((r, n), dtype=decision_dtype)
     for i in range(0, n, block):
         iend = min(i + block, n)
@@ -194,6 +202,8 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
             if group and j % group == 0:
                 scale, zero = grid_params(Wk[:, j:j + group], bits, grid, decision_dtype)
                 scales[:, j // group], zeros[:, j // group] = scale, zero
+                if grid == "minmax":
+                    zero_real[:, j // group] = minmax_grid(Wk[:, j:j + group], bits, decision_dtype, with_real_zero=True)[2]
             codes[:, j] = quant_codes(Wk[:, j], scale, zero, maxq, decision_dtype)
             frac[:, j] = Wk[:, j].astype(decision_dtype) / scale
             if teacher_levels is not None:
@@ -207,7 +217,7 @@ def gptq_quantize(W, U, bits: int, grid: str = "minmax", block: int = 128, group
             Wk[:, j:iend] -= np.outer(E[:, j - i], Ub[j - i, j:iend])
         Wk[:, iend:] -= E @ Ub[:, iend:]
         E_all[:, i:iend] = E
-    return dict(codes=codes, scale=scales, zero=zeros, Q=Q, E=E_all, W_final=Wk, frac=frac)
+    return dict(codes=codes, scale=scales, zero=zeros, Q=Q, E=E_all, W_final=Wk, frac=frac, zero_real=zero_real)
 
 
 def naive_obs_quantize(W, Hd, bits: int, grid: str = "minmax", group: int = 0, decision_dtype=np.float64):

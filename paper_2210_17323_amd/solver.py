@@ -67,14 +67,16 @@ def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", 
     return LayerResult(codes, scales, zeros, half, Wq, packed)
 
 
-def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bool = False, timings: dict | None = None):
+def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bool = False, timings: dict | None = None,
+                factors: dict | None = None):
     """The layers of one block, quantized in sequence (Section 4, Setup: a block's inputs are collected, its
     layers quantized, then the next block).  `groups` is a list of (X, layers): X [n x m] are the input
     activations shared by `layers`, a list of (name, W, settings) with settings an object carrying
     bits / grid / block / group / percdamp (e.g. workloads.configs.Layer).  Layers that share an input share
     one Hessian and one factor U.  Returns {name: LayerResult}; if `timings` is a dict it receives, per group,
     the milliseconds of the Hessian and of the factorisation, and per layer those of Alg. 1 plus packing
-    (CUDA events on the current stream)."""
+    (CUDA events on the current stream).  If `factors` is a dict it receives {group index: U}, the factor each
+    group's layers were quantized with (otherwise it is freed as soon as the group is done)."""
     out = {}
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
@@ -100,6 +102,8 @@ def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bo
             out[name] = quantize(W, U, b, lay.grid, lay.block, lay.group, want_Wq=want_Wq, pack=True, ws=ws)
             q1.record()
             marks.append((f"{name}:quantize_pack", q0, q1))
+        if factors is not None:
+            factors[gi] = U
         del H, U, ws
     if timings is not None:
         torch.cuda.synchronize()

@@ -22,7 +22,7 @@ import pytest
 import torch
 
 from oracle import gptq_oracle as O
-from parity_util import audit_alg1
+from parity_util import audit_alg1, compare_quant
 from workloads import configs
 
 pytestmark = pytest.mark.gpu
@@ -48,6 +48,8 @@ def _layers():
         "opt6.7b_attn_4bit": configs.config2()[0],
         "bloom176b_qkv_2bit_g128": c4[0],
         "bloom176b_out_ternary_g128": c4[3],
+        "bloom176b_qkv_ternary_g128": c4[2],
+        "bloom176b_out_2bit_g128": c4[1],
         "opt175b_q_4bit": c5[0],
     }
 
@@ -169,3 +171,101 @@ def test_full_size_sampled_parity(which):
     # packing of the sampled rows
     assert np.array_equal(res.packed[rows].cpu().numpy().view(np.uint32), O.pack_codes(codes_g, lay.bits))
     _say(f"full-size parity done in {time.time() - t0:.1f}s")
+
+
+def test_config2_whole_against_the_oracles_own_hessian_and_factor():
+    """The OPT-6.7B-shaped layer (W 4096 x 4096, X 4096 x 262144 fp16, 4-bit) end to end: the oracle computes its own
+    float64 H over all tokens, its own U and all codes; nothing of the GPU path is fed into it."""
+    import paper_2210_17323_amd as g
+    from paper_2210_17323_amd import solver as S
+    lay = configs.config2()[0]
+    r, n, m = lay.r, lay.n, lay.x.m
+    _say(f"config 2 whole: W {r} x {n}, X {n} x {m}")
+    t0 = time.time()
+    W, X = configs.materialize(lay, "cuda")
+    H = S.new_hessian(n)
+    S.accumulate(H, X)                       # the whole calibration set in one call, as bench.py does for this layer
+    g.gptq_hessian_symmetrize(H)
+    Hg = H.double().cpu().numpy()
+    U = S.cholesky_inverse(H, lay.percdamp)
+    res = S.quantize(W, U, lay.bits, lay.grid, lay.block, lay.group, want_Wq=True, pack=True)
+    torch.cuda.synchronize()
+    _say(f"  GPU path done at {time.time() - t0:.1f}s")
+    Ho = np.zeros((n, n))
+    for c0 in range(0, m, 32768):            # float64 sum of the chunks' 2 X X^T
+        Ho += O.hessian(X[:, c0:c0 + 32768].cpu().double().numpy())
+        _say(f"  oracle Hessian: {c0 + 32768} tokens at {time.time() - t0:.1f}s")
+    herr = np.linalg.norm(Hg - Ho) / np.linalg.norm(Ho)
+    Hdo = O.damp(Ho, lay.percdamp)
+    Uo = O.hinv_cholesky_upper(Hdo)
+    uerr = np.linalg.norm(U.double().cpu().numpy() - Uo) / np.linalg.norm(Uo)
+    _say(f"  hessian rel_fro={herr:.3e}  U rel_fro={uerr:.3e} at {time.time() - t0:.1f}s")
+    assert herr <= 1e-5 and uerr <= 2e-5
+    W64 = W.double().cpu().numpy()
+    compare_quant(res, W64, Uo, Hdo, lay.bits, lay.grid, lay.group, "config2", tie_tol=2e-3, say=_say)
+    assert np.array_equal(res.packed.cpu().numpy().view(np.uint32), O.pack_codes(res.codes.cpu().numpy(), lay.bits))
+    _say(f"config 2 whole done in {time.time() - t0:.1f}s")
+
+
+def test_full_size_decoder_block_3_and_4_bits():
+    """The six linears of an OPT-175B-shaped decoder block through solver.solve_block (q, k, v share one Hessian and
+    one U) at 3 and at 4 bits, every layer checked on sampled rows: Alg. 1 against the oracle run with that group's
+    U (both decision precisions, near-tie audit), the kernel's (1/2) sum e^2 -- which equals the layer error
+    (1/2) tr(D (H + lambda I) D^T) for the U it was given -- within 1 % of the oracle's, packing bit-exact.  H and
+    U themselves are checked per layer shape in test_full_size_sampled_parity."""
+    from paper_2210_17323_amd import solver as S
+    t0 = time.time()
+    layers = configs.config5()
+    by_x = {}
+    for lay in layers:
+        by_x.setdefault(lay.x.tensor_id, []).append(lay)
+    groups, Ws = [], {}
+    for xid, lays in by_x.items():
+        X = None
+        members = []
+        for lay in lays:
+            Wl, Xl = configs.materialize(lay, "cuda") if X is None else (None, None)
+            if X is None:
+                X = Xl
+            else:
+                Wl = torch.empty((lay.r, lay.n), dtype=lay.dtype, device="cuda")
+                step = max(1, (1 << 27) // lay.n)
+                for r0 in range(0, lay.r, step):
+                    Wl[r0:r0 + step] = lay.weights(row0=r0, nrows=min(step, lay.r - r0), device="cuda")
+            Ws[lay.name] = Wl
+            members.append((lay.name, Wl, lay))
+        groups.append((X, members))
+    torch.cuda.synchronize()
+    _say(f"block inputs generated at {time.time() - t0:.1f}s")
+    U_host = {}
+    for bits in (3, 4):
+        factors, timings = {}, {}
+        res = S.solve_block(groups, bits=bits, chunk=32768, timings=timings, factors=factors)
+        torch.cuda.synchronize()
+        total = sum(timings.values())
+        _say(f"{bits}-bit block solved at {time.time() - t0:.1f}s: {total:.0f} ms on the GPU; " +
+             ", ".join(f"{k} {v:.1f}" for k, v in timings.items()))
+        assert set(res) == {"q", "k", "v", "out", "fc1", "fc2"}
+        for gi, (X, members) in enumerate(groups):
+            if gi not in U_host:
+                U_host[gi] = factors[gi].cpu().numpy()
+            else:       # the factor does not depend on the bit width: the same bits again
+                assert torch.equal(factors[gi].cpu(), torch.from_numpy(U_host[gi]))
+            for name, Wl, lay in members:
+                r, n = lay.r, lay.n
+                rows = np.unique(np.array([0, 65, r // 2 + 3, r - 1]))
+                rl = res[name]
+                codes_g = rl.codes[rows].cpu().numpy().astype(np.int64)
+                zero_g = rl.zeros[rows].cpu().numpy().astype(np.int64)
+                scale_g = rl.scales[rows].cpu().numpy()
+                Wr = Wl[rows].double().cpu().numpy()
+                half = rl.half_E2_rows[rows].cpu().numpy()
+                for dd in (np.float64, np.float32):
+                    a = audit_alg1(Wr, U_host[gi], bits, lay.grid, lay.block, lay.group, codes_g, zero_g, scale_g, dd,
+                                   tie_tol=2e-3, say=_say, tag=f"{bits}-bit {name}")
+                    eo = 0.5 * np.sum(a["free"]["E"] ** 2, axis=1)
+                    assert abs(half.sum() - eo.sum()) <= 0.01 * eo.sum()
+                assert np.array_equal(rl.packed[rows].cpu().numpy().view(np.uint32), O.pack_codes(codes_g, bits))
+                _say(f"  {bits}-bit {name}: rows {rows.tolist()} ok at {time.time() - t0:.1f}s")
+        del factors, res
+    _say(f"full-size block done in {time.time() - t0:.1f}s")

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from oracle import gptq_oracle as O
-from parity_util import audit_alg1, levels
+from parity_util import compare_quant
 from workloads import configs
 
 pytestmark = pytest.mark.gpu
@@ -172,31 +172,7 @@ def test_cholesky_reports_a_non_positive_pivot():
 # ------------------------------------------------------------------ step 3: Algorithm 1
 
 def _compare_quant(res, W64, U64, Hd, bits, grid, group, n, tag, tie_tol=1e-3):
-    """The GPU result against the oracle's Alg. 1 on (W64, U64), with the decision w -> code taken in float64
-    (the oracle proper) and in float32 (the precision of the kernel): at least 99.9 % of the levels equal and every
-    difference a one-step rounding tie, audited on the GPU's own history (tests/parity_util.py); layer error within
-    1 %; the kernel's closed-form (1/2) sum e^2 within 1 % of the real error."""
-    codes = res.codes.cpu().numpy().astype(np.int64)
-    zero = res.zeros.cpu().numpy().astype(np.int64)
-    scale = res.scales.cpu().numpy()
-    gsz = group if group else n
-    lev_g = levels(codes, zero, gsz)
-    Qg = np.repeat(scale.astype(np.float64), gsz, axis=1) * lev_g
-    eg = O.layer_error_H(W64, Qg, Hd)
-    half = float(res.half_E2_rows.sum().item())
-    raws = []
-    for dd in (np.float64, np.float32):
-        a = audit_alg1(W64, U64, bits, grid, 128, group, codes, zero, scale, dd, tie_tol=tie_tol, say=_say, tag=tag)
-        ora = a["free"]
-        eo = O.layer_error_H(W64, ora["Q"], Hd)
-        _say(f"  {tag}: err_gpu={eg:.6e} err_oracle={eo:.6e} halfE2={half:.6e}")
-        assert abs(eg - eo) <= 0.01 * eo
-        assert abs(half - 0.5 * np.sum(ora["E"] ** 2)) <= 0.01 * 0.5 * np.sum(ora["E"] ** 2)
-        raws.append(a["raw"])
-    assert abs(half - eg) <= 0.01 * eg                       # the kernel's closed-form error is the real one
-    if res.Wq is not None:
-        assert np.allclose(res.Wq.double().cpu().numpy(), Qg, rtol=1e-6, atol=1e-12)
-    return min(raws)
+    return compare_quant(res, W64, U64, Hd, bits, grid, group, tag, tie_tol=tie_tol, say=_say)
 
 
 QUANT_CASES = [

@@ -53,3 +53,26 @@ def test_audit_rejects_planted_mistakes():
     trunc = np.clip(np.floor(good["frac"]).astype(np.int64) + good["zero"], 0, 7)
     with pytest.raises(AssertionError):
         audit_alg1(W, U, 3, "minmax", 128, 0, trunc, good["zero"], good["scale"], np.float64, say=quiet)
+
+
+def test_audit_zero_point_ties():
+    W, U = _case(seed=5, r=16, n=128)
+    quiet = lambda *_: None
+    # row 3: lo = -1.5 s, hi = +1.5 s at 2 bits, so -lo/scale = 1.5 exactly: rint gives 2; an arithmetic that sees
+    # 1.4999999 gives 1 and clamps at the other end of the range
+    W[3] = np.clip(W[3], -0.03, 0.03)
+    W[3, 10], W[3, 20] = -0.046875, 0.046875
+    good = O.gptq_quantize(W, U, 2)
+    assert good["zero"][3, 0] == 2 and good["zero_real"][3, 0] == 1.5
+    Wn = W.copy()
+    Wn[3, 10] *= (1 - 1e-9)
+    other = O.gptq_quantize(Wn, U, 2)
+    assert other["zero"][3, 0] == 1
+    audit_alg1(W, U, 2, "minmax", 128, 0, other["codes"], other["zero"], other["scale"], np.float64, say=quiet)
+    # a zero point that is off by one where -lo/scale is nowhere near a half-integer is a mistake
+    far = int(np.argmax(np.abs(np.abs(good["zero_real"][:, 0] % 1.0 - 0.5) - 0.5) < 0.2))
+    zbad = good["zero"].copy()
+    zbad[far, 0] += 1
+    cbad = np.clip(good["codes"] + (np.arange(16) == far)[:, None], 0, 3)
+    with pytest.raises(AssertionError):
+        audit_alg1(W, U, 2, "minmax", 128, 0, cbad, zbad, good["scale"], np.float64, say=quiet)
