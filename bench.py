@@ -5,7 +5,8 @@ One step = one pass of the whole hot path over one synthetic layer: zero H, accu
 H += 2 X X^T over all calibration tokens (in chunks), damp + Cholesky of the inverse, Algorithm 1
 (block quantizer + trailing updates), bit packing.  Inputs are resident in HBM before timing starts.
 Prints ONE JSON line: metric, value (TFLOP/s over the algorithmic flops of the whole solve), ms_per_step, per-phase
-times and rates, the roofline of the dominant kernel and the CPU oracle baseline.
+times, rates and fractions of peak, the roofline of the dominant kernel (the fp16 SYRK) and of the float32 GEMM, the same
+figures for the other workload shapes from one short run each, and the CPU oracle baseline.
 """
 from __future__ import annotations
 
@@ -23,11 +24,14 @@ PEAK_F16_MFMA_TFLOPS = 2516.6      # MI355X dense fp16/bf16 matrix-core peak
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes of ONE syrk_f16_dma_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by
-# what the same counter reads for a plain 1 GiB copy kernel (factors 2.000 and 1.000): see
-# profiles/layer_solve_opt175b_fc2_pmc_counters.txt (the fetch reading varies between 7.7e7 and 1.35e8 KiB from one
-# collection to the next; this is the one tabulated there).  Keyed by (n, tokens per call); other shapes: not measured.
-MEASURED_SYRK_TRAFFIC_BYTES = {(49152, 32768): (6.8303e7 * 2.0 + 5.1301e6 * 1.0) * 1024}
+# HBM-side bytes of ONE syrk_f16_dma_kernel launch: a STORED reading, not measured in this run (hardware counters need
+# rocprofv3 around the process).  From rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same counter reads
+# for a plain 1 GiB copy kernel (factors 2.000 and 1.000): profiles/layer_solve_opt175b_fc2_pmc_counters.txt.  The fetch
+# reading varies from one collection to the next; the entry is the one tabulated there, the note gives the range seen.
+# Keyed by (n, tokens per call); other shapes: not collected.
+MEASURED_SYRK_TRAFFIC = {(49152, 32768): {"bytes": (6.8303e7 * 2.0 + 5.1301e6 * 1.0) * 1024,
+                                          "note": "stored rocprofv3 reading (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000), not collected in "
+                                                  "this run; six collections of this launch gave 145-276 GB against 12.9 GB algorithmic"}}
 
 
 def parse():
@@ -42,6 +46,8 @@ def parse():
                     help="tokens per gptq_hessian_accumulate call (default: 32768; all tokens at once for layers of up to "
                          "6144 input channels, whose few tiles make the library split the token range of a call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-layers", action="store_true",
+                    help="skip the short runs of the other workload shapes that the default (opt175b_fc2) line carries as extra keys")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the timed region, run one plain 1 GiB device-to-device copy kernel (dst = src * 1: known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
@@ -169,6 +175,93 @@ def replace_rows(lay, r):
     return replace(lay, r=r)
 
 
+class LayerBench:
+    """Device buffers of one layer solve and the step that walks them through the four C-ABI calls."""
+
+    def __init__(self, lay, chunk_arg: int, dev):
+        import torch
+        import paper_2210_17323_amd as g
+        from workloads import configs
+        self.g, self.torch, self.lay = g, torch, lay
+        r, n, m = lay.r, lay.n, lay.x.m
+        self.W, self.X = configs.materialize(lay, dev)
+        self.H = torch.empty((n, n), dtype=torch.float32, device=dev)
+        self.chol_ws = torch.empty(g.gptq_damp_cholesky_inverse_workspace_bytes(n), dtype=torch.uint8, device=dev)
+        self.info = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.q_ws = torch.empty(g.gptq_quantize_layer_workspace_bytes(r, n, lay.block, lay.group), dtype=torch.uint8, device=dev)
+        G = n // lay.group if lay.group else 1
+        self.codes = torch.empty((r, n), dtype=torch.uint8, device=dev)
+        self.scales = torch.empty((r, G), dtype=torch.float32, device=dev)
+        self.zeros = torch.empty((r, G), dtype=torch.int32, device=dev)
+        self.half = torch.empty(r, dtype=torch.float64, device=dev)
+        self.pbits = 2 if lay.grid == "ternary" else lay.bits
+        self.packed = torch.empty((r, g.packed_words_per_row(n, self.pbits)), dtype=torch.int32, device=dev)
+        self.grid = g.GPTQ_GRID_TERNARY if lay.grid == "ternary" else g.GPTQ_GRID_MINMAX
+        self.chunk = min(chunk_arg or (m if n <= 6144 else 32768), m)
+        self.chunks = [(c0, min(c0 + self.chunk, m)) for c0 in range(0, m, self.chunk)]
+        h_bytes = g.gptq_hessian_accumulate_workspace_bytes(n, self.chunk, lay.x.dtype)
+        self.h_ws = torch.empty(h_bytes, dtype=torch.uint8, device=dev) if h_bytes else None
+        self.syrk_events, self.phase_events = [], []
+
+    def step(self, record: bool):
+        g, lay, torch = self.g, self.lay, self.torch
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        marks = [ev() for _ in range(5)] if record else None
+        if record: marks[0].record()
+        self.H.zero_()
+        for (c0, c1) in self.chunks:
+            if record:
+                e0, e1 = ev(), ev(); e0.record()
+            g.gptq_hessian_accumulate(self.H, self.X[:, c0:c1], self.h_ws)
+            if record:
+                e1.record(); self.syrk_events.append((e0, e1, c1 - c0))
+        if record: marks[1].record()
+        g.gptq_damp_cholesky_inverse(self.H, lay.percdamp, self.chol_ws, self.info)
+        if record: marks[2].record()
+        g.gptq_quantize_layer(self.W, self.H, lay.bits, self.grid, lay.block, lay.group, self.codes, self.scales, self.zeros,
+                              self.q_ws, None, self.half)
+        if record: marks[3].record()
+        g.gptq_pack(self.codes, self.pbits, self.packed)
+        if record:
+            marks[4].record(); self.phase_events.append(marks)
+
+    def run(self, steps: int, warmup: int):
+        """`warmup` untimed steps, then exactly `steps` timed ones between two device synchronisations."""
+        torch, g = self.torch, self.g
+        for _ in range(warmup):
+            self.step(False)
+        torch.cuda.synchronize()
+        if g.gptq_check_info(self.info) != 0:
+            raise RuntimeError("Cholesky reported a non-positive pivot")
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(True)
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+        names = ["hessian", "damp_cholesky_inverse", "quantize_layer", "pack"]
+        phases = {nm: sum(mk[i].elapsed_time(mk[i + 1]) for mk in self.phase_events) / len(self.phase_events)
+                  for i, nm in enumerate(names)}
+        return ms_per_step, phases
+
+
+def phase_rates(flops, phases, r, n, packed_numel):
+    tf = {
+        "hessian_syrk": flops["hessian"] / (phases["hessian"] * 1e-3) / 1e12,
+        "cholesky_plus_inverse_f32": (flops["cholesky"] + flops["tri_inverse"]) / (phases["damp_cholesky_inverse"] * 1e-3) / 1e12,
+        "quantize_f32": flops["quantize"] / (phases["quantize_layer"] * 1e-3) / 1e12,
+    }
+    frac = {
+        "hessian_of_fp16_mfma_peak": tf["hessian_syrk"] / PEAK_F16_MFMA_TFLOPS,
+        "cholesky_plus_inverse_of_fp32_peak": tf["cholesky_plus_inverse_f32"] / PEAK_F32_TFLOPS,
+        "quantize_of_fp32_peak": tf["quantize_f32"] / PEAK_F32_TFLOPS,
+        "pack_of_hbm_peak": (r * n + packed_numel * 4) / (phases["pack"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
+    return tf, frac
+
+
+OTHER_LAYERS = ["opt175b_fc1", "opt175b_q", "bloom176b_qkv_2bit_g128", "bloom176b_out_ternary_g128", "opt6.7b_attn"]
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -178,7 +271,6 @@ def main():
         return bench_block(a)
     import torch
     import paper_2210_17323_amd as g
-    from paper_2210_17323_amd import solver as S
     g.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
@@ -187,77 +279,24 @@ def main():
     lay = pick_layer(a.layer, a.tokens)
     r, n, m = lay.r, lay.n, lay.x.m
     flops = flop_model(r, n, m, lay.block)
-    from workloads import configs
-    W, X = configs.materialize(lay, dev)
-    H = torch.empty((n, n), dtype=torch.float32, device=dev)
-    chol_ws = torch.empty(g.gptq_damp_cholesky_inverse_workspace_bytes(n), dtype=torch.uint8, device=dev)
-    info = torch.zeros(1, dtype=torch.int32, device=dev)
-    q_ws = torch.empty(g.gptq_quantize_layer_workspace_bytes(r, n, lay.block, lay.group), dtype=torch.uint8, device=dev)
-    G = n // lay.group if lay.group else 1
-    codes = torch.empty((r, n), dtype=torch.uint8, device=dev)
-    scales = torch.empty((r, G), dtype=torch.float32, device=dev)
-    zeros = torch.empty((r, G), dtype=torch.int32, device=dev)
-    half = torch.empty(r, dtype=torch.float64, device=dev)
-    pbits = 2 if lay.grid == "ternary" else lay.bits
-    packed = torch.empty((r, g.packed_words_per_row(n, pbits)), dtype=torch.int32, device=dev)
-    grid = g.GPTQ_GRID_TERNARY if lay.grid == "ternary" else g.GPTQ_GRID_MINMAX
-    chunk = min(a.chunk or (m if n <= 6144 else 32768), m)
-    chunks = [(c0, min(c0 + chunk, m)) for c0 in range(0, m, chunk)]
-    h_bytes = g.gptq_hessian_accumulate_workspace_bytes(n, chunk, lay.x.dtype)
-    h_ws = torch.empty(h_bytes, dtype=torch.uint8, device=dev) if h_bytes else None
-
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    syrk_events, phase_events = [], []
-
-    def step(record: bool):
-        marks = [ev() for _ in range(5)] if record else None
-        if record: marks[0].record()
-        H.zero_()
-        for (c0, c1) in chunks:
-            if record:
-                e0, e1 = ev(), ev(); e0.record()
-            g.gptq_hessian_accumulate(H, X[:, c0:c1], h_ws)
-            if record:
-                e1.record(); syrk_events.append((e0, e1, c1 - c0))
-        if record: marks[1].record()
-        g.gptq_damp_cholesky_inverse(H, lay.percdamp, chol_ws, info)
-        if record: marks[2].record()
-        g.gptq_quantize_layer(W, H, lay.bits, grid, lay.block, lay.group, codes, scales, zeros, q_ws, None, half)
-        if record: marks[3].record()
-        g.gptq_pack(codes, pbits, packed)
-        if record:
-            marks[4].record(); phase_events.append(marks)
-
     if a.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)
         torch.mul(src, 1.0, out=dst)        # an elementwise kernel (a same-dtype copy_ would be a DMA transfer, not a kernel)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(a.warmup):
-        step(False)
-    torch.cuda.synchronize()
-    if g.gptq_check_info(info) != 0:
-        raise RuntimeError("Cholesky reported a non-positive pivot")
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        step(True)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / a.steps
+    lb = LayerBench(lay, a.chunk, dev)
+    ms_per_step, phases = lb.run(a.steps, a.warmup)
+    chunk = lb.chunk
+    ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    names = ["hessian", "damp_cholesky_inverse", "quantize_layer", "pack"]
-    phases = {nm: sum(mk[i].elapsed_time(mk[i + 1]) for mk in phase_events) / len(phase_events) for i, nm in enumerate(names)}
-    syrk_ms = [e0.elapsed_time(e1) for (e0, e1, _) in syrk_events]
+    syrk_ms = [e0.elapsed_time(e1) for (e0, e1, _) in lb.syrk_events]
     syrk_avg_ms = sum(syrk_ms) / len(syrk_ms)
-    syrk_flops_per_launch = sum(float(n) * (n + 1) * t for (_, _, t) in syrk_events) / len(syrk_events)
+    syrk_flops_per_launch = sum(float(n) * (n + 1) * t for (_, _, t) in lb.syrk_events) / len(lb.syrk_events)
     achieved = syrk_flops_per_launch / (syrk_avg_ms * 1e-3) / 1e12
     total_flops = sum(flops.values())
+    tf, frac = phase_rates(flops, phases, r, n, lb.packed.numel())
 
-    # Consumers of the packed layer (outside the timed step): batch-1 product and full decompression
-    xv = torch.randn(n, device=dev).half()
-    yv = torch.empty(r, dtype=torch.float32, device=dev)
-    Wd = torch.empty((r, n), dtype=torch.float16, device=dev)
     def timed(fn, reps):
         fn(); torch.cuda.synchronize()
         e0, e1 = ev(), ev()
@@ -266,27 +305,51 @@ def main():
             fn()
         e1.record(); torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
+
+    # Consumers of the packed layer (outside the timed step): batch-1 product and full decompression
+    packed, scales, zeros, pbits = lb.packed, lb.scales, lb.zeros, lb.pbits
+    xv = torch.randn(n, device=dev).half()
+    yv = torch.empty(r, dtype=torch.float32, device=dev)
+    Wd = torch.empty((r, n), dtype=torch.float16, device=dev)
     mv_ms = timed(lambda: g.gptq_matvec_packed(packed, n, pbits, scales, zeros, lay.group, xv, yv), 50)
     dq_ms = timed(lambda: g.gptq_dequantize_packed(packed, n, pbits, scales, zeros, lay.group, Wd), 10)
     grid_bytes = scales.numel() * 8
     mv_bytes = packed.numel() * 4 + grid_bytes + n * 2 + r * 4
     dq_bytes = packed.numel() * 4 + grid_bytes + r * n * 2
     del Wd
+
+    # The float32 matrix-core GEMM that carries the larger share of the step (rank-1024 updates of the factorisation,
+    # of the inverse and of Alg. 1), timed alone through gptq_trailing_update at the shape of Alg. 1's median deferred
+    # update of this layer: W[r x n/2] -= E[r x 1024] U[1024 x n/2], operands taken from the buffers of the solve.
+    gemm = None
+    kk, nc = min(1024, n), (n // 2) // 256 * 256
+    if nc >= 256 and r >= 256:
+        Wt = torch.zeros((r, nc), dtype=torch.float32, device=dev)
+        Et = torch.randn((r, kk), dtype=torch.float32, device=dev)
+        Ut = lb.H[:kk, n - nc:]                                     # rows of the factor right of their diagonal block
+        g_ms = timed(lambda: g.gptq_trailing_update(Wt, Et, Ut), 10)
+        g_flops = 2.0 * r * nc * kk
+        gemm = {"kernel": f"gemm_f32_dma_kernel (gptq_trailing_update: W[{r}x{nc}] -= E[{r}x{kk}] U[{kk}x{nc}])", "bound": "mfma",
+                "achieved": g_flops / (g_ms * 1e-3) / 1e12, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
+                "frac": g_flops / (g_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS, "avg_launch_ms": g_ms, "flops_per_launch": g_flops,
+                "traffic": None}
+        del Wt, Et, Ut
+
+    traffic = MEASURED_SYRK_TRAFFIC.get((n, chunk)) if lay.x.dtype != torch.float32 else None
     out = {
         "metric": "gptq_layer_solve_tflops", "value": total_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1); u8 codes",
         "data": "synthetic",
+        "value_note": "all algorithmic flops of the solve (fp16 SYRK + fp32 factorisation, inverse and Alg. 1) over the step "
+                      "time: a throughput of the whole job, comparable with no single peak; see phase_frac_of_peak",
         "config": {"workload": f"{lay.name}: W {r}x{n} {str(lay.dtype).split('.')[-1]}, X {n}x{m} {str(lay.x.dtype).split('.')[-1]}, "
                                f"{lay.bits}-bit {lay.grid} grid, group {lay.group or 'per-row'}, B={lay.block}, damp {lay.percdamp}",
                    "tokens_per_accumulate_call": chunk},
         "phases_ms": {k: round(v, 3) for k, v in phases.items()},
-        "phase_tflops": {
-            "hessian_syrk": flops["hessian"] / (phases["hessian"] * 1e-3) / 1e12,
-            "cholesky_plus_inverse_f32": (flops["cholesky"] + flops["tri_inverse"]) / (phases["damp_cholesky_inverse"] * 1e-3) / 1e12,
-            "quantize_f32": flops["quantize"] / (phases["quantize_layer"] * 1e-3) / 1e12,
-        },
+        "phase_tflops": tf,
+        "phase_frac_of_peak": frac,
         "pack_GBps": (r * n + packed.numel() * 4) / (phases["pack"] * 1e-3) / 1e9,
         "algorithmic_flops": flops,
         "packed_consumers": {"matvec_us": mv_ms * 1e3, "matvec_GBps": mv_bytes / (mv_ms * 1e-3) / 1e9,
@@ -297,9 +360,29 @@ def main():
                      "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_F16_MFMA_TFLOPS,
                      "avg_launch_ms": syrk_avg_ms, "flops_per_launch": syrk_flops_per_launch,
-                     "traffic": MEASURED_SYRK_TRAFFIC_BYTES.get((n, chunk)) if lay.x.dtype != torch.float32 else None,
-                     "traffic_unit": "bytes per launch"},
+                     "traffic": traffic["bytes"] if traffic else None,
+                     "traffic_unit": "bytes per launch",
+                     "traffic_note": traffic["note"] if traffic else "not collected for this shape"},
+        "roofline_f32_gemm": gemm,
     }
+    # The other workload shapes, one short run each (1 warm-up + 2 timed steps): per-layer time and per-phase fraction of peak
+    if a.layer == "opt175b_fc2" and not a.no_other_layers:
+        del lb, packed, scales, zeros, xv, yv
+        torch.cuda.empty_cache()
+        others = {}
+        for name in OTHER_LAYERS:
+            ol = pick_layer(name, a.tokens)
+            ob = LayerBench(ol, 0, dev)
+            oms, oph = ob.run(2, 1)
+            ofl = flop_model(ol.r, ol.n, ol.x.m, ol.block)
+            otf, ofr = phase_rates(ofl, oph, ol.r, ol.n, ob.packed.numel())
+            others[name] = {"workload": f"W {ol.r}x{ol.n}, X {ol.n}x{ol.x.m}, {ol.bits}-bit {ol.grid}, group {ol.group or 'per-row'}",
+                            "ms_per_step": round(oms, 3), "phases_ms": {k: round(v, 3) for k, v in oph.items()},
+                            "phase_tflops": {k: round(v, 2) for k, v in otf.items()},
+                            "phase_frac_of_peak": {k: round(v, 4) for k, v in ofr.items()}}
+            del ob
+            torch.cuda.empty_cache()
+        out["other_layers"] = others
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(lay, flops)
     print(json.dumps(out))

@@ -177,6 +177,19 @@ GPTQ_API int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t
                         void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The lazy batch update on its own (Alg. 1, last statement of the outer loop; Section 3, Step 2):
+ *   W[r x ncols] -= E[r x k] * U[k x ncols]
+ * with E the scaled errors of k already quantized columns and U the rows of the factor that belong to them,
+ * restricted to the ncols columns still to be quantized -- the product gptq_quantize_layer issues after every
+ * block (k = 128, the rest of the current 1024-column outer block) and after every outer block (k = 1024, all
+ * later columns).  float32 on the matrix cores, float32 accumulation.  All three matrices row-major, 16-byte
+ * aligned, leading dimensions multiples of 4 elements (ldw >= ncols, lde >= k, ldu >= ncols).  Any size is taken;
+ * r % 256 == 0, ncols % 128 == 0 and k % 64 == 0 run on the large-tile kernel.  A zero size is a no-op.
+ */
+GPTQ_API int gptq_trailing_update(float* W, int64_t ldw, const float* E, int64_t lde, const float* U, int64_t ldu,
+                         int64_t r, int64_t ncols, int64_t k, void* stream);
+
+/*
  * Step 4 -- bit packing (the paper stores 3-bit weights densely, Section 4 "Practical Speedups",
  * but prints no layout; this one is ours).
  *

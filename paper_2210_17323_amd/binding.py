@@ -61,6 +61,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_quantize_layer_workspace_bytes.argtypes = [i64, i64, ci, i64]
     L.gptq_quantize_layer_workspace_bytes.restype = sz
     L.gptq_quantize_layer.argtypes = [vp, ci, i64, i64, i64, vp, i64, ci, ci, ci, i64, vp, i64, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.gptq_trailing_update.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i64, vp]
     L.gptq_pack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     L.gptq_unpack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     L.gptq_dequantize_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, i64, vp]
@@ -208,6 +209,17 @@ def gptq_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, grid: int, 
                                      _ptr(codes), _ld(codes), _ptr(scales), _ptr(zeros),
                                      _ptr(Wq), _ld(Wq) if Wq is not None else 0, _ptr(half_E2_rows),
                                      _ptr(ws), ws.numel(), _stream()))
+
+
+def gptq_trailing_update(W: torch.Tensor, E: torch.Tensor, U: torch.Tensor) -> None:
+    """W[r x ncols] -= E[r x k] @ U[k x ncols] (float32): the lazy batch update of Alg. 1."""
+    for t, nm in ((W, "W"), (E, "E"), (U, "U")):
+        _dev2d(t, nm, (torch.float32,))
+    r, ncols = W.shape
+    k = E.shape[1]
+    if E.shape[0] != r or U.shape != (k, ncols):
+        raise ValueError("need E [r x k] and U [k x ncols] for W [r x ncols]")
+    _check(lib().gptq_trailing_update(_ptr(W), _ld(W), _ptr(E), _ld(E), _ptr(U), _ld(U), r, ncols, k, _stream()))
 
 
 def gptq_pack(codes: torch.Tensor, bits: int, out: torch.Tensor) -> None:

@@ -362,6 +362,20 @@ static QuantWs quant_ws_layout(int64_t r, int64_t n) {
 
 using namespace gptq;
 
+extern "C" int gptq_trailing_update(float* W, int64_t ldw, const float* E, int64_t lde, const float* U, int64_t ldu,
+                                    int64_t r, int64_t ncols, int64_t k, void* stream) {
+    if (r < 0 || ncols < 0 || k < 0) return fail(GPTQ_ERR_INVALID_ARG, "trailing_update: negative size");
+    if (r == 0 || ncols == 0 || k == 0) return GPTQ_OK;
+    if (!W || !E || !U) return fail(GPTQ_ERR_INVALID_ARG, "trailing_update: null pointer");
+    if (ldw < ncols || lde < k || ldu < ncols) return fail(GPTQ_ERR_INVALID_ARG, "trailing_update: leading dimension smaller than the row length");
+    if (!aligned(W, 16) || !aligned(E, 16) || !aligned(U, 16) || ldw % 4 || lde % 4 || ldu % 4)
+        return fail(GPTQ_ERR_INVALID_ARG, "trailing_update: W, E and U must be 16-byte aligned with leading dimensions that are multiples of 4");
+    GemmF32 g{};
+    g.A = E; g.lda = lde; g.B = U; g.ldb = ldu; g.C = W; g.ldc = ldw;
+    g.M = r; g.N = ncols; g.K = k; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
+    return launch_gemm_f32(g, static_cast<hipStream_t>(stream));
+}
+
 extern "C" size_t gptq_quantize_layer_workspace_bytes(int64_t r, int64_t n, int block, int64_t group) {
     (void)block; (void)group;
     if (r < 0 || n < 0) return 0;

@@ -333,3 +333,21 @@ def test_empty_inputs_are_no_ops():
     out = torch.zeros((0, 3), dtype=torch.int32, device="cuda")
     g.gptq_pack(torch.zeros((0, 32), dtype=torch.uint8, device="cuda"), 3, out)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("r,ncols,k", [(256, 1024, 128), (512, 2304, 1024), (130, 200, 128), (7, 36, 20)])
+def test_trailing_update_matches_oracle(r, ncols, k):
+    # Alg. 1's lazy batch update W -= E U on its own: float32 products against the float64 product of the same inputs
+    _say(f"trailing update r={r} ncols={ncols} k={k}")
+    rng = np.random.default_rng(r + ncols + k)
+    W0 = rng.normal(size=(r, ncols)).astype(np.float32)
+    E = rng.normal(size=(r, k)).astype(np.float32)
+    U = (rng.normal(size=(k, ncols)) / np.sqrt(k)).astype(np.float32)
+    Wd = _padded(r, ncols, torch.float32, 4); Wd.copy_(torch.from_numpy(W0))
+    Ed = _padded(r, k, torch.float32, 4); Ed.copy_(torch.from_numpy(E))
+    Ud = _padded(k, ncols, torch.float32, 4); Ud.copy_(torch.from_numpy(U))
+    g.gptq_trailing_update(Wd, Ed, Ud)
+    want = W0.astype(np.float64) - E.astype(np.float64) @ U.astype(np.float64)
+    err = _rel_fro(Wd.double().cpu().numpy(), want)
+    _say(f"  rel_fro={err:.3e}")
+    assert err <= 1e-6              # float32 accumulation of k terms: about sqrt(k) * 6e-8

@@ -76,6 +76,12 @@ def test_argument_validation_happens_on_the_host():
     assert q(wsb=1024) == WORKSPACE
     assert q(r=0) == OK
     assert q(grid=1, bits=0, wsb=8) == WORKSPACE   # ternary ignores bits; fails later on the workspace
+    tu = L.gptq_trailing_update
+    assert tu(ctypes.c_void_p(260), 64, one, 8, one, 64, 4, 64, 8, None) == INVALID and "aligned" in _err()
+    assert tu(one, 64, one, 10, one, 64, 4, 64, 8, None) == INVALID          # lde % 4
+    assert tu(one, 60, one, 8, one, 64, 4, 64, 8, None) == INVALID          # ldw < ncols
+    assert tu(None, 64, one, 8, one, 64, 4, 64, 8, None) == INVALID
+    assert tu(one, 64, one, 8, one, 64, 0, 64, 8, None) == OK and tu(one, 64, one, 8, one, 64, 4, 64, 0, None) == OK
     assert L.gptq_pack(one, 64, 2, 64, 5, one, 8, None) == INVALID
     assert L.gptq_pack(one, 64, 2, 64, 3, one, 5, None) == INVALID      # 64*3/32 = 6 words needed
     assert L.gptq_pack(one, 32, 2, 64, 3, one, 6, None) == INVALID      # ldc < n
