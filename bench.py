@@ -46,6 +46,11 @@ def parse():
                     help="tokens per gptq_hessian_accumulate call (default: 32768; all tokens at once for layers of up to "
                          "6144 input channels, whose few tiles make the library split the token range of a call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--form", choices=["auto", "factor", "inverse"], default="auto",
+                    help="steps 2 and 3.  factor: gptq_damp_cholesky + gptq_quantize_layer_from_factor (Alg. 1 driven by the Cholesky "
+                         "factor of H + lambda I itself, no triangular inverse; per-row grids only).  inverse: "
+                         "gptq_damp_cholesky_inverse + gptq_quantize_layer (U = Cholesky of the inverse, any grid).  auto: factor "
+                         "for per-row grids, inverse for grouped ones")
     ap.add_argument("--no-other-layers", action="store_true",
                     help="skip the short runs of the other workload shapes that the default (opt175b_fc2) line carries as extra keys")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -178,11 +183,13 @@ def replace_rows(lay, r):
 class LayerBench:
     """Device buffers of one layer solve and the step that walks them through the four C-ABI calls."""
 
-    def __init__(self, lay, chunk_arg: int, dev):
+    def __init__(self, lay, chunk_arg: int, dev, factor_form: bool = False):
         import torch
         import paper_2210_17323_amd as g
         from workloads import configs
         self.g, self.torch, self.lay = g, torch, lay
+        # factor_form: steps 2 and 3 through gptq_damp_cholesky + gptq_quantize_layer_from_factor (no triangular inverse)
+        self.factor_form = factor_form
         r, n, m = lay.r, lay.n, lay.x.m
         self.W, self.X = configs.materialize(lay, dev)
         self.H = torch.empty((n, n), dtype=torch.float32, device=dev)
@@ -216,10 +223,13 @@ class LayerBench:
             if record:
                 e1.record(); self.syrk_events.append((e0, e1, c1 - c0))
         if record: marks[1].record()
-        g.gptq_damp_cholesky_inverse(self.H, lay.percdamp, self.chol_ws, self.info)
+        if self.factor_form:
+            g.gptq_damp_cholesky(self.H, lay.percdamp, self.chol_ws, self.info)
+        else:
+            g.gptq_damp_cholesky_inverse(self.H, lay.percdamp, self.chol_ws, self.info)
         if record: marks[2].record()
         g.gptq_quantize_layer(self.W, self.H, lay.bits, self.grid, lay.block, lay.group, self.codes, self.scales, self.zeros,
-                              self.q_ws, None, self.half)
+                              self.q_ws, None, self.half, from_factor=self.factor_form)
         if record: marks[3].record()
         g.gptq_pack(self.codes, self.pbits, self.packed)
         if record:
@@ -244,10 +254,11 @@ class LayerBench:
         return ms_per_step, phases
 
 
-def phase_rates(flops, phases, r, n, packed_numel):
+def phase_rates(flops, phases, r, n, packed_numel, factor_form=False):
+    chol_flops = flops["cholesky"] + (0.0 if factor_form else flops["tri_inverse"])
     tf = {
         "hessian_syrk": flops["hessian"] / (phases["hessian"] * 1e-3) / 1e12,
-        "cholesky_plus_inverse_f32": (flops["cholesky"] + flops["tri_inverse"]) / (phases["damp_cholesky_inverse"] * 1e-3) / 1e12,
+        "cholesky_plus_inverse_f32": chol_flops / (phases["damp_cholesky_inverse"] * 1e-3) / 1e12,
         "quantize_f32": flops["quantize"] / (phases["quantize_layer"] * 1e-3) / 1e12,
     }
     frac = {
@@ -259,6 +270,8 @@ def phase_rates(flops, phases, r, n, packed_numel):
     return tf, frac
 
 
+FORM_NAME = {True: "gptq_damp_cholesky + gptq_quantize_layer_from_factor (Alg. 1 driven by the factor R of H + lambda I; no triangular inverse)",
+             False: "gptq_damp_cholesky_inverse + gptq_quantize_layer (U = Cholesky((H + lambda I)^-1)^T)"}
 OTHER_LAYERS = ["opt175b_fc1", "opt175b_q", "bloom176b_qkv_2bit_g128", "bloom176b_out_ternary_g128", "opt6.7b_attn"]
 
 
@@ -285,7 +298,8 @@ def main():
         torch.mul(src, 1.0, out=dst)        # an elementwise kernel (a same-dtype copy_ would be a DMA transfer, not a kernel)
         torch.cuda.synchronize()
         del src, dst
-    lb = LayerBench(lay, a.chunk, dev)
+    factor_form = a.form == "factor" or (a.form == "auto" and lay.group == 0)
+    lb = LayerBench(lay, a.chunk, dev, factor_form=factor_form)
     ms_per_step, phases = lb.run(a.steps, a.warmup)
     chunk = lb.chunk
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -294,8 +308,10 @@ def main():
     syrk_avg_ms = sum(syrk_ms) / len(syrk_ms)
     syrk_flops_per_launch = sum(float(n) * (n + 1) * t for (_, _, t) in lb.syrk_events) / len(lb.syrk_events)
     achieved = syrk_flops_per_launch / (syrk_avg_ms * 1e-3) / 1e12
+    if factor_form:
+        flops = dict(flops, tri_inverse=0.0)            # this form has no triangular inverse: not counted
     total_flops = sum(flops.values())
-    tf, frac = phase_rates(flops, phases, r, n, lb.packed.numel())
+    tf, frac = phase_rates(flops, phases, r, n, lb.packed.numel(), factor_form)
 
     def timed(fn, reps):
         fn(); torch.cuda.synchronize()
@@ -346,7 +362,8 @@ def main():
                       "time: a throughput of the whole job, comparable with no single peak; see phase_frac_of_peak",
         "config": {"workload": f"{lay.name}: W {r}x{n} {str(lay.dtype).split('.')[-1]}, X {n}x{m} {str(lay.x.dtype).split('.')[-1]}, "
                                f"{lay.bits}-bit {lay.grid} grid, group {lay.group or 'per-row'}, B={lay.block}, damp {lay.percdamp}",
-                   "tokens_per_accumulate_call": chunk},
+                   "tokens_per_accumulate_call": chunk,
+                   "steps_2_and_3": FORM_NAME[factor_form]},
         "phases_ms": {k: round(v, 3) for k, v in phases.items()},
         "phase_tflops": tf,
         "phase_frac_of_peak": frac,
@@ -367,16 +384,28 @@ def main():
     }
     # The other workload shapes, one short run each (1 warm-up + 2 timed steps): per-layer time and per-phase fraction of peak
     if a.layer == "opt175b_fc2" and not a.no_other_layers:
+        # the same layer through the other pair of calls (2 timed steps), on the buffers of the headline run
+        if factor_form and a.form == "auto":
+            lb.factor_form, lb.syrk_events, lb.phase_events = False, [], []
+            ims, iph = lb.run(2, 1)
+            ifl = flop_model(r, n, m, lay.block)
+            itf, ifr = phase_rates(ifl, iph, r, n, lb.packed.numel(), False)
+            out["same_layer_inverse_form"] = {"steps_2_and_3": FORM_NAME[False], "ms_per_step": round(ims, 3),
+                                              "phases_ms": {k: round(v, 3) for k, v in iph.items()},
+                                              "phase_tflops": {k: round(v, 2) for k, v in itf.items()},
+                                              "phase_frac_of_peak": {k: round(v, 4) for k, v in ifr.items()}}
         del lb, packed, scales, zeros, xv, yv
         torch.cuda.empty_cache()
         others = {}
         for name in OTHER_LAYERS:
             ol = pick_layer(name, a.tokens)
-            ob = LayerBench(ol, 0, dev)
+            off = ol.group == 0
+            ob = LayerBench(ol, 0, dev, factor_form=off)
             oms, oph = ob.run(2, 1)
             ofl = flop_model(ol.r, ol.n, ol.x.m, ol.block)
-            otf, ofr = phase_rates(ofl, oph, ol.r, ol.n, ob.packed.numel())
+            otf, ofr = phase_rates(ofl, oph, ol.r, ol.n, ob.packed.numel(), off)
             others[name] = {"workload": f"W {ol.r}x{ol.n}, X {ol.n}x{ol.x.m}, {ol.bits}-bit {ol.grid}, group {ol.group or 'per-row'}",
+                            "steps_2_and_3": FORM_NAME[off],
                             "ms_per_step": round(oms, 3), "phases_ms": {k: round(v, 3) for k, v in oph.items()},
                             "phase_tflops": {k: round(v, 2) for k, v in otf.items()},
                             "phase_frac_of_peak": {k: round(v, 4) for k, v in ofr.items()}}

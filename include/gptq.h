@@ -177,6 +177,33 @@ GPTQ_API int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t
                         void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Steps 2 and 3 without the inverse.  Alg. 1 can be driven by R, the Cholesky factor of H + lambda I itself
+ * (H + lambda I = R R^T, R upper triangular), instead of U = Cholesky((H + lambda I)^-1)^T = R^-1: with
+ * d_i = w_i - q_i (original weight minus its grid value) for the columns already quantized, the weight Alg. 1 holds
+ * at column j is w_j + (sum_{i<j} d_i R[i][j]) / R[j][j] (the minimiser of Eq. 1 over the free columns makes
+ * (delta R)_k vanish there), and its scaled error is e_j = (that weight - q_j) R[j][j] because U[j][j] = 1 / R[j][j]
+ * (Section 3, Step 3; Eq. 2, Eq. 3).  Same codes as gptq_damp_cholesky_inverse + gptq_quantize_layer up to rounding
+ * ties of the float32 arithmetic, at half the factorisation work (no triangular inverse).
+ *
+ * gptq_damp_cholesky: as gptq_damp_cholesky_inverse, but stops after the factorisation.  Out: R in the upper triangle
+ *   of H_R, zeros strictly below.  Workspace and info_dev as there.
+ * gptq_quantize_layer_from_factor: as gptq_quantize_layer with R in place of U.  One grid per row only (group must
+ *   be 0: a grid taken from the current weights in the middle of the walk is GPTQ_ERR_UNSUPPORTED here, use the U
+ *   form).  W is read in its own type at every block (it is not copied); the workspace
+ *   (gptq_quantize_layer_workspace_bytes) holds the float32 accumulators instead.  All other arguments, outputs
+ *   (codes, scales, zeros, Wq, half_E2_rows) and error behaviour as for gptq_quantize_layer.
+ */
+GPTQ_API size_t gptq_damp_cholesky_workspace_bytes(int64_t n);
+GPTQ_API int gptq_damp_cholesky(float* H_R, int64_t ld, int64_t n, float percdamp,
+                       void* ws, size_t ws_bytes, int* info_dev, void* stream);
+GPTQ_API int gptq_quantize_layer_from_factor(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
+                                    const float* R, int64_t ldr,
+                                    int bits, int grid, int block, int64_t group,
+                                    uint8_t* codes, int64_t ldc, float* scales, int32_t* zeros,
+                                    float* Wq, int64_t ldq, double* half_E2_rows,
+                                    void* ws, size_t ws_bytes, void* stream);
+
+/*
  * The lazy batch update on its own (Alg. 1, last statement of the outer loop; Section 3, Step 2):
  *   W[r x ncols] -= E[r x k] * U[k x ncols]
  * with E the scaled errors of k already quantized columns and U the rows of the factor that belong to them,

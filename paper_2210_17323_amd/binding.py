@@ -61,6 +61,10 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_quantize_layer_workspace_bytes.argtypes = [i64, i64, ci, i64]
     L.gptq_quantize_layer_workspace_bytes.restype = sz
     L.gptq_quantize_layer.argtypes = [vp, ci, i64, i64, i64, vp, i64, ci, ci, ci, i64, vp, i64, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.gptq_damp_cholesky_workspace_bytes.argtypes = [i64]
+    L.gptq_damp_cholesky_workspace_bytes.restype = sz
+    L.gptq_damp_cholesky.argtypes = [vp, i64, i64, f32, vp, sz, vp, vp]
+    L.gptq_quantize_layer_from_factor.argtypes = L.gptq_quantize_layer.argtypes
     L.gptq_trailing_update.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i64, vp]
     L.gptq_pack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     L.gptq_unpack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
@@ -165,6 +169,18 @@ def gptq_damp_cholesky_inverse(H_U: torch.Tensor, percdamp: float, ws: torch.Ten
     _check(lib().gptq_damp_cholesky_inverse(_ptr(H_U), _ld(H_U), n, percdamp, _ptr(ws), ws.numel(), _ptr(info), _stream()))
 
 
+def gptq_damp_cholesky_workspace_bytes(n: int) -> int:
+    return lib().gptq_damp_cholesky_workspace_bytes(n)
+
+
+def gptq_damp_cholesky(H_R: torch.Tensor, percdamp: float, ws: torch.Tensor, info: torch.Tensor) -> None:
+    """In place: the upper triangle of H becomes R with H + lambda I = R R^T (no inverse)."""
+    _dev2d(H_R, "H_R", (torch.float32,))
+    if info.dtype != torch.int32 or not info.is_cuda or ws.dtype != torch.uint8 or not ws.is_cuda:
+        raise ValueError("info must be a GPU int32 tensor and ws a GPU uint8 tensor")
+    _check(lib().gptq_damp_cholesky(_ptr(H_R), _ld(H_R), H_R.shape[0], percdamp, _ptr(ws), ws.numel(), _ptr(info), _stream()))
+
+
 def gptq_noalloc_max_n() -> int:
     return lib().gptq_noalloc_max_n()
 
@@ -190,7 +206,10 @@ def gptq_quantize_layer_workspace_bytes(r: int, n: int, block: int = 128, group:
 
 def gptq_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, grid: int, block: int, group: int,
                         codes: torch.Tensor, scales: torch.Tensor, zeros: torch.Tensor, ws: torch.Tensor,
-                        Wq: torch.Tensor | None = None, half_E2_rows: torch.Tensor | None = None) -> None:
+                        Wq: torch.Tensor | None = None, half_E2_rows: torch.Tensor | None = None,
+                        from_factor: bool = False) -> None:
+    """Alg. 1 with U = Cholesky((H + lambda I)^-1)^T, or -- from_factor=True, gptq_quantize_layer_from_factor -- with
+    the Cholesky factor R of H + lambda I in its place."""
     _dev2d(W, "W", tuple(_DTYPE))
     _dev2d(U, "U", (torch.float32,))
     _dev2d(codes, "codes", (torch.uint8,))
@@ -205,10 +224,15 @@ def gptq_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, grid: int, 
         _dev2d(Wq, "Wq", (torch.float32,))
     if half_E2_rows is not None and (half_E2_rows.dtype != torch.float64 or half_E2_rows.numel() != r or not half_E2_rows.is_cuda):
         raise ValueError("half_E2_rows must be a GPU float64 tensor of r elements")
-    _check(lib().gptq_quantize_layer(_ptr(W), _DTYPE[W.dtype], _ld(W), r, n, _ptr(U), _ld(U), bits, grid, block, group,
-                                     _ptr(codes), _ld(codes), _ptr(scales), _ptr(zeros),
-                                     _ptr(Wq), _ld(Wq) if Wq is not None else 0, _ptr(half_E2_rows),
-                                     _ptr(ws), ws.numel(), _stream()))
+    fn = lib().gptq_quantize_layer_from_factor if from_factor else lib().gptq_quantize_layer
+    _check(fn(_ptr(W), _DTYPE[W.dtype], _ld(W), r, n, _ptr(U), _ld(U), bits, grid, block, group,
+          _ptr(codes), _ld(codes), _ptr(scales), _ptr(zeros),
+          _ptr(Wq), _ld(Wq) if Wq is not None else 0, _ptr(half_E2_rows),
+          _ptr(ws), ws.numel(), _stream()))
+
+
+def gptq_quantize_layer_from_factor(W, R, bits, grid, block, group, codes, scales, zeros, ws, Wq=None, half_E2_rows=None) -> None:
+    gptq_quantize_layer(W, R, bits, grid, block, group, codes, scales, zeros, ws, Wq, half_E2_rows, from_factor=True)
 
 
 def gptq_trailing_update(W: torch.Tensor, E: torch.Tensor, U: torch.Tensor) -> None:

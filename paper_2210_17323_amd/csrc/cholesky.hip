@@ -291,7 +291,9 @@ static int chol_check_args(const float* H, int64_t ld, int64_t n, float percdamp
 
 // The whole of step 2 on validated arguments.  `ws` holds chol_ws_layout(n).total bytes; nothing in it has to be
 // initialised (every region is written in this call before it is read).  lookahead = false keeps all work on `s`.
-static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, int* info_dev, hipStream_t s, bool lookahead) {
+// want_inverse = false stops after the factorisation: H holds R (upper triangular, zeros below) with H + lambda I = R R^T.
+static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, int* info_dev, hipStream_t s, bool lookahead,
+                    bool want_inverse = true) {
     const CholWs w = chol_ws_layout(ws, n);
     float* dinv = w.dinv;
     constexpr size_t diag_lds = (2 * NB * DP + 32 * 64) * sizeof(float);
@@ -368,6 +370,7 @@ static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, i
     // lower half and the below-diagonal parts of straddling update tiles); nothing writes there afterwards.
     hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
     GPTQ_LAUNCH_CHECK();
+    if (!want_inverse) return GPTQ_OK;
     {
         hipEvent_t cleared = nullptr;
         if (int rc = ts.mark(s, &cleared)) return rc;
@@ -435,6 +438,17 @@ extern "C" int gptq_damp_cholesky_inverse(float* H, int64_t ld, int64_t n, float
     if (!ws || !aligned(ws, 256) || ws_bytes < gptq_damp_cholesky_inverse_workspace_bytes(n))
         return fail(GPTQ_ERR_WORKSPACE, "damp_cholesky_inverse: workspace missing, misaligned or too small");
     return chol_run(H, ld, n, percdamp, ws, info_dev, static_cast<hipStream_t>(stream), true);
+}
+
+extern "C" size_t gptq_damp_cholesky_workspace_bytes(int64_t n) { return gptq_damp_cholesky_inverse_workspace_bytes(n); }
+
+extern "C" int gptq_damp_cholesky(float* H, int64_t ld, int64_t n, float percdamp,
+                                  void* ws, size_t ws_bytes, int* info_dev, void* stream) {
+    int rc;
+    if (chol_check_args(H, ld, n, percdamp, info_dev, &rc)) return rc;
+    if (!ws || !aligned(ws, 256) || ws_bytes < gptq_damp_cholesky_workspace_bytes(n))
+        return fail(GPTQ_ERR_WORKSPACE, "damp_cholesky: workspace missing, misaligned or too small");
+    return chol_run(H, ld, n, percdamp, ws, info_dev, static_cast<hipStream_t>(stream), true, false);
 }
 
 // ---- the variant that allocates nothing -------------------------------------------------------------------

@@ -140,22 +140,56 @@ struct QuantState {
     int zero;
     float* edst;                        // this row of the block's error matrix
     bool active;                        // row inside the matrix
+    __device__ __forceinline__ float (&acc())[QB] { return w; }      // what the rank-1 updates of a column go to
+};
+
+// The same walk driven by the Cholesky factor R of H + lambda I itself instead of U = R^-1 (see quant_block_rf_kernel):
+// the original weights stay as they are and the updates go to an accumulator s[k] = sum over quantized i of d_i R[i][k].
+template <typename WT> struct WeightRegs {                  // float32 weights: one register each
+    float v[QB];
+    template <int J> __device__ __forceinline__ float get() const { return v[J]; }
+};
+template <> struct WeightRegs<_Float16> {                    // 16-bit weights stay packed two to a register
+    uint32_t v[QB / 2];
+    template <int J> __device__ __forceinline__ float get() const {
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(v[J / 2] >> (16 * (J & 1))));
+    }
+};
+template <> struct WeightRegs<__bf16> {
+    uint32_t v[QB / 2];
+    template <int J> __device__ __forceinline__ float get() const {
+        return __builtin_bit_cast(float, (J & 1) ? (v[J / 2] & 0xffff0000u) : (v[J / 2] << 16));
+    }
+};
+
+template <typename WT>
+struct FactorState {
+    WeightRegs<WT> w;                   // original weights of the block
+    float s[QB];                        // accumulators; d_j = w_j - q_j once column j is done
+    float ring[ustream::RING];
+    uint32_t packed[4];                 // codes of the current 16 columns, four to a word
+    float e2, scale, zf;
+    int zero;
+    float* edst;                        // this row of the block's matrix of d
+    uint8_t* cdst;                      // this row's codes of the block (16-byte aligned) or null
+    bool active;
+    __device__ __forceinline__ float (&acc())[QB] { return s; }
 };
 
 // Volatile on purpose: volatile accesses and volatile asm statements (the multiply-adds below) keep their
 // program order, which is what places each request RING chunks ahead of its use.  An ordinary load has no such
 // order: with the whole column loop one straight line, the compiler either hoists all requests to the top or
 // sinks each one down to its use and then waits for it.  `ubl` is the block in LDS offset by lane % 16.
-template <int T>
-__device__ __forceinline__ void request_chunk(QuantState& st, lds_floats ubl) {
+template <int T, class St>
+__device__ __forceinline__ void request_chunk(St& st, lds_floats ubl) {
     if constexpr (T < ustream::TOTAL) {
         constexpr int j = ustream::row_at(T), q = ustream::first_chunk(j) + (T - ustream::start(j));
         st.ring[T % ustream::RING] = *static_cast<lds_floats_ordered>(ubl + j * QB + ustream::CHUNK * q);
     }
 }
 
-template <int... T>
-__device__ __forceinline__ void request_first(QuantState& st, lds_floats ubl, std::integer_sequence<int, T...>) {
+template <class St, int... T>
+__device__ __forceinline__ void request_first(St& st, lds_floats ubl, std::integer_sequence<int, T...>) {
     (request_chunk<T>(st, ubl), ...);
 }
 
@@ -169,24 +203,63 @@ __device__ __forceinline__ void fma_bcast(float& w, float u, float ne) {
         asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(w) : "v"(u), "v"(ne), "n"(C));
 }
 
-template <int J, int K0, int... C>
-__device__ __forceinline__ void update_chunk_columns(QuantState& st, float u, float ne, std::integer_sequence<int, C...>) {
+template <int J, int K0, class St, int... C>
+__device__ __forceinline__ void update_chunk_columns(St& st, float u, float ne, std::integer_sequence<int, C...>) {
     // columns K0 + C right of J; the first one issued carries the s_nop
     constexpr int first = (J >= K0) ? J - K0 + 1 : 0;
-    ((K0 + C > J ? fma_bcast<C, C == first>(st.w[K0 + C], u, ne) : (void)0), ...);
+    ((K0 + C > J ? fma_bcast<C, C == first>(st.acc()[K0 + C], u, ne) : (void)0), ...);
 }
 
 // w[k] -= e * U[J][k] for the columns of chunk Q right of J, then the request that refills the slot
-template <int J, int Q>
-__device__ __forceinline__ void update_chunk(QuantState& st, lds_floats ubl, float ne) {
+template <int J, int Q, class St>
+__device__ __forceinline__ void update_chunk(St& st, lds_floats ubl, float ne) {
     constexpr int t = ustream::start(J) + Q, k0 = ustream::CHUNK * (ustream::first_chunk(J) + Q);
     update_chunk_columns<J, k0>(st, st.ring[t % ustream::RING], ne, std::make_integer_sequence<int, ustream::CHUNK>{});
     request_chunk<t + ustream::RING>(st, ubl);
 }
 
-template <int J, int... Q>
-__device__ __forceinline__ void update_row(QuantState& st, lds_floats ubl, float ne, std::integer_sequence<int, Q...>) {
+template <int J, class St, int... Q>
+__device__ __forceinline__ void update_row(St& st, lds_floats ubl, float ne, std::integer_sequence<int, Q...>) {
     (update_chunk<J, Q>(st, ubl, ne), ...);
+}
+
+// The 128 x 128 diagonal block of an upper-triangular matrix M (U, or the factor R) into LDS:
+// ubs[j][k] = M[j0+j][j0+k] for k >= j, zero below the diagonal, identity outside the matrix.  The whole workgroup
+// (256 threads) calls it: 16 independent 16-byte loads per thread (in PARTS passes of 16 / PARTS, for callers short
+// of registers), then one barrier.
+template <int PARTS = 1>
+__device__ __forceinline__ void stage_diag_block(float* ubs, const float* M, int64_t ldm, int64_t j0, int64_t n) {
+    const int tid = threadIdx.x;
+    constexpr int PER = 16 / PARTS;
+#pragma unroll
+    for (int part = 0; part < PARTS; ++part) {
+    float4 in[PER];
+#pragma unroll
+    for (int tt = 0; tt < PER; ++tt) {
+        const int t = part * PER + tt;
+        const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
+        const int64_t gj = j0 + j, gk = j0 + k;
+        const float* src = M + gj * ldm + gk;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gj < n && gk + 4 <= n) v = *reinterpret_cast<const float4*>(src);
+        else if (gj < n && gk < n) { v.x = src[0]; if (gk + 1 < n) v.y = src[1]; if (gk + 2 < n) v.z = src[2]; }
+        in[tt] = v;
+    }
+#pragma unroll
+    for (int tt = 0; tt < PER; ++tt) {
+        const int t = part * PER + tt;
+        const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
+        const int64_t gj = j0 + j, gk = j0 + k;
+        float e[4] = {in[tt].x, in[tt].y, in[tt].z, in[tt].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool inside = gj < n && gk + c < n;
+            e[c] = inside ? (k + c >= j ? e[c] : 0.f) : (k + c == j ? 1.f : 0.f);
+        }
+        *reinterpret_cast<float4*>(&ubs[j * QB + k]) = make_float4(e[0], e[1], e[2], e[3]);
+    }
+    }
+    __syncthreads();
 }
 
 // Column J of the block: its grid if a group starts here, the code, the error, the update of the columns right of it.
@@ -263,36 +336,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int k = 0; k < QB; ++k) w[k] = (k < a.nbk) ? src[k] : 0.f;
         }
     }
-    // ---- the diagonal block of U into LDS: ubs[j][k] = U[j0+j][j0+k] for k >= j, identity outside the
-    //      matrix.  16 independent 16-byte loads per thread.
     __shared__ __align__(16) float ubs[QB * QB];
-    {
-        const int tid = threadIdx.x;
-        float4 in[16];
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
-            const int64_t gj = a.j0 + j, gk = a.j0 + k;
-            const float* src = a.U + gj * a.ldu + gk;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gj < a.n && gk + 4 <= a.n) v = *reinterpret_cast<const float4*>(src);
-            else if (gj < a.n && gk < a.n) { v.x = src[0]; if (gk + 1 < a.n) v.y = src[1]; if (gk + 2 < a.n) v.z = src[2]; }
-            in[t] = v;
-        }
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
-            const int64_t gj = a.j0 + j, gk = a.j0 + k;
-            float e[4] = {in[t].x, in[t].y, in[t].z, in[t].w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const bool inside = gj < a.n && gk + c < a.n;
-                e[c] = inside ? (k + c >= j ? e[c] : 0.f) : (k + c == j ? 1.f : 0.f);
-            }
-            *reinterpret_cast<float4*>(&ubs[j * QB + k]) = make_float4(e[0], e[1], e[2], e[3]);
-        }
-        __syncthreads();
-    }
+    stage_diag_block<1>(ubs, a.U, a.ldu, a.j0, a.n);
     const float maxq = (float)a.maxq;
     st.scale = 1.f; st.zero = 0;
     if (G == 0) {
@@ -303,7 +348,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     st.zf = (float)st.zero;
     st.e2 = 0.f;
     lds_floats ub = (lds_floats)ubs + (threadIdx.x & 15);           // this lane's element of every chunk
-    request_first(st, ub, std::make_integer_sequence<int, ustream::RING>{});
+    request_first<QuantState>(st, ub, std::make_integer_sequence<int, ustream::RING>{});
     st.active = active;
     st.edst = a.E + rr * a.lde;
     quantize_columns<G>(st, ub, a, rr, maxq, std::make_integer_sequence<int, QB>{});
@@ -323,6 +368,166 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (a.half_e2) {
         const double prev = a.first_block ? 0.0 : a.half_e2[row];
         a.half_e2[row] = prev + 0.5 * (double)e2;
+    }
+}
+
+// ---- the factor form: Alg. 1 driven by R, the Cholesky factor of H + lambda I itself (H + lambda I = R R^T) -------
+// U = R^-1 is never formed.  With d_i = w_i - q_i (original weight minus grid value) for the columns already
+// quantized, the weight Alg. 1 holds at column j is  w_j + s_j / R[j][j],  s_j = sum_{i<j} d_i R[i][j]  -- the
+// unique correction that keeps (delta R)_k = 0 for the columns still free -- and Alg. 1's scaled error is
+// e_j = (that weight - q_j) R[j][j], since U[j][j] = 1 / R[j][j].  So the walk is the same as above with other
+// operands: the original weights stay untouched in registers, the rank-1 update of a column adds d_j R[j][k] to the
+// accumulators s[k], and the deferred updates are S[:, later] += D R[block, later] on the matrix cores.
+// One grid per row only (it comes from the original weights): a grid taken from the current weights in the middle of
+// the walk would need the waiting columns' corrections, a triangular solve per group start.
+struct FactorArgs {
+    const void* W; int64_t ldw;     // original weights, type WT
+    float* S; int64_t lds_;         // accumulators [r x n] (leading dimension lds_)
+    const float* R; int64_t ldr;
+    int64_t r, n, j0; int nbk;
+    int maxq;
+    const float* scales; const int32_t* zeros;      // [r]
+    uint8_t* codes; int64_t ldc;
+    uint8_t* cstage;                // [r x 128] bytes, 16-byte aligned: codes of a block that cannot be stored in place 16 at a time
+    float* D; int64_t ldd;          // this block's 128 columns of the outer matrix of d [r x 1024]
+    double* half_e2;
+    int first_block;
+};
+
+template <int J, typename WT>
+__device__ __forceinline__ void factor_column(FactorState<WT>& st, lds_floats ubs, float maxq) {
+    constexpr int diag_slot = ustream::start(J) % ustream::RING;        // row J's first chunk holds R[J][J]
+    const float rjj = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, st.ring[diag_slot]),
+                                                                            0x150 + J % ustream::CHUNK, 0xf, 0xf, true));   // row_newbcast
+    // s_j / R[J][J]: reciprocal estimate and one correction step with the exact remainder (the rounded quotient
+    // without the range scaling of a general division; R[J][J] is the square root of a pivot of the damped Hessian)
+    const float rcp = __builtin_amdgcn_rcpf(rjj);
+    const float sj = st.s[J];
+    const float t0 = sj * rcp;
+    const float wj = st.w.template get<J>();
+    const float wn = wj + fmaf(fmaf(-t0, rjj, sj), rcp, t0);           // the weight Alg. 1 holds at this column
+    const float x = wn / st.scale;
+    float c = rintf(x) + st.zf;
+    c = fminf(fmaxf(c, 0.f), maxq);
+    const float q = __fmul_rn(st.scale, c - st.zf);
+    const float d = wj - q;
+    const float e = (wn - q) * rjj;
+    const uint32_t ci = (uint32_t)c;
+    if constexpr ((J & 3) == 0) st.packed[(J >> 2) & 3] = ci; else st.packed[(J >> 2) & 3] |= ci << (8 * (J & 3));
+    st.e2 = fmaf(e, e, st.e2);
+    st.s[J] = d;
+    // Finished columns leave as they go, which frees their registers: d four at a time, codes sixteen at a time.  No
+    // test of `active` (it would cut the straight line into pieces): lanes past the last row work on a copy of the
+    // last row and store the same values to the same place as that row's own lane.
+    if constexpr ((J & 3) == 3)
+        *reinterpret_cast<float4*>(st.edst + J - 3) = make_float4(st.s[J - 3], st.s[J - 2], st.s[J - 1], st.s[J]);
+    if constexpr ((J & 15) == 15)
+        *reinterpret_cast<uint4*>(st.cdst + J - 15) = make_uint4(st.packed[0], st.packed[1], st.packed[2], st.packed[3]);
+    update_row<J>(st, ubs, d, std::make_integer_sequence<int, ustream::chunks(J)>{});
+}
+
+template <typename WT, int... J>
+__device__ __forceinline__ void factor_columns(FactorState<WT>& st, lds_floats ubs, float maxq, std::integer_sequence<int, J...>) {
+    (factor_column<J>(st, ubs, maxq), ...);
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void quant_block_rf_kernel(FactorArgs a) {
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool active = row < a.r;
+    const int64_t rr = active ? row : a.r - 1;
+    FactorState<WT> st;
+    {
+        // This lane's accumulators and original weights first (scattered loads, lanes are a whole row apart): their
+        // round trips overlap the staging of R below, which goes in two passes to stay inside the register file.
+        const float* src = a.S + rr * a.lds_ + a.j0;
+        const WT* wsrc = static_cast<const WT*>(a.W) + rr * a.ldw + a.j0;
+        if (a.nbk == QB) {
+#pragma unroll
+            for (int k = 0; k < QB; k += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(src + k);
+                st.s[k] = v.x; st.s[k + 1] = v.y; st.s[k + 2] = v.z; st.s[k + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < QB; ++k) st.s[k] = (k < a.nbk) ? src[k] : 0.f;
+        }
+        if constexpr (sizeof(WT) == 2) {
+            if (a.nbk == QB && (reinterpret_cast<uintptr_t>(wsrc) & 15) == 0) {
+#pragma unroll
+                for (int k = 0; k < QB / 2; k += 4) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(wsrc + 2 * k);
+                    st.w.v[k] = v.x; st.w.v[k + 1] = v.y; st.w.v[k + 2] = v.z; st.w.v[k + 3] = v.w;
+                }
+            } else {
+                const uint16_t* hsrc = reinterpret_cast<const uint16_t*>(wsrc);
+#pragma unroll
+                for (int k = 0; k < QB / 2; ++k) {
+                    const uint32_t lo = (2 * k < a.nbk) ? hsrc[2 * k] : 0u, hi = (2 * k + 1 < a.nbk) ? hsrc[2 * k + 1] : 0u;
+                    st.w.v[k] = lo | (hi << 16);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < QB; ++k) st.w.v[k] = (k < a.nbk) ? to_f32<WT>(wsrc[k]) : 0.f;
+        }
+    }
+    __shared__ __align__(16) float ubs[QB * QB];
+    stage_diag_block<2>(ubs, a.R, a.ldr, a.j0, a.n);
+    const float maxq = (float)a.maxq;
+    st.scale = a.scales[rr];
+    st.zero = a.zeros[rr];
+    st.zf = (float)st.zero;
+    st.e2 = 0.f;
+    lds_floats ub = (lds_floats)ubs + (threadIdx.x & 15);
+    request_first<FactorState<WT>>(st, ub, std::make_integer_sequence<int, ustream::RING>{});
+    st.active = active;
+    st.edst = a.D + rr * a.ldd;
+    // Codes go straight to their place when the block is whole and the row's 128 bytes are 16-byte aligned; otherwise
+    // (last, short block; odd leading dimension) to a 128-byte slot of the row in the scratch area `cstage`, and the
+    // valid ones are copied out below.
+    const bool direct = a.nbk == QB && ((reinterpret_cast<uintptr_t>(a.codes + rr * a.ldc + a.j0) & 15) == 0);
+    st.cdst = direct ? a.codes + rr * a.ldc + a.j0 : a.cstage + rr * QB;
+    factor_columns<WT>(st, ub, maxq, std::make_integer_sequence<int, QB>{});
+    const float e2 = st.e2;
+    if (!active) return;
+    if (!direct) {
+        const uint8_t* src = a.cstage + row * QB;
+        uint8_t* cdst = a.codes + row * a.ldc + a.j0;
+        for (int k = 0; k < a.nbk; ++k) cdst[k] = src[k];
+    }
+    if (a.half_e2) {
+        const double prev = a.first_block ? 0.0 : a.half_e2[row];
+        a.half_e2[row] = prev + 0.5 * (double)e2;
+    }
+}
+
+// One workgroup per row: the per-row grid from the original weights, and the row of accumulators cleared.
+template <typename T>
+__global__ __launch_bounds__(256) void prepare_rows_rf_kernel(const T* W, int64_t ldw, int64_t n, float* S, int64_t lds_,
+                                                              int grid, float maxq, float* scales, int32_t* zeros) {
+    const int64_t row = blockIdx.x;
+    float lo = INFINITY, hi = -INFINITY, am = 0.f;
+    for (int64_t k = threadIdx.x; k < n; k += 256) {
+        const float v = to_f32<T>(W[row * ldw + k]);
+        S[row * lds_ + k] = 0.f;
+        lo = fminf(lo, v); hi = fmaxf(hi, v); am = fmaxf(am, fabsf(v));
+    }
+    __shared__ float slo[256], shi[256], sam[256];
+    slo[threadIdx.x] = lo; shi[threadIdx.x] = hi; sam[threadIdx.x] = am;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            slo[threadIdx.x] = fminf(slo[threadIdx.x], slo[threadIdx.x + w]);
+            shi[threadIdx.x] = fmaxf(shi[threadIdx.x], shi[threadIdx.x + w]);
+            sam[threadIdx.x] = fmaxf(sam[threadIdx.x], sam[threadIdx.x + w]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        float sc; int zr;
+        grid_from_range(grid, maxq, slo[0], shi[0], sam[0], sc, zr);
+        scales[row] = sc; zeros[row] = zr;
     }
 }
 
@@ -347,13 +552,14 @@ static bool group_supported(int64_t group) {
 
 constexpr int QOB = 1024;   // outer block: trailing updates beyond it are deferred and applied as one rank-1024 GEMM
 
-struct QuantWs { size_t wk, e, total; int64_t ldk; };
+struct QuantWs { size_t wk, e, cs, total; int64_t ldk; };
 static QuantWs quant_ws_layout(int64_t r, int64_t n) {
     QuantWs l;
     l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
     l.wk = 0;
     size_t off = round_up((size_t)std::max<int64_t>(r, 1) * l.ldk * sizeof(float), 256);
     l.e = off; off += 2 * round_up((size_t)std::max<int64_t>(r, 1) * QOB * sizeof(float), 256);   // two error panels (look-ahead)
+    l.cs = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QB, 256);                        // codes of a block that cannot be stored in place
     l.total = off + 256;
     return l;
 }
@@ -382,12 +588,15 @@ extern "C" size_t gptq_quantize_layer_workspace_bytes(int64_t r, int64_t n, int 
     return quant_ws_layout(r, n).total;
 }
 
-extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
-                                   const float* U, int64_t ldu,
-                                   int bits, int grid, int block, int64_t group,
-                                   uint8_t* codes, int64_t ldc, float* scales, int32_t* zeros,
-                                   float* Wq, int64_t ldq, double* half_E2_rows,
-                                   void* ws, size_t ws_bytes, void* stream) {
+// Both forms of Alg. 1 share validation, blocking and look-ahead.  rf = false: `U` is Cholesky((H + lambda I)^-1)^T,
+// the working weights are updated (W -= E U).  rf = true: `U` is R with H + lambda I = R R^T, the accumulators are
+// updated (S += D R) and the weights are read from the caller's W as they are (one grid per row only).
+static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
+                    const float* U, int64_t ldu,
+                    int bits, int grid, int block, int64_t group,
+                    uint8_t* codes, int64_t ldc, float* scales, int32_t* zeros,
+                    float* Wq, int64_t ldq, double* half_E2_rows,
+                    void* ws, size_t ws_bytes, void* stream) {
     if (r < 0 || n < 0) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: negative size");
     if (grid != GPTQ_GRID_MINMAX && grid != GPTQ_GRID_TERNARY) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: unknown grid %d", grid);
     if (grid == GPTQ_GRID_MINMAX && (bits < 2 || bits > 4)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: bits must be 2, 3 or 4 (got %d)", bits);
@@ -398,6 +607,9 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     if (group > 0 && n % group) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: n must be a multiple of the group size");
     if (group > 0 && (QB % group) && (group % QB)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: a group must not straddle a block end (need 128 %% g == 0 or g %% 128 == 0)");
     if (!group_supported(group)) return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer: group size %lld not built (8, 16, 32, 64 or a multiple of 128)", (long long)group);
+    if (rf && group != 0)
+        return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer_from_factor: grouped grids are taken from the current weights, which this form does "
+                                          "not hold; use gptq_damp_cholesky_inverse + gptq_quantize_layer");
     if (r == 0 || n == 0) return GPTQ_OK;
     if (!W || !U || !codes || !scales || !zeros) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: null pointer");
     if (ldw < n || ldu < n || ldc < n || (Wq && ldq < n)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: leading dimension smaller than n");
@@ -415,6 +627,18 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     const int64_t ngroups = group ? n / group : 1;
     const int want_grid = group == 0;
 
+    if (rf) {
+        switch (wdtype) {
+            case GPTQ_F16:
+                hipLaunchKernelGGL(prepare_rows_rf_kernel<_Float16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const _Float16*>(W), ldw, n, Wk, lay.ldk, grid, (float)maxq, scales, zeros);
+                break;
+            case GPTQ_BF16:
+                hipLaunchKernelGGL(prepare_rows_rf_kernel<__bf16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const __bf16*>(W), ldw, n, Wk, lay.ldk, grid, (float)maxq, scales, zeros);
+                break;
+            default:
+                hipLaunchKernelGGL(prepare_rows_rf_kernel<float>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const float*>(W), ldw, n, Wk, lay.ldk, grid, (float)maxq, scales, zeros);
+        }
+    } else
     switch (wdtype) {
         case GPTQ_F16:
             hipLaunchKernelGGL(prepare_rows_kernel<_Float16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const _Float16*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
@@ -457,6 +681,18 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
                 hipLaunchKernelGGL(group_grid_kernel, dim3((unsigned)r), dim3(64), 0, s, (const float*)Wk, lay.ldk, j0, group, grid, (float)maxq, scales, zeros, ngroups, j0 / group);
                 GPTQ_LAUNCH_CHECK();
             }
+            if (rf) {
+                FactorArgs f{};
+                f.W = W; f.ldw = ldw; f.S = Wk; f.lds_ = lay.ldk; f.R = U; f.ldr = ldu; f.r = r; f.n = n; f.j0 = j0; f.nbk = nbk;
+                f.maxq = maxq; f.scales = scales; f.zeros = zeros; f.codes = codes; f.ldc = ldc;
+                f.cstage = reinterpret_cast<uint8_t*>(base + lay.cs);
+                f.D = E + (j0 - o0); f.ldd = QOB; f.half_e2 = half_E2_rows; f.first_block = (j0 == 0);
+                switch (wdtype) {
+                    case GPTQ_F16:  hipLaunchKernelGGL(quant_block_rf_kernel<_Float16>, dim3(qblocks), dim3(256), 0, s, f); break;
+                    case GPTQ_BF16: hipLaunchKernelGGL(quant_block_rf_kernel<__bf16>,  dim3(qblocks), dim3(256), 0, s, f); break;
+                    default:        hipLaunchKernelGGL(quant_block_rf_kernel<float>,   dim3(qblocks), dim3(256), 0, s, f); break;
+                }
+            } else {
             QuantArgs a{};
             a.Wk = Wk; a.ldk = lay.ldk; a.U = U; a.ldu = ldu; a.r = r; a.n = n; a.j0 = j0; a.nbk = nbk; a.grid = grid; a.maxq = maxq;
             a.scales = scales; a.zeros = zeros; a.ngroups = ngroups; a.group = group;
@@ -469,11 +705,12 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
                 case 32: hipLaunchKernelGGL(quant_block_kernel<32>, dim3(qblocks), dim3(256), 0, s, a); break;
                 default: hipLaunchKernelGGL(quant_block_kernel<64>, dim3(qblocks), dim3(256), 0, s, a); break;
             }
+            }
             GPTQ_LAUNCH_CHECK();
             if (j1 < o1) {
                 GemmF32 g{};
                 g.A = E + (j0 - o0); g.lda = QOB; g.B = U + j0 * ldu + j1; g.ldb = ldu; g.C = Wk + j1; g.ldc = lay.ldk;
-                g.M = r; g.N = o1 - j1; g.K = nbk; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
+                g.M = r; g.N = o1 - j1; g.K = nbk; g.alpha = rf ? 1.f : -1.f; g.b_is_nk = false; g.overwrite = false;
                 const int rc = launch_gemm_f32(g, s);
                 if (rc) return rc;
             }
@@ -485,7 +722,7 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
             if (int rc = ts.wait(s, rest_done)) return rc;      // it wrote the columns from o1 on
             GemmF32 g{};
             g.A = E; g.lda = QOB; g.B = U + o0 * ldu + o1; g.ldb = ldu; g.C = Wk + o1; g.ldc = lay.ldk;
-            g.M = r; g.N = o2 - o1; g.K = o1 - o0; g.alpha = -1.f; g.b_is_nk = false; g.overwrite = false;
+            g.M = r; g.N = o2 - o1; g.K = o1 - o0; g.alpha = rf ? 1.f : -1.f; g.b_is_nk = false; g.overwrite = false;
             int rc = launch_gemm_f32(g, s);
             if (rc) return rc;
             rest_done = nullptr;
@@ -504,4 +741,24 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
         GPTQ_LAUNCH_CHECK();
     }
     return GPTQ_OK;
+}
+
+extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
+                                   const float* U, int64_t ldu,
+                                   int bits, int grid, int block, int64_t group,
+                                   uint8_t* codes, int64_t ldc, float* scales, int32_t* zeros,
+                                   float* Wq, int64_t ldq, double* half_E2_rows,
+                                   void* ws, size_t ws_bytes, void* stream) {
+    return alg1_run(false, W, wdtype, ldw, r, n, U, ldu, bits, grid, block, group, codes, ldc, scales, zeros, Wq, ldq,
+                    half_E2_rows, ws, ws_bytes, stream);
+}
+
+extern "C" int gptq_quantize_layer_from_factor(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
+                                               const float* R, int64_t ldr,
+                                               int bits, int grid, int block, int64_t group,
+                                               uint8_t* codes, int64_t ldc, float* scales, int32_t* zeros,
+                                               float* Wq, int64_t ldq, double* half_E2_rows,
+                                               void* ws, size_t ws_bytes, void* stream) {
+    return alg1_run(true, W, wdtype, ldw, r, n, R, ldr, bits, grid, block, group, codes, ldc, scales, zeros, Wq, ldq,
+                    half_E2_rows, ws, ws_bytes, stream);
 }

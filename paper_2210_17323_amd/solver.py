@@ -45,8 +45,20 @@ def cholesky_inverse(H: torch.Tensor, percdamp: float = 0.01, check: bool = True
     return H
 
 
+def cholesky_factor(H: torch.Tensor, percdamp: float = 0.01, check: bool = True) -> torch.Tensor:
+    """In place H -> R with H + lambda I = R R^T (no inverse); returns H (now R)."""
+    n = H.shape[0]
+    ws = torch.empty(B.gptq_damp_cholesky_workspace_bytes(n), dtype=torch.uint8, device=H.device)
+    info = torch.zeros(1, dtype=torch.int32, device=H.device)
+    B.gptq_damp_cholesky(H, percdamp, ws, info)
+    if check:
+        B.gptq_check_info(info)
+    return H
+
+
 def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", block: int = 128, group: int = 0,
-             want_Wq: bool = False, pack: bool = False, ws: torch.Tensor | None = None) -> LayerResult:
+             want_Wq: bool = False, pack: bool = False, ws: torch.Tensor | None = None, from_factor: bool = False) -> LayerResult:
+    """Alg. 1 + optional packing.  from_factor: `U` is the factor R of cholesky_factor (per-row grids only)."""
     r, n = W.shape
     dev = W.device
     G = n // group if group else 1
@@ -58,7 +70,7 @@ def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", 
     if ws is None:
         ws = torch.empty(B.gptq_quantize_layer_workspace_bytes(r, n, block, group), dtype=torch.uint8, device=dev)
     gid = B.GPTQ_GRID_TERNARY if grid == "ternary" else B.GPTQ_GRID_MINMAX
-    B.gptq_quantize_layer(W, U, bits, gid, block, group, codes, scales, zeros, ws, Wq, half)
+    B.gptq_quantize_layer(W, U, bits, gid, block, group, codes, scales, zeros, ws, Wq, half, from_factor=from_factor)
     packed = None
     if pack:
         pbits = 2 if grid == "ternary" else bits
@@ -68,7 +80,7 @@ def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", 
 
 
 def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bool = False, timings: dict | None = None,
-                factors: dict | None = None):
+                factors: dict | None = None, form: str = "auto"):
     """The layers of one block, quantized in sequence (Section 4, Setup: a block's inputs are collected, its
     layers quantized, then the next block).  `groups` is a list of (X, layers): X [n x m] are the input
     activations shared by `layers`, a list of (name, W, settings) with settings an object carrying
@@ -76,7 +88,10 @@ def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bo
     one Hessian and one factor U.  Returns {name: LayerResult}; if `timings` is a dict it receives, per group,
     the milliseconds of the Hessian and of the factorisation, and per layer those of Alg. 1 plus packing
     (CUDA events on the current stream).  If `factors` is a dict it receives {group index: U}, the factor each
-    group's layers were quantized with (otherwise it is freed as soon as the group is done)."""
+    group's layers were quantized with (otherwise it is freed as soon as the group is done).
+    form: "inverse" factors every group into U = Cholesky((H + lambda I)^-1)^T; "factor" into R with
+    H + lambda I = R R^T and runs Alg. 1 from R (no triangular inverse; per-row grids only); "auto" takes the
+    factor form for the groups whose layers all have per-row grids."""
     out = {}
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
@@ -87,7 +102,8 @@ def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bo
         H = new_hessian(n, X.device)
         accumulate(H, X, chunk)
         e[1].record()
-        U = cholesky_inverse(H, layers[0][2].percdamp)
+        from_factor = form == "factor" or (form == "auto" and all(lay.group == 0 for _, _, lay in layers))
+        U = (cholesky_factor if from_factor else cholesky_inverse)(H, layers[0][2].percdamp)
         e[2].record()
         marks.append((f"group{gi}:hessian", e[0], e[1]))
         marks.append((f"group{gi}:damp_cholesky_inverse", e[1], e[2]))
@@ -99,7 +115,7 @@ def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bo
                 ws = torch.empty(need, dtype=torch.uint8, device=X.device)
             q0, q1 = ev(), ev()
             q0.record()
-            out[name] = quantize(W, U, b, lay.grid, lay.block, lay.group, want_Wq=want_Wq, pack=True, ws=ws)
+            out[name] = quantize(W, U, b, lay.grid, lay.block, lay.group, want_Wq=want_Wq, pack=True, ws=ws, from_factor=from_factor)
             q1.record()
             marks.append((f"{name}:quantize_pack", q0, q1))
         if factors is not None:

@@ -123,7 +123,7 @@ def test_full_size_sampled_parity(which):
     perr = float((z2 - v).norm() / v.norm())
     _say(f"  probe |U^T U Hd v - v| / |v| = {perr:.3e}")
     assert perr <= 1e-3
-    del blk, strict, y, z, z2
+    del blk, strict, z, z2
 
     # ---- step 3 + 4
     res = S.quantize(W, U, lay.bits, lay.grid, lay.block, lay.group, want_Wq=False, pack=True)
@@ -172,6 +172,39 @@ def test_full_size_sampled_parity(which):
     assert np.array_equal(res.packed[rows].cpu().numpy().view(np.uint32), O.pack_codes(codes_g, lay.bits))
     _say(f"full-size parity done in {time.time() - t0:.1f}s")
 
+    # ---- steps 2 and 3 without the inverse (per-row grids): R with H + lambda I = R R^T, then Alg. 1 driven by R
+    if lay.group == 0:
+        del res
+        R = S.cholesky_factor(Hd, lay.percdamp)             # in place: Hd is not needed any more
+        torch.cuda.synchronize()
+        z = torch.zeros_like(v)
+        for r0 in range(0, n, 2048):
+            z += R[r0:r0 + 2048].double().T @ v[r0:r0 + 2048]             # R^T v
+        w2 = torch.zeros_like(v)
+        for r0 in range(0, n, 2048):
+            w2[r0:r0 + 2048] = R[r0:r0 + 2048].double() @ z                # R (R^T v)
+        rerr = float((w2 - y).norm() / y.norm())
+        _say(f"  factor probe |R R^T v - (H + lambda I) v| / |(H + lambda I) v| = {rerr:.3e} at {time.time() - t0:.1f}s")
+        assert rerr <= 1e-5
+        assert float(R[n - 1, n - 1]) == pytest.approx((float(diag[-1]) + lam) ** 0.5, rel=1e-5)
+        res = S.quantize(W, R, lay.bits, lay.grid, lay.block, 0, pack=True, from_factor=True)
+        torch.cuda.synchronize()
+        codes_f = res.codes[rows].cpu().numpy().astype(np.int64)
+        zero_f = res.zeros[rows].cpu().numpy().astype(np.int64)
+        scale_f = res.scales[rows].cpu().numpy()
+        assert np.array_equal(zero_f, zero_g) and np.array_equal(scale_f, scale_g)
+        same = float((codes_f == codes_g).mean())
+        _say(f"  factor form vs U form on the sampled rows: {same:.6f} of the codes equal")
+        a = audit_alg1(Wr, Uh, lay.bits, lay.grid, lay.block, 0, codes_f, zero_f, scale_f, np.float64, tie_tol=2e-3,
+                       say=_say, tag=which + " factor form", free=own)
+        half_f = res.half_E2_rows[rows].cpu().numpy()
+        if same == 1.0:
+            assert np.all(np.abs(half_f - eg) <= 0.01 * eg)
+        else:
+            assert abs(half_f.sum() - eg.sum()) <= 0.01 * eg.sum()
+        assert np.array_equal(res.packed[rows].cpu().numpy().view(np.uint32), O.pack_codes(codes_f, lay.bits))
+        _say(f"  factor form done at {time.time() - t0:.1f}s")
+
 
 def test_config2_whole_against_the_oracles_own_hessian_and_factor():
     """The OPT-6.7B-shaped layer (W 4096 x 4096, X 4096 x 262144 fp16, 4-bit) end to end: the oracle computes its own
@@ -209,7 +242,8 @@ def test_config2_whole_against_the_oracles_own_hessian_and_factor():
 
 def test_full_size_decoder_block_3_and_4_bits():
     """The six linears of an OPT-175B-shaped decoder block through solver.solve_block (q, k, v share one Hessian and
-    one U) at 3 and at 4 bits, every layer checked on sampled rows: Alg. 1 against the oracle run with that group's
+    one U) at 3 bits with U = Cholesky of the inverse and at 4 bits in the inverse-free form (Alg. 1 driven by the factor R
+    of H + lambda I), every layer checked on sampled rows: Alg. 1 against the oracle run with that group's
     U (both decision precisions, near-tie audit), the kernel's (1/2) sum e^2 -- which equals the layer error
     (1/2) tr(D (H + lambda I) D^T) for the U it was given -- within 1 % of the oracle's, packing bit-exact.  H and
     U themselves are checked per layer shape in test_full_size_sampled_parity."""
@@ -238,19 +272,19 @@ def test_full_size_decoder_block_3_and_4_bits():
     torch.cuda.synchronize()
     _say(f"block inputs generated at {time.time() - t0:.1f}s")
     U_host = {}
-    for bits in (3, 4):
+    for bits, form in ((3, "inverse"), (4, "factor")):      # 3 bits through U = Cholesky of the inverse, 4 bits through the factor R
         factors, timings = {}, {}
-        res = S.solve_block(groups, bits=bits, chunk=32768, timings=timings, factors=factors)
+        res = S.solve_block(groups, bits=bits, chunk=32768, timings=timings, factors=factors, form=form)
         torch.cuda.synchronize()
         total = sum(timings.values())
-        _say(f"{bits}-bit block solved at {time.time() - t0:.1f}s: {total:.0f} ms on the GPU; " +
+        _say(f"{bits}-bit block ({form} form) solved at {time.time() - t0:.1f}s: {total:.0f} ms on the GPU; " +
              ", ".join(f"{k} {v:.1f}" for k, v in timings.items()))
         assert set(res) == {"q", "k", "v", "out", "fc1", "fc2"}
         for gi, (X, members) in enumerate(groups):
-            if gi not in U_host:
+            if form == "inverse":
                 U_host[gi] = factors[gi].cpu().numpy()
-            else:       # the factor does not depend on the bit width: the same bits again
-                assert torch.equal(factors[gi].cpu(), torch.from_numpy(U_host[gi]))
+            else:       # R, not U: the oracle keeps running on the U of the first pass (the same H, the same damping)
+                assert float(factors[gi][-1, -1]) == pytest.approx(1.0 / float(U_host[gi][-1, -1]), rel=1e-5)
             for name, Wl, lay in members:
                 r, n = lay.r, lay.n
                 rows = np.unique(np.array([0, 65, r // 2 + 3, r - 1]))

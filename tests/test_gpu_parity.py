@@ -300,7 +300,8 @@ def test_whole_path_matches_oracle(which):
     assert ex_g < rtn
 
 
-def test_block_driver_shares_hessians_and_matches_oracle():
+@pytest.mark.parametrize("form", ["inverse", "factor"])
+def test_block_driver_shares_hessians_and_matches_oracle(form):
     # a scaled twin of the decoder-block workload: q, k, v share one input (one Hessian, one U), out has its own
     c5 = configs.config5()
     n, m = 384, 6144
@@ -311,7 +312,7 @@ def test_block_driver_shares_hessians_and_matches_oracle():
     Xa, Xo = xa.tile(device="cuda"), xo.tile(device="cuda")
     groups = [(Xa, [(l.name, l.weights(device="cuda"), l) for l in lays[:3]]), (Xo, [(lays[3].name, lays[3].weights(device="cuda"), lays[3])])]
     timings = {}
-    res = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, timings=timings)
+    res = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, timings=timings, form=form)
     assert set(res) == {"q", "k", "v", "out"}
     assert {"group0:hessian", "group0:damp_cholesky_inverse", "group1:hessian", "q:quantize_pack", "out:quantize_pack"} <= set(timings)
     for X, ls in ((Xa, lays[:3]), (Xo, lays[3:])):
@@ -351,3 +352,77 @@ def test_trailing_update_matches_oracle(r, ncols, k):
     err = _rel_fro(Wd.double().cpu().numpy(), want)
     _say(f"  rel_fro={err:.3e}")
     assert err <= 1e-6              # float32 accumulation of k terms: about sqrt(k) * 6e-8
+
+
+# ------------------------------------------------------------------ steps 2 and 3 without the inverse
+
+def _upper_factor(Hd):
+    """R upper triangular with Hd = R R^T: the Cholesky factorisation taken from the last column backwards (float64)."""
+    return np.linalg.cholesky(Hd[::-1, ::-1])[::-1, ::-1].copy()
+
+
+@pytest.mark.parametrize("n,kind", [(256, "cfg1"), (1000, "lognormal"), (2048, "relu"), (1153, "relu"), (129, "lognormal"), (4, "lognormal")])
+def test_cholesky_factor_matches_oracle(n, kind):
+    _say(f"cholesky factor n={n} kind={kind}")
+    if kind == "cfg1":
+        X = configs.config1()[0].x.tile().double().numpy()
+    else:
+        base = configs.config2()[0] if kind == "lognormal" else configs.config3()[1]
+        X = _layer(base, n, 8, 4 * n).x.tile().double().numpy()
+    H32 = O.hessian(X).astype(np.float32)
+    Hd = O.damp(H32.astype(np.float64), 0.01)
+    want = _upper_factor(Hd)
+    assert np.allclose(want @ O.hinv_cholesky_upper(Hd), np.eye(n), atol=1e-8)      # R = U^-1, U the oracle's factor of the inverse
+    H = _padded(n, n, torch.float32, 4)
+    H.copy_(torch.from_numpy(np.triu(H32) + np.tril(np.full_like(H32, 7.0), -1)))    # only the upper triangle may be read
+    S.cholesky_factor(H, 0.01)
+    got = H.double().cpu().numpy()
+    err = _rel_fro(got, want)
+    resid = float(np.abs(got @ got.T - Hd).max() / np.abs(Hd).max())
+    _say(f"  rel_fro={err:.3e} max|R R^T - Hd|/max|Hd|={resid:.3e}")
+    assert np.array_equal(np.tril(got, -1), np.zeros_like(got))
+    assert err <= 2e-5 and resid <= 1e-5
+
+
+FACTOR_CASES = [c for c in QUANT_CASES if c[2] == 0] + [(2, "ternary", 0, torch.float16, 130, 640), (3, "minmax", 0, torch.float32, 64, 2304)]
+
+
+@pytest.mark.parametrize("bits,grid,group,dtype,r,n", FACTOR_CASES)
+def test_quantize_layer_from_factor_matches_oracle(bits, grid, group, dtype, r, n):
+    # Alg. 1 driven by R (H + lambda I = R R^T) must give what the oracle's Alg. 1 gives with U = Cholesky((H + lambda I)^-1)^T
+    _say(f"quantize from factor bits={bits} grid={grid} dtype={dtype} r={r} n={n}")
+    lay = _layer(configs.config3()[1], n, r, 8 * n, shift=bits)
+    W = lay.weights().to(dtype)
+    X = lay.x.tile().double().numpy()
+    Hd = O.damp(O.hessian(X))
+    U = O.hinv_cholesky_upper(Hd)
+    R32 = _upper_factor(Hd).astype(np.float32)
+    Wd = _padded(r, n, dtype, 8)
+    Wd.copy_(W)
+    Rd = _padded(n, n, torch.float32, 4)
+    Rd.copy_(torch.from_numpy(R32))
+    res = S.quantize(Wd, Rd, bits, grid, 128, 0, want_Wq=True, from_factor=True)
+    torch.cuda.synchronize()
+    # the oracle runs on its own float64 U; the kernel saw R rounded to float32
+    _compare_quant(res, W.double().numpy(), U, Hd, bits, grid, 0, n, "factor form", tie_tol=2e-3)
+    assert int(res.codes.max()) <= O.grid_maxq(bits, grid)
+    assert torch.equal(Wd.cpu(), W)
+    if n % 8 == 0:
+        with pytest.raises(g.GptqError) as ei:       # grouped grids need the current weights: the U form
+            S.quantize(Wd, Rd, bits, grid, 128, 8, from_factor=True)
+        assert ei.value.code == 4
+
+
+def test_whole_path_without_the_inverse_matches_oracle():
+    lay = _layer(configs.config2()[0], 1024, 512, 16384)
+    W, X = lay.weights(), lay.x.tile()
+    W64, X64 = W.double().numpy(), X.double().numpy()
+    Hdo = O.damp(O.hessian(X64), lay.percdamp)
+    Uo = O.hinv_cholesky_upper(Hdo)
+    H = S.new_hessian(lay.n)
+    S.accumulate(H, X.cuda(), chunk=4096)
+    R = S.cholesky_factor(H, lay.percdamp)
+    res = S.quantize(W.cuda(), R, lay.bits, lay.grid, lay.block, 0, want_Wq=True, pack=True, from_factor=True)
+    torch.cuda.synchronize()
+    _compare_quant(res, W64, Uo, Hdo, lay.bits, lay.grid, 0, lay.n, "whole path, factor form", tie_tol=2e-3)
+    assert np.array_equal(res.packed.cpu().numpy().view(np.uint32), O.pack_codes(res.codes.cpu().numpy(), lay.bits))
