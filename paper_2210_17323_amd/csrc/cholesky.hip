@@ -7,16 +7,20 @@
 // matrix Alg. 1 asks for, at half the flops of "Cholesky, invert, Cholesky again" and without ever
 // forming the explicit inverse.
 //
-// Two-level blocking (inner 128, outer 1024), everything in place in the upper triangle:
-//   factorisation, outer blocks last .. first, inner blocks last .. first:
-//     R_bb  = reverse-Cholesky of the 128x128 diagonal block (one workgroup, block in LDS),
-//             and its inverse R_bb^-1 kept in the workspace
-//     R[0:j0, j0:j1] = H[0:j0, j0:j1] * R_bb^-T             (the panel of R above the block, in place)
-//     H[0:j0, outer block columns left of j0] -= R[0:j0, j0:j1] R[.., j0:j1]^T   (rank-128, confined to the outer block)
-//     after the outer block: H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T   (rank-1024, carries the flops)
-//   triangular inverse, outer block columns first .. last:
-//     the 1024x1024 diagonal block is inverted in place with rank-128 steps, then
-//     U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1)           (K = o0, carries the flops)
+// Two-level blocking (inner blocks of 128 columns, outer blocks of 1024), result in place in the upper triangle.
+//
+// Factorisation, outer blocks o last .. first, inner blocks b last .. first:
+//     R_bb = reverse-Cholesky of the 128 x 128 diagonal block (one workgroup, block in LDS), R_bb^-1 kept
+//     R[0:j0, b] = H[0:j0, b] R_bb^-T                                  (the panel of R above the block, in place)
+//     H[0:j0, outer block's columns left of b] -= R[0:j0, b] R[.., b]^T   (rank 128, confined to the outer block)
+//   after the outer block: H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T   (rank 1024, carries the flops)
+//   one step behind, on a stream of its own (only when the inverse is wanted): the row blocks of U_oo = R_oo^-1,
+//     U[b, right] = -R_bb^-1 (R[b, right] U[right, right]), kept dense for the inverse.
+//
+// Triangular inverse (right-looking, outer block columns k first .. last), with the U_kk kept from the factorisation:
+//     T = -U_kk R[k, right of k] ;  U[above k, right of k] += U[above k, k] T ;  row block k <- T
+//     U[above k, k] <- U[above k, k] U_kk ;  diagonal block <- U_kk
+// Every long product has K = 1024 and an output of (rows above) x (columns to the right): many tiles at every k.
 #include "common.h"
 
 #include <mutex>
@@ -244,6 +248,20 @@ __global__ __launch_bounds__(256) void copy_block_kernel(float* dst, int64_t ld_
     }
 }
 
+// dst[rows x cols] = src[rows x cols]; both 16-byte aligned with leading dimensions and cols that are multiples of 4
+__global__ __launch_bounds__(256) void copy2d_kernel(float* dst, int64_t ld_dst, const float* src, int64_t ld_src, int64_t rows, int64_t cols4) {
+    const int64_t total = rows * cols4;
+    for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < total; q += (int64_t)gridDim.x * 256) {
+        const int64_t i = q / cols4, c = q - i * cols4;
+        reinterpret_cast<float4*>(dst + i * ld_dst)[c] = reinterpret_cast<const float4*>(src + i * ld_src)[c];
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float4* p, int64_t count4) {
+    for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < count4; q += (int64_t)gridDim.x * 256)
+        p[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
 __global__ __launch_bounds__(256) void zero_lower_kernel(float* H, int64_t ld, int64_t n) {
     const int64_t row = blockIdx.x;
     for (int64_t k = threadIdx.x; k < row; k += 256) H[row * ld + k] = 0.f;
@@ -256,15 +274,19 @@ using namespace gptq;
 namespace {
 constexpr int OB = 1024;     // outer block: rank-1024 updates keep the big GEMMs compute-bound and their tiles long
 
-struct CholWs { float* dinv; float* T; float* dense; size_t total; };
+struct CholWs { float* dinv; float* T; float* T2; int64_t ld2; float* Uoo; float* tmp; size_t total; };
 CholWs chol_ws_layout(void* ws, int64_t n) {
-    const size_t nblk = (size_t)ceil_div(std::max<int64_t>(n, 1), NB);
+    const size_t n1 = (size_t)std::max<int64_t>(n, 1);
+    const size_t nblk = (size_t)ceil_div((int64_t)n1, NB), nouter = (size_t)ceil_div((int64_t)n1, OB);
     size_t off = 0;
     CholWs l{};
     char* base = static_cast<char*>(ws);
-    l.dinv = reinterpret_cast<float*>(base + off);  off += round_up(nblk * NB * NB * sizeof(float), 256);
-    l.T = reinterpret_cast<float*>(base + off);     off += round_up((size_t)std::max<int64_t>(n, 1) * OB * sizeof(float), 256);
-    l.dense = reinterpret_cast<float*>(base + off); off += (size_t)OB * OB * sizeof(float);
+    l.ld2 = (int64_t)round_up(n1, 4);
+    l.dinv = reinterpret_cast<float*>(base + off);  off += round_up(nblk * NB * NB * sizeof(float), 256);       // R_bb^-1, dense
+    l.T = reinterpret_cast<float*>(base + off);     off += round_up(n1 * OB * sizeof(float), 256);              // a column panel [n x 1024]
+    l.T2 = reinterpret_cast<float*>(base + off);    off += round_up((size_t)OB * l.ld2 * sizeof(float), 256);   // a row panel [1024 x n]
+    l.Uoo = reinterpret_cast<float*>(base + off);   off += round_up(nouter * OB * OB * sizeof(float), 256);     // U_oo of every outer block, dense
+    l.tmp = reinterpret_cast<float*>(base + off);   off += round_up((size_t)NB * OB * sizeof(float), 256);      // one row block of a product
     l.total = off + 256;
     return l;
 }
@@ -290,7 +312,8 @@ static int chol_check_args(const float* H, int64_t ld, int64_t n, float percdamp
 }
 
 // The whole of step 2 on validated arguments.  `ws` holds chol_ws_layout(n).total bytes; nothing in it has to be
-// initialised (every region is written in this call before it is read).  lookahead = false keeps all work on `s`.
+// initialised (every region is written in this call before it is read).  lookahead = false keeps all work on `s`
+// (the host code below enqueues in an order that respects every dependence, so one stream is always valid).
 // want_inverse = false stops after the factorisation: H holds R (upper triangular, zeros below) with H + lambda I = R R^T.
 static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, int* info_dev, hipStream_t s, bool lookahead,
                     bool want_inverse = true) {
@@ -302,132 +325,145 @@ static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, i
     hipLaunchKernelGGL(damp_kernel, dim3(1), dim3(1024), 0, s, H, ld, n, percdamp, info_dev);
     GPTQ_LAUNCH_CHECK();
 
-    auto gemm_on = [&](hipStream_t st, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int64_t N, int64_t K,
-                       float alpha, bool nk, bool overwrite, bool upper, int64_t crow0, int64_t ccol0, bool atri) -> int {
+    // C (+)= alpha A op(B) on stream st
+    struct Opt { bool nk = false, overwrite = false, upper = false, atri = false, btri = false; int64_t crow0 = 0, ccol0 = 0; int cap = 0; };
+    auto gemm_on = [&](hipStream_t st, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                       int64_t M, int64_t N, int64_t K, float alpha, const Opt& o) -> int {
         GemmF32 g{};
         g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
-        g.b_is_nk = nk; g.overwrite = overwrite; g.upper_only = upper; g.crow0 = crow0; g.ccol0 = ccol0; g.a_upper_tri = atri;
+        g.b_is_nk = o.nk; g.overwrite = o.overwrite; g.upper_only = o.upper; g.crow0 = o.crow0; g.ccol0 = o.ccol0;
+        g.a_upper_tri = o.atri; g.b_upper_tri = o.btri; g.max_workgroups = o.cap;
         return launch_gemm_f32(g, st);
     };
-    auto gemm = [&](const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t M, int64_t N, int64_t K,
-                    float alpha, bool nk, bool overwrite, bool upper, int64_t crow0, int64_t ccol0, bool atri) -> int {
-        return gemm_on(s, A, lda, B, ldb, C, ldc, M, N, K, alpha, nk, overwrite, upper, crow0, ccol0, atri);
+    auto copy2d = [&](hipStream_t st, float* dst, int64_t ld_dst, const float* src, int64_t ld_src, int64_t rows, int64_t cols) -> int {
+        if (rows <= 0 || cols <= 0) return GPTQ_OK;
+        if (cols % 4 == 0 && ld_dst % 4 == 0 && ld_src % 4 == 0 && aligned(dst, 16) && aligned(src, 16)) {
+            const int64_t total4 = rows * (cols / 4);
+            hipLaunchKernelGGL(copy2d_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(total4, 256), 2048)), dim3(256), 0, st, dst, ld_dst, src, ld_src, rows, cols / 4);
+        } else {
+            hipLaunchKernelGGL(copy_block_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(rows * cols, 256), 2048)), dim3(256), 0, st, dst, ld_dst, src, ld_src, rows, (int)cols, 0);
+        }
+        GPTQ_LAUNCH_CHECK();
+        return GPTQ_OK;
     };
     const int64_t nouter = ceil_div(n, OB);
     TwoStreams ts;
     if (int rc = ts.open(s, lookahead)) return rc;
-    hipStream_t s2 = ts.side;
+    hipStream_t s2 = ts.side;       // long products: panels through U_oo and rank-1024 updates
+    hipStream_t s3 = ts.side2;      // (joined below; carries nothing here)
+    hipStream_t s4 = ts.side3;      // trails the factorisation's chain: the rows of U_oo
 
-    // ---- H + lambda I = R R^T, from the last column backwards.  Two levels: inside an outer block of
-    //      1024 columns the rank-128 updates touch only that block's columns; the rest of the matrix gets
-    //      one rank-1024 update per outer block.
-    hipEvent_t rest_done = nullptr;         // the helper stream's last trailing update, if one is pending
+    // ---- H + lambda I = R R^T, from the last column backwards.  Two levels: inside an outer block of 1024 columns the
+    //      rank-128 updates touch only that block's columns; the rest of the matrix gets one rank-1024 update per block.
+    hipEvent_t rest_done = nullptr;     // s2: the last rank-1024 update, if one is pending
     for (int64_t o = nouter - 1; o >= 0; --o) {
-        const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);
-        for (int64_t j0 = (ceil_div(o1 - o0, NB) - 1) * NB + o0; j0 >= o0; j0 -= NB) {
+        const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n), ow = o1 - o0;
+        float* Ublk = w.Uoo + o * (int64_t)OB * OB;      // U_oo = R_oo^-1 [ow x ow], leading dimension OB, for the inverse
+        if (want_inverse) {                              // zeros below the diagonal are relied on by the products that read it
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, s4, reinterpret_cast<float4*>(Ublk), (int64_t)OB * OB / 4);
+            GPTQ_LAUNCH_CHECK();
+        }
+        for (int64_t j0 = (ceil_div(ow, NB) - 1) * NB + o0; j0 >= o0; j0 -= NB) {
             const int nbk = (int)std::min<int64_t>(NB, n - j0);
+            const int64_t j1 = j0 + nbk;
             float* dinv_b = dinv + (j0 / NB) * NB * NB;
             hipLaunchKernelGGL(diag_block_kernel, dim3(1), dim3(256), diag_lds, s, H + j0 * ld + j0, ld, nbk, dinv_b, info_dev, (int)j0);
             GPTQ_LAUNCH_CHECK();
-            if (j0 == 0) break;
-            // R[0:j0, j0:j1] = H[0:j0, j0:j1] * R_bb^-T, the panel of R above the block.  In place: there is a
-            // single tile column, and a workgroup reads all of its own rows before it writes them.
-            int rc = gemm(H + j0, ld, dinv_b, NB, H + j0, ld, j0, nbk, nbk, 1.f, true, true, false, 0, 0, false);
-            if (rc) return rc;
-            // H[0:j0, o0:j0] -= R[0:j0, j0:j1] * R[o0:j0, j0:j1]^T  (columns of this outer block only; tiles below the
-            // diagonal skipped).  Right-looking: many short tiles, which keeps this serial chain short; a left-looking
-            // product per inner block (one tile column, K up to 896) measured slower on mid-size matrices.
+            if (j0 > 0) {
+                // R[0:j0, b] = H[0:j0, b] R_bb^-T, the panel of R above the block.  In place: there is a single tile column,
+                // and a workgroup reads all of its own rows before it writes them.
+                Opt po; po.nk = true; po.overwrite = true;
+                if (int rc = gemm_on(s, H + j0, ld, dinv_b, NB, H + j0, ld, j0, nbk, nbk, 1.f, po)) return rc;
+            }
+            if (want_inverse) {
+                // One step behind, on its own stream: the row block of U_oo,
+                // U[b, b] = R_bb^-1,  U[b, right] = -R_bb^-1 (R[b, right] U[right, right])  (U[right, right] upper triangular)
+                hipEvent_t step = nullptr;
+                if (int rc = ts.mark(s, &step)) return rc;
+                if (int rc = ts.wait(s4, step)) return rc;
+                const int64_t d = j0 - o0;               // position of the row block inside U_oo
+                hipLaunchKernelGGL(copy_block_kernel, dim3(64), dim3(256), 0, s4, Ublk + d * OB + d, (int64_t)OB, (const float*)dinv_b, (int64_t)NB, (int64_t)nbk, nbk, 1);
+                GPTQ_LAUNCH_CHECK();
+                if (j1 < o1) {
+                    Opt a; a.overwrite = true; a.btri = true;
+                    if (int rc = gemm_on(s4, H + j0 * ld + j1, ld, Ublk + (d + nbk) * OB + (d + nbk), OB, w.tmp, OB, nbk, o1 - j1, o1 - j1, 1.f, a)) return rc;
+                    Opt c; c.overwrite = true;
+                    if (int rc = gemm_on(s4, dinv_b, NB, w.tmp, OB, Ublk + d * OB + (d + nbk), OB, nbk, o1 - j1, nbk, -1.f, c)) return rc;
+                }
+            }
             if (j0 > o0) {
-                rc = gemm(H + j0, ld, H + o0 * ld + j0, ld, H + o0, ld, j0, j0 - o0, nbk, -1.f, true, false, true, 0, o0, false);
-                if (rc) return rc;
+                // H[0:j0, o0:j0] -= R[0:j0, b] R[o0:j0, b]^T (columns of this outer block only; tiles below the diagonal
+                // skipped).  Right-looking: many short tiles, which keeps this serial chain short.
+                Opt uo; uo.nk = true; uo.upper = true; uo.ccol0 = o0;
+                if (int rc = gemm_on(s, H + j0, ld, H + o0 * ld + j0, ld, H + o0, ld, j0, j0 - o0, nbk, -1.f, uo)) return rc;
             }
         }
-        // H[0:o0, 0:o0] -= R[0:o0, o0:o1] * R[0:o0, o0:o1]^T  (rank-1024, upper tiles), with look-ahead:
-        // the columns [p0, o0) of the next outer block are updated first, on the caller's stream, which then
-        // goes on to factor that block (short, serial kernels); the rest, H[0:p0, 0:p0], is updated on the
-        // helper stream meanwhile.  The two parts and the next block's factorisation write disjoint regions;
-        // the next block's own column update waits for the helper's, which wrote the same region.
+        // H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T (rank 1024, upper tiles), with look-ahead: the columns [p0, o0) of the next
+        // outer block are updated first, on the caller's stream, which then goes on to factor that block (short, serial
+        // kernels); the rest, H[0:p0, 0:p0], is updated on a helper stream meanwhile.  The two parts and the next block's
+        // factorisation write disjoint regions; the next block's own column update waits for the helper's, which wrote
+        // the same region.
         if (o0 > 0) {
             const int64_t p0 = o0 - OB;                  // outer blocks start at multiples of OB
             hipEvent_t factored = nullptr;
             if (int rc = ts.mark(s, &factored)) return rc;
             if (int rc = ts.wait(s, rest_done)) return rc;
-            int rc = gemm(H + o0, ld, H + p0 * ld + o0, ld, H + p0, ld, o0, o0 - p0, o1 - o0, -1.f, true, false, true, 0, p0, false);
-            if (rc) return rc;
+            Opt co; co.nk = true; co.upper = true; co.ccol0 = p0;
+            if (int rc = gemm_on(s, H + o0, ld, H + p0 * ld + o0, ld, H + p0, ld, o0, o0 - p0, ow, -1.f, co)) return rc;
+            rest_done = nullptr;
             if (p0 > 0) {
-                if ((rc = ts.wait(s2, factored))) return rc;
-                rc = gemm_on(s2, H + o0, ld, H + o0, ld, H, ld, p0, p0, o1 - o0, -1.f, true, false, true, 0, 0, false);
-                if (rc) return rc;
-                if ((rc = ts.mark(s2, &rest_done))) return rc;
-            } else {
-                rest_done = nullptr;
+                if (int rc = ts.wait(s2, factored)) return rc;
+                Opt ro; ro.nk = true; ro.upper = true;
+                if (int rc = gemm_on(s2, H + o0, ld, H + o0, ld, H, ld, p0, p0, ow, -1.f, ro)) return rc;
+                if (int rc = ts.mark(s2, &rest_done)) return rc;
             }
         }
     }
+    // everything back on the caller's stream
+    for (hipStream_t st : {s2, s3, s4}) {
+        hipEvent_t done = nullptr;
+        if (int rc = ts.mark(st, &done)) return rc;
+        if (int rc = ts.wait(s, done)) return rc;
+    }
 
-    // The triangular GEMMs below skip the K range left of a tile's first row and rely on zeros below the
-    // diagonal inside the tile's own rows, so clear the strictly lower triangle first (it holds the input's
-    // lower half and the below-diagonal parts of straddling update tiles); nothing writes there afterwards.
+    // Nothing below the diagonal is part of the result (it holds the input's lower half and the below-diagonal parts of
+    // straddling update tiles), and the triangular products of the inverse rely on zeros there.
     hipLaunchKernelGGL(zero_lower_kernel, dim3((unsigned)n), dim3(256), 0, s, H, ld, n);
     GPTQ_LAUNCH_CHECK();
     if (!want_inverse) return GPTQ_OK;
-    {
-        hipEvent_t cleared = nullptr;
-        if (int rc = ts.mark(s, &cleared)) return rc;
-        if (int rc = ts.wait(s2, cleared)) return rc;
-    }
 
-    // ---- U = R^-1 in place, one outer block column at a time (left to right):
-    //      invert the 1024 x 1024 diagonal block in place with rank-128 steps, then
-    //      U[above, o] = -U[above, above] * (R[above, o] * R_oo^-1), a long-K GEMM against the finished part.
-    //      The in-block inversions touch nothing but their own diagonal block, so they all run ahead on the
-    //      helper stream while the caller's stream carries the long GEMMs, each waiting for its block's event.
-    for (int64_t o = 0; o < nouter; ++o) {
-        const int64_t o0 = o * OB, o1 = std::min<int64_t>(o0 + OB, n);
-        for (int64_t j0 = o0; j0 < o1; j0 += NB) {
-            const int nbk = (int)std::min<int64_t>(NB, n - j0);
-            const int64_t j1 = j0 + nbk;
-            const float* dinv_b = dinv + (j0 / NB) * NB * NB;
-            if (j1 < o1) {
-                // R[b, right] = -R_bb^-1 * R[b, right].  In place: a workgroup reads its own 128 columns of all
-                // (<= 128) rows through LDS before its epilogue writes them, and there is a single tile row.
-                int rc = gemm_on(s2, dinv_b, NB, H + j0 * ld + j1, ld, H + j0 * ld + j1, ld, nbk, o1 - j1, nbk, -1.f, false, true, false, 0, 0, false);
-                if (rc) return rc;
-                if (j0 > o0) {
-                    rc = gemm_on(s2, H + o0 * ld + j0, ld, H + j0 * ld + j1, ld, H + o0 * ld + j1, ld, j0 - o0, o1 - j1, nbk, 1.f, false, false, false, 0, 0, false);
-                    if (rc) return rc;
-                }
+    // ---- U = R^-1 in place, right-looking over the outer block columns --------------------------------------------
+    hipEvent_t panel_done = nullptr;     // s2: the last column panel, which reuses T
+    for (int64_t k = 0; k < nouter; ++k) {
+        const int64_t k0 = k * OB, k1 = std::min<int64_t>(k0 + OB, n), kw = k1 - k0;
+        const float* Ukk = w.Uoo + k * (int64_t)OB * OB;
+        hipEvent_t read_done = nullptr;  // s: the column block above k has been read by this step's update
+        if (k1 < n) {
+            // T2 = -U_kk R[k, k1:n]   (U_kk upper triangular: a tile's K loop starts at its first row)
+            Opt a; a.overwrite = true; a.atri = true;
+            if (int rc = gemm_on(s, Ukk, OB, H + k0 * ld + k1, ld, w.T2, w.ld2, kw, n - k1, kw, -1.f, a)) return rc;
+            if (k0 > 0) {
+                // U[0:k0, k1:n] += U[0:k0, k] T2   (U[0:k0, k] not yet multiplied by U_kk)
+                Opt u;
+                if (int rc = gemm_on(s, H + k0, ld, w.T2, w.ld2, H + k1, ld, k0, n - k1, kw, 1.f, u)) return rc;
             }
-            if (j0 > o0) {
-                // R[above-in-block, b] = R[above-in-block, b] * R_bb^-1.  In place: a single tile column, each
-                // workgroup reads all of its own rows before writing them.
-                const int rc = gemm_on(s2, H + o0 * ld + j0, ld, dinv_b, NB, H + o0 * ld + j0, ld, j0 - o0, nbk, nbk, 1.f, false, true, false, 0, 0, false);
-                if (rc) return rc;
-            }
-            hipLaunchKernelGGL(copy_block_kernel, dim3(64), dim3(256), 0, s2, H + j0 * ld + j0, ld, dinv_b, (int64_t)NB, (int64_t)nbk, nbk, 1);
-            GPTQ_LAUNCH_CHECK();
+            if (int rc = ts.mark(s, &read_done)) return rc;
+            if (int rc = copy2d(s, H + k0 * ld + k1, ld, w.T2, w.ld2, kw, n - k1)) return rc;
+        } else {
+            if (int rc = ts.mark(s, &read_done)) return rc;
         }
-        {
-            hipEvent_t inverted = nullptr;
-            if (int rc = ts.mark(s2, &inverted)) return rc;
-            if (int rc = ts.wait(s, inverted)) return rc;
+        // On the other stream: U[0:k0, k] <- U[0:k0, k] U_kk through T, and the diagonal block.  Nothing later reads them.
+        if (int rc = ts.wait(s2, read_done)) return rc;
+        if (k0 > 0) {
+            Opt c; c.overwrite = true; c.btri = true;
+            if (int rc = gemm_on(s2, H + k0, ld, Ukk, OB, w.T, OB, k0, kw, kw, 1.f, c)) return rc;
+            if (int rc = copy2d(s2, H + k0, ld, w.T, OB, k0, kw)) return rc;
         }
-        if (o0 > 0) {
-            const int ow = (int)(o1 - o0);
-            // dense copy of the inverted diagonal block with an explicit zero lower triangle
-            hipLaunchKernelGGL(copy_block_kernel, dim3(256), dim3(256), 0, s, w.dense, (int64_t)OB, (const float*)(H + o0 * ld + o0), ld, (int64_t)ow, ow, 1);
-            GPTQ_LAUNCH_CHECK();
-            // T = R[0:o0, o] * U_oo; U_oo is upper triangular (zeros below the diagonal in the dense copy), so a tile's
-            // K loop ends at its last column
-            GemmF32 gt{};
-            gt.A = H + o0; gt.lda = ld; gt.B = w.dense; gt.ldb = OB; gt.C = w.T; gt.ldc = OB; gt.M = o0; gt.N = ow; gt.K = ow;
-            gt.alpha = 1.f; gt.b_is_nk = false; gt.overwrite = true; gt.b_upper_tri = true;
-            int rc = launch_gemm_f32(gt, s);
-            if (rc) return rc;
-            rc = gemm(H, ld, w.T, OB, H + o0, ld, o0, ow, o0, -1.f, false, true, false, 0, 0, true);
-            if (rc) return rc;
-        }
+        hipLaunchKernelGGL(copy_block_kernel, dim3(256), dim3(256), 0, s2, H + k0 * ld + k0, ld, Ukk, (int64_t)OB, kw, (int)kw, 1);
+        GPTQ_LAUNCH_CHECK();
+        if (int rc = ts.mark(s2, &panel_done)) return rc;
     }
+    if (int rc = ts.wait(s, panel_done)) return rc;
     return GPTQ_OK;
 }
 
@@ -457,9 +493,9 @@ extern "C" int gptq_damp_cholesky(float* H, int64_t ld, int64_t n, float percdam
 // pointer -- never the array's name, which in host code is a stand-in and no device address -- is handed to kernels.
 namespace {
 constexpr int64_t NOALLOC_MAX_N = GPTQ_NOALLOC_MAX_N;
-constexpr size_t NOALLOC_BYTES = (size_t)(NOALLOC_MAX_N / NB) * NB * NB * sizeof(float)      // inverses of the diagonal blocks
-                                 + (size_t)NOALLOC_MAX_N * OB * sizeof(float)                // one n x 1024 product
-                                 + (size_t)OB * OB * sizeof(float) + 512;                    // one dense 1024 x 1024 block
+constexpr size_t NOALLOC_BYTES = (size_t)(NOALLOC_MAX_N / NB) * NB * NB * sizeof(float)      // inverses of the 128 x 128 diagonal blocks
+                                 + 3 * (size_t)NOALLOC_MAX_N * OB * sizeof(float)            // a column panel, a row panel, the U_oo blocks
+                                 + (size_t)NB * OB * sizeof(float) + 2048;                   // one row block of a product
 static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
 
 constexpr int MAXDEV = 64;

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <cstdarg>
+#include <initializer_list>
 #include <cstdint>
 #include <cstdio>
 
@@ -41,26 +42,36 @@ inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 // ends.  Every use forks from and joins back into the caller's stream with events, so after an entry
 // point returns all of its work is ordered on the caller's stream alone.
 struct Lookahead {
-    hipStream_t stream = nullptr;
-    hipEvent_t ev[8] = {};
+    hipStream_t stream = nullptr;       // long trailing updates
+    hipStream_t stream2 = nullptr;      // the short kernels that trail the factorisation's serial chain: the next block's strip
+    hipStream_t stream3 = nullptr;      // ... and the inverse of the diagonal block
+    hipEvent_t ev[32] = {};
     unsigned next = 0;
-    hipEvent_t event() { return ev[next++ & 7]; }
+    hipEvent_t event() { return ev[next++ & 31]; }
 };
 int lookahead_get(Lookahead** out);     // for the current device; GPTQ_OK or an error code
 
-// The two streams of one entry point.  open(s, true) forks onto the library's helper stream; open(s, false) keeps
-// everything on the caller's stream (side == main, no events: the same kernels in an order that respects every
-// dependence, without overlap) -- for callers that must not create streams or events.  The destructor joins the
-// helper stream back into the caller's on EVERY return path, so also after a launch failed half way through a call
-// nothing is left running unordered beside the caller's stream.
+// The streams of one entry point.  open(s, true) forks onto the library's helper streams; open(s, false) keeps
+// everything on the caller's stream (every side stream == main, no events: the same kernels in an order that respects
+// every dependence, without overlap) -- for callers that must not create streams or events.  The destructor joins
+// the helper streams back into the caller's on EVERY return path, so also after a launch failed half way through a
+// call nothing is left running unordered beside the caller's stream.  An event of the ring may be recorded again
+// while an earlier wait on it is still pending: a wait refers to the record that was current when it was enqueued.
 struct TwoStreams {
-    hipStream_t main = nullptr, side = nullptr;
+    hipStream_t main = nullptr, side = nullptr, side2 = nullptr, side3 = nullptr;
     Lookahead* la = nullptr;
     int open(hipStream_t s, bool lookahead) {
-        main = side = s;
+        main = side = side2 = side3 = s;
         if (!lookahead) return GPTQ_OK;
         if (int rc = lookahead_get(&la)) return rc;
         side = la->stream;
+        side2 = la->stream2;
+        side3 = la->stream3;
+        // fork: nothing on a helper stream may start before the work already on the caller's stream (a helper's first
+        // kernel may touch memory -- a workspace, say -- that earlier work of the caller still writes)
+        hipEvent_t fork = la->event();
+        GPTQ_HIP_CHECK(hipEventRecord(fork, main));
+        for (hipStream_t st : {side, side2, side3}) GPTQ_HIP_CHECK(hipStreamWaitEvent(st, fork, 0));
         return GPTQ_OK;
     }
     // *ev = a point on `on` that wait() can order another stream behind; stays null in single-stream mode
@@ -79,8 +90,10 @@ struct TwoStreams {
     }
     ~TwoStreams() {
         if (!la) return;
-        hipEvent_t e = la->event();
-        if (hipEventRecord(e, side) == hipSuccess) (void)hipStreamWaitEvent(main, e, 0);
+        for (hipStream_t st : {side, side2, side3}) {
+            hipEvent_t e = la->event();
+            if (hipEventRecord(e, st) == hipSuccess) (void)hipStreamWaitEvent(main, e, 0);
+        }
     }
 };
 
@@ -109,6 +122,9 @@ struct GemmF32 {
     int64_t crow0, ccol0;
     bool a_upper_tri;   // A is upper triangular with zeros below its diagonal blocks: skip k < first row of the tile
     bool b_upper_tri;   // B [K x N] is upper triangular with zeros below the diagonal: skip k > last column of the tile
+    int max_workgroups; // > 0: a launch of large tiles uses at most this many workgroups (each walks several tiles), which
+                        //      leaves the other CUs to kernels of other streams; workgroup w runs on XCD w % 8, so a
+                        //      multiple of 8 below the CU count frees the same number of CUs on every XCD
 };
 int launch_gemm_f32(const GemmF32& g, hipStream_t s);
 

@@ -28,6 +28,7 @@ struct GemmArgs {
     int b_upper_tri;
     int tiles_m, tiles_n;
     int64_t per_xcd, total;
+    int64_t slots;      // tile slots of the launch: per_xcd * 8 (the large-tile kernels may run them on fewer workgroups)
     int tri_ratio;      // > 0: exactly the upper tiles of a square C are enumerated; value = tile rows / tile columns
 };
 
@@ -291,8 +292,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ __attribute__((aligned(16))) unsigned char st2[LSTAGE_];
     __shared__ __attribute__((aligned(16))) unsigned char st3[LSTAGE_];
 
+    // The launch may hold fewer workgroups than tiles (a caller that wants CUs left free for other streams): a
+    // workgroup then walks the tile slots w, w + gridDim.x, ...; gridDim.x is a multiple of the XCD count, so all of
+    // them are slots of its own XCD's share.
+    for (int64_t wslot = blockIdx.x; wslot < g.slots; wslot += gridDim.x) {
     int64_t m0, n0;
-    if (!TileOrder::origin(g, blockIdx.x, LM, TN_, m0, n0)) return;
+    if (!TileOrder::origin(g, wslot, LM, TN_, m0, n0)) continue;
 
     // 8 wavefronts (two per SIMD, so one can issue MFMAs while the other waits on LDS or the barrier);
     // wavefront (wm, wn) owns rows wm*32*SM.., columns wn*64.. of the tile: SM x 2 MFMA tiles.
@@ -427,6 +432,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 cbase[(int64_t)(8 * (i >> 2) + (i & 3)) * g.ldc] = g.overwrite ? v : (cv[i] + v);
             }
         }
+    __syncthreads();        // the next tile's first copies overwrite the stages this tile's wavefronts still read
+    }
 }
 
 int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
@@ -456,7 +463,10 @@ int launch_gemm_f32(const GemmF32& p, hipStream_t s) {
         g.total = TileOrder::triangle_total(g.tiles_m, g.tiles_n, g.tri_ratio);
     }
     g.per_xcd = ceil_div(g.total, NXCD);
-    dim3 grid((unsigned)(g.per_xcd * NXCD));
+    g.slots = g.per_xcd * NXCD;
+    int64_t wgs = g.slots;
+    if (large && p.max_workgroups >= NXCD && wgs > p.max_workgroups) wgs = p.max_workgroups / NXCD * NXCD;
+    dim3 grid((unsigned)wgs);
     if (large) {
         if (wide) {
             if (p.b_is_nk) hipLaunchKernelGGL((gemm_f32_dma_kernel<true, true>), grid, dim3(512), 0, s, g);

@@ -27,17 +27,23 @@ int lookahead_get(Lookahead** out) {
     if (dev < 0 || dev >= MAXDEV) return fail(GPTQ_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
     Lookahead& l = table[dev];
     if (!l.stream) {
-        hipStream_t st = nullptr;
+        hipStream_t st = nullptr, st2 = nullptr, st3 = nullptr;
         GPTQ_HIP_CHECK(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+        hipError_t err = hipStreamCreateWithFlags(&st2, hipStreamNonBlocking);
+        if (err == hipSuccess) err = hipStreamCreateWithFlags(&st3, hipStreamNonBlocking);
         for (hipEvent_t& e : l.ev) {
-            const hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
-            if (err != hipSuccess) {            // give back what was created: the next call starts from nothing
-                for (hipEvent_t& d : l.ev) { if (d) (void)hipEventDestroy(d); d = nullptr; }
-                (void)hipStreamDestroy(st);
-                return fail(GPTQ_ERR_HIP, "hipEventCreateWithFlags failed: %s", hipGetErrorString(err));
-            }
+            if (err == hipSuccess) err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+        }
+        if (err != hipSuccess) {                // give back what was created: the next call starts from nothing
+            for (hipEvent_t& d : l.ev) { if (d) (void)hipEventDestroy(d); d = nullptr; }
+            if (st3) (void)hipStreamDestroy(st3);
+            if (st2) (void)hipStreamDestroy(st2);
+            (void)hipStreamDestroy(st);
+            return fail(GPTQ_ERR_HIP, "creating the helper streams and events failed: %s", hipGetErrorString(err));
         }
         l.stream = st;
+        l.stream2 = st2;
+        l.stream3 = st3;
     }
     *out = &l;
     return GPTQ_OK;
