@@ -17,6 +17,7 @@ struct PackedArgs {
     int64_t r, n, words_per_row;
     const float* scales; const int32_t* zeros;
     int64_t group, ngroups;      // group == 0: one grid per row (ngroups == 1)
+    int gshift;                  // log2(group) if the group size is a power of two, else -1 (then columns are divided)
     int64_t rows_per_wg;         // matvec: rows a workgroup walks, a multiple of its row chunk
 };
 
@@ -28,7 +29,155 @@ __device__ __forceinline__ uint32_t code_at(const uint32_t (&w)[BITS], int i) {
     return v & ((1u << BITS) - 1u);
 }
 
-// ---- full-matrix decompression: one thread per 8 codes = 8 consecutive outputs (one 16-byte store of halves) ---
+// ---- codes to halves without a conversion (used by both consumers) -------------------------------------------------
+// With the exponent bits of 2^b or-ed in, a code sitting at mantissa bits [10-b, 10) of a half IS the float16 number
+// 2^b + code.  Two codes whose bit positions differ by 16 (mod 32) sit at the same place of the two halves of a
+// 32-bit word, so one shift puts both at [10-b, 10) / [26-b, 26) and one and-or masks them and sets both exponents:
+//   b = 4: codes k and k+4 of a word;  b = 2: codes k and k+8 of a word;
+//   b = 3: codes k and k+16 of the 96-bit group are 48 bits apart -- low half of one word, high half of another,
+//          joined by one byte permute that serves four or five pairs; the two pairs whose codes straddle a
+//          16-bit boundary (5, 21 and 10, 26) are cut out one code at a time.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+struct PairSpec { int lo_word, hi_word, rel, k_lo, k_hi; };      // lo_word < 0: cut the two codes out one at a time
+template <int BITS> struct PairTable;
+template <> struct PairTable<4> {
+    static constexpr PairSpec at(int i) { return {i / 4, i / 4, 4 * (i % 4), 8 * (i / 4) + i % 4, 8 * (i / 4) + i % 4 + 4}; }
+};
+template <> struct PairTable<2> {
+    static constexpr PairSpec at(int i) { return {i / 8, i / 8, 2 * (i % 8), 16 * (i / 8) + i % 8, 16 * (i / 8) + i % 8 + 8}; }
+};
+template <> struct PairTable<3> {
+    static constexpr PairSpec at(int i) {
+        if (i < 5) return {0, 1, 3 * i, i, i + 16};                                   // k = 0..4
+        if (i < 9) return {2, 0, 3 * (i + 1) - 16, (i + 1) + 16, i + 1};              // k = 6..9
+        if (i < 14) return {1, 2, 3 * (i + 2) - 32, i + 2, (i + 2) + 16};             // k = 11..15
+        return i == 14 ? PairSpec{-1, -1, 0, 5, 21} : PairSpec{-1, -1, 0, 10, 26};
+    }
+};
+
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
+    uint32_t v;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(v) : "v"(a), "s"(mask), "v"(c));   // written out: the compiler spends two on it
+    return v;
+}
+
+// 32 bits of the stream of words w[0..BITS] (w[BITS] = 0) starting at bit `from` (may be negative: shifted in zeros)
+template <int BITS>
+__device__ __forceinline__ uint32_t stream_bits(const uint32_t (&w)[BITS + 1], int from) {
+    if (from < 0) return w[0] << (-from);
+    const int wi = from >> 5, sh = from & 31;
+    return sh ? __builtin_amdgcn_alignbit(w[wi + 1], w[wi], sh) : w[wi];
+}
+
+
+// The 32 codes of b words as 16 registers of two halves (2^b + code each); register i holds codes PairTable::at(i).k_lo
+// (low half) and .k_hi (high half).  w[BITS] must be 0.
+template <int BITS>
+__device__ __forceinline__ void codes_as_half_pairs(const uint32_t (&w)[BITS + 1], uint32_t (&pr)[16]) {
+    constexpr int WANT = 10 - BITS;
+    constexpr uint32_t M = (1u << BITS) - 1u;
+    constexpr uint32_t MASK_LO = M << WANT, MASK_HI = M << (16 + WANT), MASK = MASK_LO | MASK_HI;
+    const uint32_t magic = 0x3C003C00u + (uint32_t)BITS * 0x04000400u;       // (2^b, 2^b) as two halves
+    uint32_t joined[3] = {0u, 0u, 0u};
+    if constexpr (BITS == 3) {
+        joined[0] = __builtin_amdgcn_perm(w[1], w[0], 0x07060100u);      // low half of w0, high half of w1
+        joined[1] = __builtin_amdgcn_perm(w[0], w[2], 0x07060100u);      // low half of w2, high half of w0
+        joined[2] = __builtin_amdgcn_perm(w[2], w[1], 0x07060100u);      // low half of w1, high half of w2
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const PairSpec sp = PairTable<BITS>::at(i);
+        if (sp.lo_word < 0) {
+            const uint32_t ta = stream_bits<BITS>(w, BITS * sp.k_lo - WANT);
+            const uint32_t tb = stream_bits<BITS>(w, BITS * sp.k_hi - (16 + WANT));
+            pr[i] = and_or(tb, MASK_HI, and_or(ta, MASK_LO, magic));
+        } else {
+            uint32_t m;
+            if (sp.lo_word == sp.hi_word) m = w[sp.lo_word];
+            else m = joined[sp.lo_word == 0 ? 0 : (sp.lo_word == 2 ? 1 : 2)];
+            const uint32_t t = sp.rel >= WANT ? (m >> (sp.rel - WANT)) : (m << (WANT - sp.rel));
+            pr[i] = and_or(t, MASK, magic);
+        }
+    }
+}
+
+// ---- full-matrix decompression, the usual case (n a multiple of 8, one grid per 8 columns, 16-byte aligned rows) ----
+// A workgroup walks along a row (then along every gridDim.x-th row after it), one thread per 8 codes per step:
+// neighbouring lanes write neighbouring 16 bytes, so a store instruction of a wavefront covers 1 KB without a gap and a
+// workgroup streams a whole row; lanes re-read words their neighbours also read (served by the vector cache).
+// The 8 codes are 8 b consecutive bits of at most two words.  Or-ed into 0x6400 a code IS the half 1024 + code, so a
+// pair of codes costs a shift and two and-ors, one packed subtraction of 1024 + zero leaves the exact integers
+// code - zero, and each output is the float32 product with the scale, rounded to the output type.
+template <int BITS, typename OT>
+__global__ __launch_bounds__(256) void dequantize8_kernel(PackedArgs a, OT* __restrict__ out, int64_t ldo, int64_t octets_per_row) {
+    constexpr uint32_t M = (1u << BITS) - 1u;
+    constexpr int UN = 1;                       // octets per thread per step (256 apart; more in flight measured slower)
+    for (int64_t row = blockIdx.x; row < a.r; row += gridDim.x) {
+        const uint32_t* __restrict__ wrow = a.words + row * a.ldp;
+        OT* orow = out + row * ldo;
+        const float* srow = a.scales + row * a.ngroups;
+        const int32_t* zrow = a.zeros + row * a.ngroups;
+        for (int64_t oc0 = threadIdx.x; oc0 < octets_per_row; oc0 += 256 * UN) {
+            uint32_t lo[UN], hi[UN];
+            float sc[UN], zf[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int64_t oc = oc0 + 256 * u;
+                lo[u] = hi[u] = 0u; sc[u] = 0.f; zf[u] = 0.f;
+                if (oc < octets_per_row) {
+                    const int64_t bit0 = oc * 8 * BITS, wi = bit0 >> 5;
+                    const int off = (int)(bit0 & 31);
+                    lo[u] = wrow[wi];
+                    if ((off + 8 * BITS > 32) && (wi + 1 < a.words_per_row)) hi[u] = wrow[wi + 1];
+                    // column / group size without the 64-bit division (n < 2^31 columns are checked on the host)
+                    const uint32_t col = (uint32_t)(oc * 8);
+                    const uint32_t gcol = a.group == 0 ? 0u : (a.gshift >= 0 ? col >> a.gshift : col / (uint32_t)a.group);
+                    sc[u] = srow[gcol];
+                    zf[u] = (float)zrow[gcol];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int64_t oc = oc0 + 256 * u;
+                if (oc >= octets_per_row) break;
+                const int off = (int)((oc * 8 * BITS) & 31);
+                const uint32_t bits8 = __builtin_amdgcn_alignbit(hi[u], lo[u], off);       // code i at bits [i*b, (i+1)*b)
+                const _Float16 zh = (_Float16)(1024.f + zf[u]);                              // exact
+                half2v z2; z2.x = zh; z2.y = zh;
+                _Float16 d[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t t = bits8 >> (2 * i * BITS);                              // codes 2i and 2i+1 at the bottom
+                    const uint32_t pair = and_or(t << (16 - BITS), M << 16, and_or(t, M, 0x64006400u));
+                    const half2v v = __builtin_bit_cast(half2v, pair) - z2;
+                    d[2 * i] = v.x; d[2 * i + 1] = v.y;
+                }
+                OT* dst = orow + oc * 8;
+                if constexpr (sizeof(OT) == 2) {
+                    union { uint4 u4; _Float16 h[8]; } pk;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        float prod = sc[u] * (float)d[i];       // the float32 product, rounded, and only then the half: the
+                        asm volatile("" : "+v"(prod));          // two must not be fused into one mixed-precision instruction
+                        pk.h[i] = (_Float16)prod;
+                    }
+                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                    u32x4 v4; v4.x = pk.u4.x; v4.y = pk.u4.y; v4.z = pk.u4.z; v4.w = pk.u4.w;
+                    __builtin_nontemporal_store(v4, reinterpret_cast<u32x4*>(dst));     // written once, not read again here
+                } else {
+                    typedef float f32x4 __attribute__((ext_vector_type(4)));
+                    f32x4 a4 = {sc[u] * (float)d[0], sc[u] * (float)d[1], sc[u] * (float)d[2], sc[u] * (float)d[3]};
+                    f32x4 b4 = {sc[u] * (float)d[4], sc[u] * (float)d[5], sc[u] * (float)d[6], sc[u] * (float)d[7]};
+                    __builtin_nontemporal_store(a4, reinterpret_cast<f32x4*>(dst));
+                    __builtin_nontemporal_store(b4, reinterpret_cast<f32x4*>(dst) + 1);
+                }
+            }
+        }
+    }
+}
+
+// ---- full-matrix decompression, any shape: one thread per 8 codes = 8 consecutive outputs (one 16-byte store of halves) ---
 // 8 codes are 8*b consecutive bits starting at a multiple of 8 bits: at most two words.  Neighbouring lanes
 // write neighbouring 16 bytes, and re-read words their neighbours also read (served by the vector cache).
 template <int BITS, typename OT>
@@ -181,50 +330,11 @@ __global__ __launch_bounds__(256) void matvec_kernel(PackedArgs a, const XT* x, 
 }
 
 // float16 vector, one grid per lane segment (one grid per row, or groups of a multiple of 32): two weights per
-// v_dot2_f32_f16, and codes become halves without a conversion.  With the exponent bits of 2^b or-ed in, a code
-// sitting at mantissa bits [10-b, 10) of a half IS the float16 number 2^b + code.  Two codes whose bit positions
-// differ by 16 (mod 32) sit at the same place of the two halves of a 32-bit word, so one shift puts both at
-// [10-b, 10) / [26-b, 26) and one and-or masks them and sets both exponents:
-//   b = 4: codes k and k+4 of a word;  b = 2: codes k and k+8 of a word;
-//   b = 3: codes k and k+16 of the 96-bit group are 48 bits apart -- low half of one word, high half of another,
-//          joined by one byte permute that serves four or five pairs; the two pairs whose codes straddle a
-//          16-bit boundary (5, 21 and 10, 26) are cut out one code at a time.
-// The vector's halves are paired the same way once per segment.  The dot products accumulate
-// sum (2^b + code) x in float32, and  sum (code - zero) x = that - (2^b + zero) sum x;  the offset is of the size
-// of the codes themselves, so the subtraction costs no accuracy worth naming.
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+// v_dot2_f32_f16 on the pairs of halves 2^b + code made as above; the vector's halves are paired the same way once
+// per segment.  The dot products accumulate sum (2^b + code) x in float32, and
+// sum (code - zero) x = that - (2^b + zero) sum x;  the offset is of the size of the codes themselves, so the
+// subtraction costs no accuracy worth naming.
 constexpr int MV2_ROWS = 4;
-
-struct PairSpec { int lo_word, hi_word, rel, k_lo, k_hi; };      // lo_word < 0: cut the two codes out one at a time
-template <int BITS> struct PairTable;
-template <> struct PairTable<4> {
-    static constexpr PairSpec at(int i) { return {i / 4, i / 4, 4 * (i % 4), 8 * (i / 4) + i % 4, 8 * (i / 4) + i % 4 + 4}; }
-};
-template <> struct PairTable<2> {
-    static constexpr PairSpec at(int i) { return {i / 8, i / 8, 2 * (i % 8), 16 * (i / 8) + i % 8, 16 * (i / 8) + i % 8 + 8}; }
-};
-template <> struct PairTable<3> {
-    static constexpr PairSpec at(int i) {
-        if (i < 5) return {0, 1, 3 * i, i, i + 16};                                   // k = 0..4
-        if (i < 9) return {2, 0, 3 * (i + 1) - 16, (i + 1) + 16, i + 1};              // k = 6..9
-        if (i < 14) return {1, 2, 3 * (i + 2) - 32, i + 2, (i + 2) + 16};             // k = 11..15
-        return i == 14 ? PairSpec{-1, -1, 0, 5, 21} : PairSpec{-1, -1, 0, 10, 26};
-    }
-};
-
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
-    uint32_t v;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(v) : "v"(a), "s"(mask), "v"(c));   // written out: the compiler spends two on it
-    return v;
-}
-
-// 32 bits of the stream of words w[0..BITS] (w[BITS] = 0) starting at bit `from` (may be negative: shifted in zeros)
-template <int BITS>
-__device__ __forceinline__ uint32_t stream_bits(const uint32_t (&w)[BITS + 1], int from) {
-    if (from < 0) return w[0] << (-from);
-    const int wi = from >> 5, sh = from & 31;
-    return sh ? __builtin_amdgcn_alignbit(w[wi + 1], w[wi], sh) : w[wi];
-}
 
 template <int BITS>
 __global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __half* x, float* y) {
@@ -352,6 +462,8 @@ static int check_packed(const char* who, const uint32_t* words, int64_t ldp, int
     if (ldp < wpr) return fail(GPTQ_ERR_INVALID_ARG, "%s: word pitch smaller than ceil(n*bits/32)", who);
     a->words = words; a->ldp = ldp; a->r = r; a->n = n; a->words_per_row = wpr;
     a->scales = scales; a->zeros = zeros; a->group = group; a->ngroups = group ? n / group : 1;
+    a->gshift = -1;
+    if (group > 0 && (group & (group - 1)) == 0) { int sh = 0; while (((int64_t)1 << sh) < group) ++sh; a->gshift = sh; }
     return -1;
 }
 
@@ -368,10 +480,22 @@ extern "C" int gptq_dequantize_packed(const uint32_t* words, int64_t ldp, int64_
     if (odtype != GPTQ_F16 && odtype != GPTQ_F32) return fail(GPTQ_ERR_INVALID_ARG, "dequantize_packed: output type must be float16 or float32");
     if (!out) return fail(GPTQ_ERR_INVALID_ARG, "dequantize_packed: null pointer");
     if (ldo < n) return fail(GPTQ_ERR_INVALID_ARG, "dequantize_packed: ldo < n");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t osz = odtype == GPTQ_F16 ? 2 : 4;
+    if (n % 8 == 0 && n < 0x7fffffffLL && (group == 0 || group % 8 == 0) && aligned(out, 16) && (ldo * osz) % 16 == 0) {
+        const int64_t octets = n / 8;
+        const dim3 grid((unsigned)std::min<int64_t>(r, 256 * 64));
+#define GPTQ_DQ8(B)                                                                                                              \
+        if (odtype == GPTQ_F16) hipLaunchKernelGGL((dequantize8_kernel<B, _Float16>), grid, dim3(256), 0, s, a, static_cast<_Float16*>(out), ldo, octets); \
+        else hipLaunchKernelGGL((dequantize8_kernel<B, float>), grid, dim3(256), 0, s, a, static_cast<float*>(out), ldo, octets)
+        if (bits == 2) { GPTQ_DQ8(2); } else if (bits == 3) { GPTQ_DQ8(3); } else { GPTQ_DQ8(4); }
+#undef GPTQ_DQ8
+        GPTQ_LAUNCH_CHECK();
+        return GPTQ_OK;
+    }
     const int64_t g32 = (n + 7) / 8;               // octets of codes per row
     if (r * g32 > (int64_t)0x7fffffff * 256) return fail(GPTQ_ERR_UNSUPPORTED, "dequantize_packed: too large");
     const unsigned blocks = (unsigned)ceil_div(r * g32, 256);
-    hipStream_t s = static_cast<hipStream_t>(stream);
 #define GPTQ_DQ(B)                                                                                                              \
     if (odtype == GPTQ_F16) hipLaunchKernelGGL((dequantize_kernel<B, __half>), dim3(blocks), dim3(256), 0, s, a, static_cast<__half*>(out), ldo, g32); \
     else hipLaunchKernelGGL((dequantize_kernel<B, float>), dim3(blocks), dim3(256), 0, s, a, static_cast<float*>(out), ldo, g32)
