@@ -334,7 +334,7 @@ __global__ __launch_bounds__(256) void matvec_kernel(PackedArgs a, const XT* x, 
 // per segment.  The dot products accumulate sum (2^b + code) x in float32, and
 // sum (code - zero) x = that - (2^b + zero) sum x;  the offset is of the size of the codes themselves, so the
 // subtraction costs no accuracy worth naming.
-constexpr int MV2_ROWS = 4;
+constexpr int MV2_ROWS = 8;
 
 template <int BITS>
 __global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __half* x, float* y) {
