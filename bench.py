@@ -119,7 +119,8 @@ def cpu_baseline(lay, flops):
 
 def bench_block(a):
     """--layer opt175b_block: the six linears of one OPT-175B-shaped decoder block in sequence (q, k, v share one
-    Hessian), 3-bit and 4-bit; prints per-layer times and the block total as one JSON line."""
+    Hessian), 3-bit and 4-bit, with and without the next group's Hessian overlapped with the current group's
+    factorisation and Alg. 1; prints per-layer times and the block totals as one JSON line."""
     import torch
     import paper_2210_17323_amd as g
     from paper_2210_17323_amd import solver as S
@@ -132,45 +133,51 @@ def bench_block(a):
     by_x = {}
     for lay in layers:
         by_x.setdefault(lay.x.tensor_id, []).append(lay)
-    per_bits = {}
-    shared = {}
+    groups = []
+    for xid, lays in by_x.items():
+        _, X = configs.materialize(replace_rows(lays[0], 1), dev)          # X only; weights come per layer below
+        members = []
+        for lay in lays:
+            W = torch.empty((lay.r, lay.n), dtype=lay.dtype, device=dev)
+            rows = max(1, (1 << 27) // lay.n)
+            for r0 in range(0, lay.r, rows):
+                W[r0:r0 + rows] = lay.weights(row0=r0, nrows=min(rows, lay.r - r0), device=dev)
+            members.append((lay.name, W, lay))
+        groups.append((X, members))
+    chunk = min(a.chunk or 32768, m)
+    form = "auto" if a.form == "auto" else a.form
+    runs = {}
     for bits in (3, 4):
-        timings = {}
-        for xid, lays in by_x.items():
-            _, X = configs.materialize(replace_rows(lays[0], 1), dev)          # X only; weights come per layer below
-            group = []
-            for lay in lays:
-                W = torch.empty((lay.r, lay.n), dtype=lay.dtype, device=dev)
-                rows = max(1, (1 << 27) // lay.n)
-                for r0 in range(0, lay.r, rows):
-                    W[r0:r0 + rows] = lay.weights(row0=r0, nrows=min(rows, lay.r - r0), device=dev)
-                group.append((lay.name, W, lay))
+        for overlap in (False, True):
+            S.solve_block(groups, bits=bits, chunk=chunk, form=form, overlap=overlap)            # warm-up
+            torch.cuda.synchronize()
             t = {}
-            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk or 32768, m), timings=t)     # warm-up
-            t = {}
-            S.solve_block([(X, group)], bits=bits, chunk=min(a.chunk or 32768, m), timings=t)
-            names = "+".join(l.name for l in lays)
-            timings[f"{names}:hessian"] = t["group0:hessian"]
-            timings[f"{names}:damp_cholesky_inverse"] = t["group0:damp_cholesky_inverse"]
-            for lay in lays:
-                timings[f"{lay.name}:quantize_pack"] = t[f"{lay.name}:quantize_pack"]
-            del X, group
-            torch.cuda.empty_cache()
-        per_bits[bits] = timings
-    hu = sum(v for k, v in per_bits[3].items() if not k.endswith("quantize_pack"))
-    q3 = sum(v for k, v in per_bits[3].items() if k.endswith("quantize_pack"))
-    q4 = sum(v for k, v in per_bits[4].items() if k.endswith("quantize_pack"))
-    total3 = hu + q3
+            t0 = time.perf_counter()
+            S.solve_block(groups, bits=bits, chunk=chunk, form=form, overlap=overlap, timings=t)
+            torch.cuda.synchronize()
+            t["wall"] = (time.perf_counter() - t0) * 1e3
+            runs[(bits, overlap)] = t
+    def named(t):
+        out = {}
+        for gi, (_, members) in enumerate(groups):
+            names = "+".join(nm for nm, _, _ in members)
+            out[f"{names}:hessian"] = round(t[f"group{gi}:hessian"], 3)
+            out[f"{names}:factorisation"] = round(t[f"group{gi}:damp_cholesky_inverse"], 3)
+            for nm, _, _ in members:
+                out[f"{nm}:quantize_pack"] = round(t[f"{nm}:quantize_pack"], 3)
+        return out
+    total3 = runs[(3, True)]["total"]
     out = {
         "metric": "gptq_block_solve_ms", "value": total3, "unit": "ms", "n_gpus": 1, "steps": 1, "warmup": 1,
         "ms_per_step": total3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1); u8 codes", "data": "synthetic",
         "config": {"workload": f"one OPT-175B-shaped decoder block: q, k, v, out 12288x12288, fc1 49152x12288, fc2 12288x49152, "
-                               f"{m} tokens, per-row grids, B=128; q/k/v share one Hessian"},
-        "per_layer_ms_3bit": {k: round(v, 3) for k, v in per_bits[3].items()},
-        "per_layer_ms_4bit": {k: round(v, 3) for k, v in per_bits[4].items()},
-        "block_total_ms": {"3bit": total3, "4bit": hu + q4, "3bit_then_4bit_sharing_H_and_U": hu + q3 + q4,
-                           "3bit_then_4bit_redoing_H_and_U": 2 * hu + q3 + q4},
+                               f"{m} tokens, per-row grids, B=128; q/k/v share one Hessian",
+                   "steps_2_and_3": form, "tokens_per_accumulate_call": chunk},
+        "per_layer_ms_3bit_sequential": named(runs[(3, False)]),
+        "per_layer_ms_4bit_sequential": named(runs[(4, False)]),
+        "block_total_ms": {"3bit_sequential": round(runs[(3, False)]["total"], 3), "3bit_hessian_overlapped": round(runs[(3, True)]["total"], 3),
+                           "4bit_sequential": round(runs[(4, False)]["total"], 3), "4bit_hessian_overlapped": round(runs[(4, True)]["total"], 3)},
     }
     print(json.dumps(out))
 

@@ -66,7 +66,7 @@ GPTQ_API const char* gptq_last_error(void);
  *       256-byte aligned.  With it, 16-bit chunks of layers with at least 2048 channels are first repacked
  *       so that every 256-channel x 32-token panel step is one contiguous 16 KB block, which the
  *       matrix-core kernel copies with far better cache-line and DRAM-page locality; for layers whose H has
- *       few 256 x 256 tiles (up to ~8000 channels) the token range of the call is also split in up to 8
+ *       few 256 x 256 tiles (up to ~16000 channels) the token range of the call is also split in up to 8
  *       parts whose partial tiles (held in the workspace) are added in a fixed order, so that all CUs have
  *       work -- pass such layers long chunks, whole calibration sets if they fit.  Without the workspace
  *       the kernels read X in place: the same sums up to float32 summation order, at lower speed.

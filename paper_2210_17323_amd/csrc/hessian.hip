@@ -513,7 +513,7 @@ struct SyrkPlan { int splits; int64_t nsteps; size_t repack_bytes, partial_bytes
 static SyrkPlan syrk_plan(int64_t n, int64_t t) {
     const int64_t nt = ceil_div(n, 256), tiles = nt * (nt + 1) / 2, steps = ceil_div(t, DK);
     int best = 1;
-    if (tiles < 1024) {
+    if (tiles < 2048) {
         double best_cost = 0.0;
         for (int S = 1; S <= 8; ++S) {
             if (S > 1 && steps < 20 * (int64_t)S) break;             // a part should be at least 20 steps long

@@ -80,33 +80,55 @@ def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", 
 
 
 def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bool = False, timings: dict | None = None,
-                factors: dict | None = None, form: str = "auto"):
+                factors: dict | None = None, form: str = "auto", overlap: bool = False):
     """The layers of one block, quantized in sequence (Section 4, Setup: a block's inputs are collected, its
     layers quantized, then the next block).  `groups` is a list of (X, layers): X [n x m] are the input
     activations shared by `layers`, a list of (name, W, settings) with settings an object carrying
     bits / grid / block / group / percdamp (e.g. workloads.configs.Layer).  Layers that share an input share
-    one Hessian and one factor U.  Returns {name: LayerResult}; if `timings` is a dict it receives, per group,
+    one Hessian and one factor.  Returns {name: LayerResult}; if `timings` is a dict it receives, per group,
     the milliseconds of the Hessian and of the factorisation, and per layer those of Alg. 1 plus packing
-    (CUDA events on the current stream).  If `factors` is a dict it receives {group index: U}, the factor each
-    group's layers were quantized with (otherwise it is freed as soon as the group is done).
+    (CUDA events; with overlap the phases of different groups run at the same time, so they do not add up to the
+    wall time, which is returned under "total").  If `factors` is a dict it receives {group index: the factor
+    each group's layers were quantized with} (otherwise it is freed as soon as the group is done).
     form: "inverse" factors every group into U = Cholesky((H + lambda I)^-1)^T; "factor" into R with
     H + lambda I = R R^T and runs Alg. 1 from R (no triangular inverse; per-row grids only); "auto" takes the
-    factor form for the groups whose layers all have per-row grids."""
+    factor form for the groups whose layers all have per-row grids.
+    overlap: the Hessian of group k+1 is accumulated on a second stream while group k is factored and quantized
+    (the factorisation's serial chains leave most of the chip idle)."""
     out = {}
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream() if overlap else main
+    t_begin, t_end = ev(), ev()
+    t_begin.record(main)
+
+    def hessian_of(gi):
+        X = groups[gi][0]
+        e0, e1 = ev(), ev()
+        with torch.cuda.stream(side):
+            e0.record()
+            H = new_hessian(X.shape[0], X.device)
+            accumulate(H, X, chunk)
+            e1.record()
+        marks.append((f"group{gi}:hessian", e0, e1))
+        return H, e1
+
+    if overlap:
+        side.wait_stream(main)
+    pending = hessian_of(0)
     for gi, (X, layers) in enumerate(groups):
         n = X.shape[0]
-        e = [ev(), ev(), ev()]
+        H, h_done = pending
+        main.wait_event(h_done)
+        if gi + 1 < len(groups):
+            pending = hessian_of(gi + 1)          # with overlap: runs beside this group's factorisation and Alg. 1
+        e = [ev(), ev()]
         e[0].record()
-        H = new_hessian(n, X.device)
-        accumulate(H, X, chunk)
-        e[1].record()
         from_factor = form == "factor" or (form == "auto" and all(lay.group == 0 for _, _, lay in layers))
         U = (cholesky_factor if from_factor else cholesky_inverse)(H, layers[0][2].percdamp)
-        e[2].record()
-        marks.append((f"group{gi}:hessian", e[0], e[1]))
-        marks.append((f"group{gi}:damp_cholesky_inverse", e[1], e[2]))
+        e[1].record()
+        marks.append((f"group{gi}:damp_cholesky_inverse", e[0], e[1]))
         ws = None
         for name, W, lay in layers:
             b = lay.bits if bits is None else bits
@@ -120,9 +142,13 @@ def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bo
             marks.append((f"{name}:quantize_pack", q0, q1))
         if factors is not None:
             factors[gi] = U
+        if overlap:
+            H.record_stream(main)
         del H, U, ws
+    t_end.record(main)
     if timings is not None:
         torch.cuda.synchronize()
         for key, a, b in marks:
             timings[key] = a.elapsed_time(b)
+        timings["total"] = t_begin.elapsed_time(t_end)
     return out

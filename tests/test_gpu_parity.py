@@ -314,7 +314,13 @@ def test_block_driver_shares_hessians_and_matches_oracle(form):
     timings = {}
     res = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, timings=timings, form=form)
     assert set(res) == {"q", "k", "v", "out"}
-    assert {"group0:hessian", "group0:damp_cholesky_inverse", "group1:hessian", "q:quantize_pack", "out:quantize_pack"} <= set(timings)
+    assert {"group0:hessian", "group0:damp_cholesky_inverse", "group1:hessian", "q:quantize_pack", "out:quantize_pack", "total"} <= set(timings)
+    # the same block with the next group's Hessian accumulated on a second stream meanwhile: the same bits
+    res2 = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, form=form, overlap=True)
+    torch.cuda.synchronize()
+    for name in res:
+        assert torch.equal(res[name].codes, res2[name].codes) and torch.equal(res[name].scales, res2[name].scales)
+        assert torch.equal(res[name].packed, res2[name].packed)
     for X, ls in ((Xa, lays[:3]), (Xo, lays[3:])):
         Hd = O.damp(O.hessian(X.double().cpu().numpy()))
         U = O.hinv_cholesky_upper(Hd)
