@@ -432,3 +432,20 @@ def test_whole_path_without_the_inverse_matches_oracle():
     torch.cuda.synchronize()
     _compare_quant(res, W64, Uo, Hdo, lay.bits, lay.grid, 0, lay.n, "whole path, factor form", tie_tol=2e-3)
     assert np.array_equal(res.packed.cpu().numpy().view(np.uint32), O.pack_codes(res.codes.cpu().numpy(), lay.bits))
+
+
+def test_quantize_from_factor_with_unaligned_weight_rows():
+    # rows of W that start at odd element offsets: the block kernel takes its element-wise loads
+    bits, r, n = 3, 70, 384
+    lay = _layer(configs.config3()[1], n, r, 8 * n, shift=11)
+    W = lay.weights().to(torch.bfloat16)
+    X = lay.x.tile().double().numpy()
+    Hd = O.damp(O.hessian(X))
+    U = O.hinv_cholesky_upper(Hd)
+    big = torch.zeros((r, n + 5), dtype=torch.bfloat16, device="cuda")
+    Wd = big[:, 3:3 + n]
+    Wd.copy_(W)
+    Rd = torch.from_numpy(_upper_factor(Hd).astype(np.float32)).cuda()
+    res = S.quantize(Wd, Rd, bits, "minmax", 128, 0, want_Wq=True, from_factor=True)
+    torch.cuda.synchronize()
+    _compare_quant(res, W.double().numpy(), U, Hd, bits, "minmax", 0, n, "factor form, unaligned rows", tie_tol=2e-3)

@@ -35,10 +35,11 @@ def test_noalloc_matches_workspace_variant_twice():
         ib = torch.full((1,), -1, dtype=torch.int32, device="cuda")
         g.gptq_damp_cholesky_inverse(A, 0.01, ws, ia)
         torch.cuda.synchronize()
-        before = torch.cuda.memory_allocated()
+        count = lambda: torch.cuda.memory_stats()["allocation.all.allocated"]       # allocations made so far through torch
+        before = count()
         g.gptq_damp_cholesky_inverse_noalloc(B, 0.01, ib)
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before
+        assert count() == before
         assert g.gptq_check_info(ia) == 0 and g.gptq_check_info(ib) == 0
         assert torch.equal(A, B)
         want = O.hinv_cholesky_upper(O.damp(H32.astype(np.float64), 0.01))
