@@ -29,9 +29,10 @@ PEAK_HBM_GBS = 8000.0
 # for a plain 1 GiB copy kernel (factors 2.000 and 1.000): profiles/layer_solve_opt175b_fc2_pmc_counters.txt.  The fetch
 # reading varies from one collection to the next; the entry is the one tabulated there, the note gives the range seen.
 # Keyed by (n, tokens per call); other shapes: not collected.
-MEASURED_SYRK_TRAFFIC = {(49152, 32768): {"bytes": (6.8303e7 * 2.0 + 5.1301e6 * 1.0) * 1024,
+MEASURED_SYRK_TRAFFIC = {(49152, 32768): {"bytes": (6.2966e7 * 2.0 + 6.0244e6 * 1.0) * 1024,
                                           "note": "stored rocprofv3 reading (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000), not collected in "
-                                                  "this run; six collections of this launch gave 145-276 GB against 12.9 GB algorithmic"}}
+                                                  "this run; seven collections of this launch gave 135-283 GB against 12.9 GB algorithmic "
+                                                  "(X chunk read once, upper triangle of H read and written once)"}}
 
 
 def parse():

@@ -109,7 +109,7 @@ GPTQ_API int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* str
  *   Computed as a Cholesky factorisation taken from the last column backwards, H + lambda I = R R^T with R
  *   upper triangular, followed by the triangular inverse U = R^-1 (the same matrix, by uniqueness of
  *   the Cholesky factor), all in float32.
- *   Part of the work is enqueued on a helper stream owned by the library (created once per host thread and
+ *   Part of the work is enqueued on helper streams owned by the library (created once per host thread and
  *   device, default priority) and joined back with events: when the call returns, everything it enqueued
  *   is ordered on `stream`, and nothing of it starts before the work already on `stream`.
  */
@@ -121,7 +121,7 @@ GPTQ_API int gptq_damp_cholesky_inverse(float* H_U, int64_t ld, int64_t n, float
  * Step 2 for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc) and therefore cannot bring a workspace: the same kernels and the same
  * result as gptq_damp_cholesky_inverse, with the scratch space in a fixed device array that is part of the
- * library image (about 22 MiB, resident on every GPU the library runs on until the process ends).
+ * library image (about 51 MiB, resident on every GPU the library runs on until the process ends).
  *
  *   n <= GPTQ_NOALLOC_MAX_N (gptq_noalloc_max_n() returns it); a larger n is GPTQ_ERR_UNSUPPORTED and nothing is
  *   enqueued.  H_U, ld, percdamp, info_dev and the result are as for gptq_damp_cholesky_inverse.
