@@ -398,6 +398,14 @@ static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, i
                 if (int rc = gemm_on(s, H + j0, ld, H + o0 * ld + j0, ld, H + o0, ld, j0, j0 - o0, nbk, -1.f, uo)) return rc;
             }
         }
+        if (want_inverse && o1 < n) {
+            // Still on the stream that trails the chain: R[o, right] <- -U_oo R[o, right], which is what the inverse below
+            // needs of this row block.  R[o, right] is final here, no later step of the factorisation reads or writes it,
+            // and the product depends on nothing the inverse computes, so it is taken off the inverse's serial path.
+            Opt a; a.overwrite = true; a.atri = true;
+            if (int rc = gemm_on(s4, Ublk, OB, H + o0 * ld + o1, ld, w.T2, w.ld2, ow, n - o1, ow, -1.f, a)) return rc;
+            if (int rc = copy2d(s4, H + o0 * ld + o1, ld, w.T2, w.ld2, ow, n - o1)) return rc;
+        }
         // H[0:o0, 0:o0] -= R[0:o0, o] R[0:o0, o]^T (rank 1024, upper tiles), with look-ahead: the columns [p0, o0) of the next
         // outer block are updated first, on the caller's stream, which then goes on to factor that block (short, serial
         // kernels); the rest, H[0:p0, 0:p0], is updated on a helper stream meanwhile.  The two parts and the next block's
@@ -438,30 +446,28 @@ static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, i
         const int64_t k0 = k * OB, k1 = std::min<int64_t>(k0 + OB, n), kw = k1 - k0;
         const float* Ukk = w.Uoo + k * (int64_t)OB * OB;
         hipEvent_t read_done = nullptr;  // s: the column block above k has been read by this step's update
-        if (k1 < n) {
-            // T2 = -U_kk R[k, k1:n]   (U_kk upper triangular: a tile's K loop starts at its first row)
-            Opt a; a.overwrite = true; a.atri = true;
-            if (int rc = gemm_on(s, Ukk, OB, H + k0 * ld + k1, ld, w.T2, w.ld2, kw, n - k1, kw, -1.f, a)) return rc;
-            if (k0 > 0) {
-                // U[0:k0, k1:n] += U[0:k0, k] T2   (U[0:k0, k] not yet multiplied by U_kk)
-                Opt u;
-                if (int rc = gemm_on(s, H + k0, ld, w.T2, w.ld2, H + k1, ld, k0, n - k1, kw, 1.f, u)) return rc;
-            }
-            if (int rc = ts.mark(s, &read_done)) return rc;
-            if (int rc = copy2d(s, H + k0 * ld + k1, ld, w.T2, w.ld2, kw, n - k1)) return rc;
-        } else {
-            if (int rc = ts.mark(s, &read_done)) return rc;
+        if (k1 < n && k0 > 0) {
+            // U[0:k0, k1:n] += U[0:k0, k] (-U_kk R[k, k1:n])   (U[0:k0, k] not yet multiplied by U_kk; the second factor is
+            // what the factorisation left in the row block)
+            Opt u;
+            if (int rc = gemm_on(s, H + k0, ld, H + k0 * ld + k1, ld, H + k1, ld, k0, n - k1, kw, 1.f, u)) return rc;
         }
+        if (int rc = ts.mark(s, &read_done)) return rc;
         // On the other stream: U[0:k0, k] <- U[0:k0, k] U_kk through T, and the diagonal block.  Nothing later reads them.
-        if (int rc = ts.wait(s2, read_done)) return rc;
+        // The last column block has no update after it: it stays on the caller's stream, with the row-panel buffer (free
+        // by now) for its product, beside the last but one on the other stream.
+        const bool last = (k == nouter - 1) && nouter > 1;
+        hipStream_t sp = last ? s : s2;
+        float* Tp = last ? w.T2 : w.T;
+        if (!last) { if (int rc = ts.wait(s2, read_done)) return rc; }
         if (k0 > 0) {
             Opt c; c.overwrite = true; c.btri = true;
-            if (int rc = gemm_on(s2, H + k0, ld, Ukk, OB, w.T, OB, k0, kw, kw, 1.f, c)) return rc;
-            if (int rc = copy2d(s2, H + k0, ld, w.T, OB, k0, kw)) return rc;
+            if (int rc = gemm_on(sp, H + k0, ld, Ukk, OB, Tp, OB, k0, kw, kw, 1.f, c)) return rc;
+            if (int rc = copy2d(sp, H + k0, ld, Tp, OB, k0, kw)) return rc;
         }
-        hipLaunchKernelGGL(copy_block_kernel, dim3(256), dim3(256), 0, s2, H + k0 * ld + k0, ld, Ukk, (int64_t)OB, kw, (int)kw, 1);
+        hipLaunchKernelGGL(copy_block_kernel, dim3(256), dim3(256), 0, sp, H + k0 * ld + k0, ld, Ukk, (int64_t)OB, kw, (int)kw, 1);
         GPTQ_LAUNCH_CHECK();
-        if (int rc = ts.mark(s2, &panel_done)) return rc;
+        if (!last) { if (int rc = ts.mark(s2, &panel_done)) return rc; }
     }
     if (int rc = ts.wait(s, panel_done)) return rc;
     return GPTQ_OK;
