@@ -49,9 +49,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--form", choices=["auto", "factor", "inverse"], default="auto",
                     help="steps 2 and 3.  factor: gptq_damp_cholesky + gptq_quantize_layer_from_factor (Alg. 1 driven by the Cholesky "
-                         "factor of H + lambda I itself, no triangular inverse; per-row grids only).  inverse: "
+                         "factor of H + lambda I itself, no triangular inverse; one grid per row or groups of 32, 64 or 128).  inverse: "
                          "gptq_damp_cholesky_inverse + gptq_quantize_layer (U = Cholesky of the inverse, any grid).  auto: factor "
-                         "for per-row grids, inverse for grouped ones")
+                         "where the library offers it for the layer's grid, else inverse")
     ap.add_argument("--no-other-layers", action="store_true",
                     help="skip the short runs of the other workload shapes that the default (opt175b_fc2) line carries as extra keys")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -306,7 +306,7 @@ def main():
         torch.mul(src, 1.0, out=dst)        # an elementwise kernel (a same-dtype copy_ would be a DMA transfer, not a kernel)
         torch.cuda.synchronize()
         del src, dst
-    factor_form = a.form == "factor" or (a.form == "auto" and lay.group == 0)
+    factor_form = a.form == "factor" or (a.form == "auto" and g.gptq_quantize_layer_from_factor_supports(lay.group))
     lb = LayerBench(lay, a.chunk, dev, factor_form=factor_form)
     ms_per_step, phases = lb.run(a.steps, a.warmup)
     chunk = lb.chunk
@@ -407,7 +407,7 @@ def main():
         others = {}
         for name in OTHER_LAYERS:
             ol = pick_layer(name, a.tokens)
-            off = ol.group == 0
+            off = g.gptq_quantize_layer_from_factor_supports(ol.group)
             ob = LayerBench(ol, 0, dev, factor_form=off)
             oms, oph = ob.run(2, 1)
             ofl = flop_model(ol.r, ol.n, ol.x.m, ol.block)

@@ -187,15 +187,21 @@ GPTQ_API int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t
  *
  * gptq_damp_cholesky: as gptq_damp_cholesky_inverse, but stops after the factorisation.  Out: R in the upper triangle
  *   of H_R, zeros strictly below.  Workspace and info_dev as there.
- * gptq_quantize_layer_from_factor: as gptq_quantize_layer with R in place of U.  One grid per row only (group must
- *   be 0: a grid taken from the current weights in the middle of the walk is GPTQ_ERR_UNSUPPORTED here, use the U
- *   form).  W is read in its own type at every block (it is not copied); the workspace
+ * gptq_quantize_layer_from_factor: as gptq_quantize_layer with R in place of U.  group must be 0 (one grid per row)
+ *   or 32, 64 or 128 (gptq_quantize_layer_from_factor_supports(group) returns 1 for these, 0 otherwise); any other
+ *   group size is GPTQ_ERR_UNSUPPORTED here, use the U form.  A group's grid is taken from the weights as they stand at
+ *   its first column (Section 4, "Additional Tricks"), which this form does not hold: at the start of every block
+ *   of 128 columns they are rebuilt as w + s R_bb^-1 from the block's accumulators s and the inverse of the block's own
+ *   128 x 128 diagonal block of R (the corrections of the waiting columns satisfy delta R_bb = s), and inside the
+ *   block Alg. 1 runs on that inverse, which is the diagonal block of U.
+ *   W is read in its own type at every block (it is not copied); the workspace
  *   (gptq_quantize_layer_workspace_bytes) holds the float32 accumulators instead.  All other arguments, outputs
  *   (codes, scales, zeros, Wq, half_E2_rows) and error behaviour as for gptq_quantize_layer.
  */
 GPTQ_API size_t gptq_damp_cholesky_workspace_bytes(int64_t n);
 GPTQ_API int gptq_damp_cholesky(float* H_R, int64_t ld, int64_t n, float percdamp,
                        void* ws, size_t ws_bytes, int* info_dev, void* stream);
+GPTQ_API int gptq_quantize_layer_from_factor_supports(int64_t group);
 GPTQ_API int gptq_quantize_layer_from_factor(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
                                     const float* R, int64_t ldr,
                                     int bits, int grid, int block, int64_t group,

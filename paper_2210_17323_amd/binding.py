@@ -65,6 +65,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_damp_cholesky_workspace_bytes.restype = sz
     L.gptq_damp_cholesky.argtypes = [vp, i64, i64, f32, vp, sz, vp, vp]
     L.gptq_quantize_layer_from_factor.argtypes = L.gptq_quantize_layer.argtypes
+    L.gptq_quantize_layer_from_factor_supports.argtypes = [i64]
+    L.gptq_quantize_layer_from_factor_supports.restype = ci
     L.gptq_trailing_update.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i64, vp]
     L.gptq_pack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     L.gptq_unpack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
@@ -229,6 +231,11 @@ def gptq_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, grid: int, 
           _ptr(codes), _ld(codes), _ptr(scales), _ptr(zeros),
           _ptr(Wq), _ld(Wq) if Wq is not None else 0, _ptr(half_E2_rows),
           _ptr(ws), ws.numel(), _stream()))
+
+
+def gptq_quantize_layer_from_factor_supports(group: int) -> bool:
+    """Whether gptq_quantize_layer_from_factor takes this group size (0 = one grid per row)."""
+    return bool(lib().gptq_quantize_layer_from_factor_supports(int(group)))
 
 
 def gptq_quantize_layer_from_factor(W, R, bits, grid, block, group, codes, scales, zeros, ws, Wq=None, half_E2_rows=None) -> None:

@@ -14,34 +14,9 @@
 //       index is static.  Outputs: codes, the block's error matrix E (r x 128), per-row sum of e^2.
 //   trailing update    : W[:, i+B:] -= E * U[i:i+B, i+B:], the float32 matrix-core GEMM, applied at once to
 //       the rest of the current 1024-column outer block and deferred (rank 1024) for the columns beyond.
-#include "common.h"
-
-#include <utility>
+#include "quantize_common.h"
 
 namespace gptq {
-
-constexpr int QB = 128;
-
-// ---- W (f16 / bf16 / f32) -> float32 working copy; optionally the per-row grid from the original row.
-template <typename T> __device__ __forceinline__ float to_f32(T v);
-template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
-template <> __device__ __forceinline__ float to_f32<_Float16>(_Float16 v) { return (float)v; }
-template <> __device__ __forceinline__ float to_f32<__bf16>(__bf16 v) { return (float)v; }
-
-__device__ __forceinline__ void grid_from_range(int grid, float maxq, float lo, float hi, float amax, float& scale, int& zero) {
-    if (grid == GPTQ_GRID_TERNARY) {
-        scale = (amax == 0.f) ? 1.f : amax;
-        zero = 1;
-    } else {
-        lo = fminf(lo, 0.f);
-        hi = fmaxf(hi, 0.f);
-        if (hi == lo) { scale = 1.f; zero = 0; }
-        else {
-            scale = (hi - lo) / maxq;
-            zero = (int)rintf(-lo / scale);
-        }
-    }
-}
 
 // One workgroup per row: convert the row and reduce min / max / max|.|.
 template <typename T>
@@ -108,30 +83,6 @@ struct QuantArgs {
     int first_block;
 };
 
-// ---- the stream of U values ------------------------------------------------------------------------------
-// Row j of the block of U is needed from the aligned chunk of 16 floats that holds column j: the diagonal
-// element and the elements right of it.  A chunk sits in ONE register: lane l holds element l % 16 (the same
-// 16 values in each of the wavefront's four rows of 16 lanes), and the multiply-add that needs element c reads
-// it from lane c of its own row through the DPP row broadcast -- v_fmac_f32_dpp ... row_newbcast:c -- so a value
-// of U reaches all 64 lanes inside the instruction that uses it.  (Reading each value into every lane with
-// 16-byte LDS reads cost as many issue cycles per value as the multiply-add itself.)
-// All rows' chunks, in the order of their use, form one stream; it is read from LDS through a ring of RING
-// registers: the chunk at stream position t + RING is requested right after the one at position t has been used,
-// so a request runs well over a thousand cycles ahead of its use, also across the serial arithmetic at a column.
-// Rows, chunks and ring slots are template parameters: every register index is a constant by construction.
-namespace ustream {
-constexpr int RING = 8;
-constexpr int CHUNK = 16;
-constexpr int first_chunk(int j) { return j / CHUNK; }
-constexpr int chunks(int j) { return QB / CHUNK - first_chunk(j); }
-constexpr int start(int j) { int s = 0; for (int i = 0; i < j; ++i) s += chunks(i); return s; }
-constexpr int TOTAL = start(QB);
-constexpr int row_at(int t) { int j = 0; while (t >= chunks(j)) { t -= chunks(j); ++j; } return j; }
-}  // namespace ustream
-
-typedef const __attribute__((address_space(3))) float* lds_floats;
-typedef const volatile __attribute__((address_space(3))) float* lds_floats_ordered;
-
 struct QuantState {
     float w[QB];                        // working weights of the block; e_j once column j is done
     float ring[ustream::RING];
@@ -145,23 +96,6 @@ struct QuantState {
 
 // The same walk driven by the Cholesky factor R of H + lambda I itself instead of U = R^-1 (see quant_block_rf_kernel):
 // the original weights stay as they are and the updates go to an accumulator s[k] = sum over quantized i of d_i R[i][k].
-template <typename WT> struct WeightRegs {                  // float32 weights: one register each
-    float v[QB];
-    template <int J> __device__ __forceinline__ float get() const { return v[J]; }
-};
-template <> struct WeightRegs<_Float16> {                    // 16-bit weights stay packed two to a register
-    uint32_t v[QB / 2];
-    template <int J> __device__ __forceinline__ float get() const {
-        return (float)__builtin_bit_cast(_Float16, (uint16_t)(v[J / 2] >> (16 * (J & 1))));
-    }
-};
-template <> struct WeightRegs<__bf16> {
-    uint32_t v[QB / 2];
-    template <int J> __device__ __forceinline__ float get() const {
-        return __builtin_bit_cast(float, (J & 1) ? (v[J / 2] & 0xffff0000u) : (v[J / 2] << 16));
-    }
-};
-
 template <typename WT>
 struct FactorState {
     WeightRegs<WT> w;                   // original weights of the block
@@ -175,92 +109,6 @@ struct FactorState {
     bool active;
     __device__ __forceinline__ float (&acc())[QB] { return s; }
 };
-
-// Volatile on purpose: volatile accesses and volatile asm statements (the multiply-adds below) keep their
-// program order, which is what places each request RING chunks ahead of its use.  An ordinary load has no such
-// order: with the whole column loop one straight line, the compiler either hoists all requests to the top or
-// sinks each one down to its use and then waits for it.  `ubl` is the block in LDS offset by lane % 16.
-template <int T, class St>
-__device__ __forceinline__ void request_chunk(St& st, lds_floats ubl) {
-    if constexpr (T < ustream::TOTAL) {
-        constexpr int j = ustream::row_at(T), q = ustream::first_chunk(j) + (T - ustream::start(j));
-        st.ring[T % ustream::RING] = *static_cast<lds_floats_ordered>(ubl + j * QB + ustream::CHUNK * q);
-    }
-}
-
-template <class St, int... T>
-__device__ __forceinline__ void request_first(St& st, lds_floats ubl, std::integer_sequence<int, T...>) {
-    (request_chunk<T>(st, ubl), ...);
-}
-
-// w[k] += ne * (element C of the chunk in `u`), for all lanes.  The s_nop covers the two wait states a DPP read
-// needs after a vector-ALU write of the same register, should the compiler ever have moved the chunk there.
-template <int C, bool FIRST>
-__device__ __forceinline__ void fma_bcast(float& w, float u, float ne) {
-    if constexpr (FIRST)
-        asm volatile("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(w) : "v"(u), "v"(ne), "n"(C));
-    else
-        asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(w) : "v"(u), "v"(ne), "n"(C));
-}
-
-template <int J, int K0, class St, int... C>
-__device__ __forceinline__ void update_chunk_columns(St& st, float u, float ne, std::integer_sequence<int, C...>) {
-    // columns K0 + C right of J; the first one issued carries the s_nop
-    constexpr int first = (J >= K0) ? J - K0 + 1 : 0;
-    ((K0 + C > J ? fma_bcast<C, C == first>(st.acc()[K0 + C], u, ne) : (void)0), ...);
-}
-
-// w[k] -= e * U[J][k] for the columns of chunk Q right of J, then the request that refills the slot
-template <int J, int Q, class St>
-__device__ __forceinline__ void update_chunk(St& st, lds_floats ubl, float ne) {
-    constexpr int t = ustream::start(J) + Q, k0 = ustream::CHUNK * (ustream::first_chunk(J) + Q);
-    update_chunk_columns<J, k0>(st, st.ring[t % ustream::RING], ne, std::make_integer_sequence<int, ustream::CHUNK>{});
-    request_chunk<t + ustream::RING>(st, ubl);
-}
-
-template <int J, class St, int... Q>
-__device__ __forceinline__ void update_row(St& st, lds_floats ubl, float ne, std::integer_sequence<int, Q...>) {
-    (update_chunk<J, Q>(st, ubl, ne), ...);
-}
-
-// The 128 x 128 diagonal block of an upper-triangular matrix M (U, or the factor R) into LDS:
-// ubs[j][k] = M[j0+j][j0+k] for k >= j, zero below the diagonal, identity outside the matrix.  The whole workgroup
-// (256 threads) calls it: 16 independent 16-byte loads per thread (in PARTS passes of 16 / PARTS, for callers short
-// of registers), then one barrier.
-template <int PARTS = 1>
-__device__ __forceinline__ void stage_diag_block(float* ubs, const float* M, int64_t ldm, int64_t j0, int64_t n) {
-    const int tid = threadIdx.x;
-    constexpr int PER = 16 / PARTS;
-#pragma unroll
-    for (int part = 0; part < PARTS; ++part) {
-    float4 in[PER];
-#pragma unroll
-    for (int tt = 0; tt < PER; ++tt) {
-        const int t = part * PER + tt;
-        const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
-        const int64_t gj = j0 + j, gk = j0 + k;
-        const float* src = M + gj * ldm + gk;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (gj < n && gk + 4 <= n) v = *reinterpret_cast<const float4*>(src);
-        else if (gj < n && gk < n) { v.x = src[0]; if (gk + 1 < n) v.y = src[1]; if (gk + 2 < n) v.z = src[2]; }
-        in[tt] = v;
-    }
-#pragma unroll
-    for (int tt = 0; tt < PER; ++tt) {
-        const int t = part * PER + tt;
-        const int q = tid + 256 * t, j = q >> 5, k = (q & 31) * 4;
-        const int64_t gj = j0 + j, gk = j0 + k;
-        float e[4] = {in[tt].x, in[tt].y, in[tt].z, in[tt].w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const bool inside = gj < n && gk + c < n;
-            e[c] = inside ? (k + c >= j ? e[c] : 0.f) : (k + c == j ? 1.f : 0.f);
-        }
-        *reinterpret_cast<float4*>(&ubs[j * QB + k]) = make_float4(e[0], e[1], e[2], e[3]);
-    }
-    }
-    __syncthreads();
-}
 
 // Column J of the block: its grid if a group starts here, the code, the error, the update of the columns right of it.
 template <int G, int J>
@@ -311,8 +159,8 @@ __device__ __forceinline__ void quantize_columns(QuantState& st, lds_floats ubs,
     (quantize_column<G, J>(st, ubs, a, row, maxq), ...);
 }
 
-// G = 0: the grid of this block's columns is already in scales/zeros (per-row grid, or a group that
-//        is a multiple of 128).  G in {8,16,32,64}: groups inside the block, grid taken from the
+// G = 0: the grid of this block's columns is already in scales/zeros (per-row grid, or a group of
+//        several blocks).  G in {8,16,32,64,128}: groups inside the block, grid taken from the
 //        current register values at each group start.
 template <int G>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void quant_block_kernel(QuantArgs a) {
@@ -505,9 +353,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 // One workgroup per row: the per-row grid from the original weights, and the row of accumulators cleared.
 template <typename T>
 __global__ __launch_bounds__(256) void prepare_rows_rf_kernel(const T* W, int64_t ldw, int64_t n, float* S, int64_t lds_,
-                                                              int grid, float maxq, float* scales, int32_t* zeros) {
+                                                              int want_grid, int grid, float maxq, float* scales, int32_t* zeros) {
     const int64_t row = blockIdx.x;
     float lo = INFINITY, hi = -INFINITY, am = 0.f;
+    if (!want_grid) {                                       // grouped grids are taken block by block, from the current weights
+        for (int64_t k = threadIdx.x; k < n; k += 256) S[row * lds_ + k] = 0.f;
+        return;
+    }
     for (int64_t k = threadIdx.x; k < n; k += 256) {
         const float v = to_f32<T>(W[row * ldw + k]);
         S[row * lds_ + k] = 0.f;
@@ -550,9 +402,13 @@ static bool group_supported(int64_t group) {
     return group == 8 || group == 16 || group == 32 || group == 64;
 }
 
+// The factor form takes one grid per row, or groups that lie inside a block and are wide enough for the walk to be
+// worth instantiating (32, 64, 128).
+static bool factor_form_group_supported(int64_t group) { return group == 0 || group == 32 || group == 64 || group == 128; }
+
 constexpr int QOB = 1024;   // outer block: trailing updates beyond it are deferred and applied as one rank-1024 GEMM
 
-struct QuantWs { size_t wk, e, cs, total; int64_t ldk; };
+struct QuantWs { size_t wk, e, cs, t, ub, total; int64_t ldk; };
 static QuantWs quant_ws_layout(int64_t r, int64_t n) {
     QuantWs l;
     l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
@@ -560,6 +416,8 @@ static QuantWs quant_ws_layout(int64_t r, int64_t n) {
     size_t off = round_up((size_t)std::max<int64_t>(r, 1) * l.ldk * sizeof(float), 256);
     l.e = off; off += 2 * round_up((size_t)std::max<int64_t>(r, 1) * QOB * sizeof(float), 256);   // two error panels (look-ahead)
     l.cs = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QB, 256);                        // codes of a block that cannot be stored in place
+    l.t = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QB * sizeof(float), 256);         // factor form with groups: S[:, block] U_bb
+    l.ub = off; off += round_up((size_t)ceil_div(std::max<int64_t>(n, 1), QB) * QB * QB * sizeof(float), 256);   // ... and every U_bb
     l.total = off + 256;
     return l;
 }
@@ -607,9 +465,10 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
     if (group > 0 && n % group) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: n must be a multiple of the group size");
     if (group > 0 && (QB % group) && (group % QB)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: a group must not straddle a block end (need 128 %% g == 0 or g %% 128 == 0)");
     if (!group_supported(group)) return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer: group size %lld not built (8, 16, 32, 64 or a multiple of 128)", (long long)group);
-    if (rf && group != 0)
-        return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer_from_factor: grouped grids are taken from the current weights, which this form does "
-                                          "not hold; use gptq_damp_cholesky_inverse + gptq_quantize_layer");
+    if (rf && !factor_form_group_supported(group))
+        return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer_from_factor: one grid per row or groups of 32, 64 or 128 columns (got %lld); a group's grid "
+                                          "is taken from the current weights, which this form rebuilds one block at a time: use "
+                                          "gptq_damp_cholesky_inverse + gptq_quantize_layer", (long long)group);
     if (r == 0 || n == 0) return GPTQ_OK;
     if (!W || !U || !codes || !scales || !zeros) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: null pointer");
     if (ldw < n || ldu < n || ldc < n || (Wq && ldq < n)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: leading dimension smaller than n");
@@ -630,13 +489,13 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
     if (rf) {
         switch (wdtype) {
             case GPTQ_F16:
-                hipLaunchKernelGGL(prepare_rows_rf_kernel<_Float16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const _Float16*>(W), ldw, n, Wk, lay.ldk, grid, (float)maxq, scales, zeros);
+                hipLaunchKernelGGL(prepare_rows_rf_kernel<_Float16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const _Float16*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
                 break;
             case GPTQ_BF16:
-                hipLaunchKernelGGL(prepare_rows_rf_kernel<__bf16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const __bf16*>(W), ldw, n, Wk, lay.ldk, grid, (float)maxq, scales, zeros);
+                hipLaunchKernelGGL(prepare_rows_rf_kernel<__bf16>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const __bf16*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
                 break;
             default:
-                hipLaunchKernelGGL(prepare_rows_rf_kernel<float>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const float*>(W), ldw, n, Wk, lay.ldk, grid, (float)maxq, scales, zeros);
+                hipLaunchKernelGGL(prepare_rows_rf_kernel<float>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const float*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
         }
     } else
     switch (wdtype) {
@@ -650,6 +509,12 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
             hipLaunchKernelGGL(prepare_rows_kernel<float>, dim3((unsigned)r), dim3(256), 0, s, static_cast<const float*>(W), ldw, n, Wk, lay.ldk, want_grid, grid, (float)maxq, scales, zeros);
     }
     GPTQ_LAUNCH_CHECK();
+    const bool hybrid = rf && group != 0;
+    float* Tblk = reinterpret_cast<float*>(base + lay.t);
+    float* Ub = reinterpret_cast<float*>(base + lay.ub);
+    if (hybrid) {
+        if (int rc = launch_invert_diag_blocks(U, ldu, n, Ub, s)) return rc;
+    }
 
     const unsigned qblocks = (unsigned)ceil_div(r, 256);
     // Lazy batching at two levels (Section 3, Step 2 applied twice): inside an outer block of 1024 columns
@@ -674,14 +539,26 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
         for (int64_t j0 = o0; j0 < o1; j0 += QB) {
             const int nbk = (int)std::min<int64_t>(QB, n - j0);
             const int64_t j1 = j0 + nbk;
-            if (group >= QB && j0 % group == 0) {
+            if (group > QB && j0 % group == 0) {
                 // The grid is taken from all columns of the group as they stand now.  Those beyond this outer
                 // block are kept current by the helper stream: its last update has to be in.
                 if (j0 + group > o1) { if (int rc = ts.wait(s, rest_done)) return rc; }
                 hipLaunchKernelGGL(group_grid_kernel, dim3((unsigned)r), dim3(64), 0, s, (const float*)Wk, lay.ldk, j0, group, grid, (float)maxq, scales, zeros, ngroups, j0 / group);
                 GPTQ_LAUNCH_CHECK();
             }
-            if (rf) {
+            if (hybrid) {
+                // T = S[:, block] U_bb (U_bb upper triangular: a tile's K range ends at its last column), then the block
+                GemmF32 g{};
+                g.A = Wk + j0; g.lda = lay.ldk; g.B = Ub + (j0 / QB) * QB * QB; g.ldb = QB; g.C = Tblk; g.ldc = QB;
+                g.M = r; g.N = nbk; g.K = nbk; g.alpha = 1.f; g.b_is_nk = false; g.overwrite = true; g.b_upper_tri = true;
+                if (int rc = launch_gemm_f32(g, s)) return rc;
+                HybridArgs h{};
+                h.W = W; h.ldw = ldw; h.T = Tblk; h.Ub = Ub + (j0 / QB) * QB * QB; h.r = r; h.n = n; h.j0 = j0; h.nbk = nbk;
+                h.grid = grid; h.maxq = maxq; h.scales = scales; h.zeros = zeros; h.ngroups = ngroups;
+                h.codes = codes; h.ldc = ldc; h.cstage = reinterpret_cast<uint8_t*>(base + lay.cs);
+                h.D = E + (j0 - o0); h.ldd = QOB; h.half_e2 = half_E2_rows; h.first_block = (j0 == 0);
+                if (int rc = launch_quant_block_hybrid(group, wdtype, qblocks, h, s)) return rc;
+            } else if (rf) {
                 FactorArgs f{};
                 f.W = W; f.ldw = ldw; f.S = Wk; f.lds_ = lay.ldk; f.R = U; f.ldr = ldu; f.r = r; f.n = n; f.j0 = j0; f.nbk = nbk;
                 f.maxq = maxq; f.scales = scales; f.zeros = zeros; f.codes = codes; f.ldc = ldc;
@@ -697,9 +574,10 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
             a.Wk = Wk; a.ldk = lay.ldk; a.U = U; a.ldu = ldu; a.r = r; a.n = n; a.j0 = j0; a.nbk = nbk; a.grid = grid; a.maxq = maxq;
             a.scales = scales; a.zeros = zeros; a.ngroups = ngroups; a.group = group;
             a.codes = codes; a.ldc = ldc; a.E = E + (j0 - o0); a.lde = QOB; a.half_e2 = half_E2_rows; a.first_block = (j0 == 0);
-            const int G = (group > 0 && group < QB) ? (int)group : 0;
+            const int G = (group > 0 && group <= QB) ? (int)group : 0;
             switch (G) {
                 case 0:  hipLaunchKernelGGL(quant_block_kernel<0>,  dim3(qblocks), dim3(256), 0, s, a); break;
+                case 128: hipLaunchKernelGGL(quant_block_kernel<128>, dim3(qblocks), dim3(256), 0, s, a); break;
                 case 8:  hipLaunchKernelGGL(quant_block_kernel<8>,  dim3(qblocks), dim3(256), 0, s, a); break;
                 case 16: hipLaunchKernelGGL(quant_block_kernel<16>, dim3(qblocks), dim3(256), 0, s, a); break;
                 case 32: hipLaunchKernelGGL(quant_block_kernel<32>, dim3(qblocks), dim3(256), 0, s, a); break;
@@ -752,6 +630,8 @@ extern "C" int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64
     return alg1_run(false, W, wdtype, ldw, r, n, U, ldu, bits, grid, block, group, codes, ldc, scales, zeros, Wq, ldq,
                     half_E2_rows, ws, ws_bytes, stream);
 }
+
+extern "C" int gptq_quantize_layer_from_factor_supports(int64_t group) { return factor_form_group_supported(group) ? 1 : 0; }
 
 extern "C" int gptq_quantize_layer_from_factor(const void* W, int wdtype, int64_t ldw, int64_t r, int64_t n,
                                                const float* R, int64_t ldr,

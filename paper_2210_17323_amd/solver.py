@@ -58,7 +58,8 @@ def cholesky_factor(H: torch.Tensor, percdamp: float = 0.01, check: bool = True)
 
 def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", block: int = 128, group: int = 0,
              want_Wq: bool = False, pack: bool = False, ws: torch.Tensor | None = None, from_factor: bool = False) -> LayerResult:
-    """Alg. 1 + optional packing.  from_factor: `U` is the factor R of cholesky_factor (per-row grids only)."""
+    """Alg. 1 + optional packing.  from_factor: `U` is the factor R of cholesky_factor (one grid per row, or groups of
+    32, 64 or 128 columns: B.gptq_quantize_layer_from_factor_supports)."""
     r, n = W.shape
     dev = W.device
     G = n // group if group else 1
@@ -125,7 +126,7 @@ def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bo
             pending = hessian_of(gi + 1)          # with overlap: runs beside this group's factorisation and Alg. 1
         e = [ev(), ev()]
         e[0].record()
-        from_factor = form == "factor" or (form == "auto" and all(lay.group == 0 for _, _, lay in layers))
+        from_factor = form == "factor" or (form == "auto" and all(B.gptq_quantize_layer_from_factor_supports(lay.group) for _, _, lay in layers))
         U = (cholesky_factor if from_factor else cholesky_inverse)(H, layers[0][2].percdamp)
         e[1].record()
         marks.append((f"group{gi}:damp_cholesky_inverse", e[0], e[1]))

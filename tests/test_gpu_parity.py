@@ -390,7 +390,12 @@ def test_cholesky_factor_matches_oracle(n, kind):
     assert err <= 2e-5 and resid <= 1e-5
 
 
-FACTOR_CASES = [c for c in QUANT_CASES if c[2] == 0] + [(2, "ternary", 0, torch.float16, 130, 640), (3, "minmax", 0, torch.float32, 64, 2304)]
+FACTOR_CASES = [c for c in QUANT_CASES if c[2] in (0, 32, 64, 128)] + [
+    (2, "ternary", 0, torch.float16, 130, 640), (3, "minmax", 0, torch.float32, 64, 2304),
+    # grids taken inside a block: the working weights are rebuilt from the accumulators at every block start
+    (3, "minmax", 128, torch.float32, 70, 1408), (4, "minmax", 64, torch.float16, 257, 2240), (2, "ternary", 32, torch.bfloat16, 33, 1184),
+    (3, "minmax", 32, torch.float16, 48, 160),        # a block and a quarter
+]
 
 
 @pytest.mark.parametrize("bits,grid,group,dtype,r,n", FACTOR_CASES)
@@ -407,14 +412,16 @@ def test_quantize_layer_from_factor_matches_oracle(bits, grid, group, dtype, r, 
     Wd.copy_(W)
     Rd = _padded(n, n, torch.float32, 4)
     Rd.copy_(torch.from_numpy(R32))
-    res = S.quantize(Wd, Rd, bits, grid, 128, 0, want_Wq=True, from_factor=True)
+    assert g.gptq_quantize_layer_from_factor_supports(group)
+    res = S.quantize(Wd, Rd, bits, grid, 128, group, want_Wq=True, from_factor=True)
     torch.cuda.synchronize()
     # the oracle runs on its own float64 U; the kernel saw R rounded to float32
-    _compare_quant(res, W.double().numpy(), U, Hd, bits, grid, 0, n, "factor form", tie_tol=2e-3)
+    _compare_quant(res, W.double().numpy(), U, Hd, bits, grid, group, n, "factor form", tie_tol=2e-3)
     assert int(res.codes.max()) <= O.grid_maxq(bits, grid)
     assert torch.equal(Wd.cpu(), W)
     if n % 8 == 0:
-        with pytest.raises(g.GptqError) as ei:       # grouped grids need the current weights: the U form
+        assert not g.gptq_quantize_layer_from_factor_supports(8)
+        with pytest.raises(g.GptqError) as ei:       # groups this form does not take: the U form
             S.quantize(Wd, Rd, bits, grid, 128, 8, from_factor=True)
         assert ei.value.code == 4
 
