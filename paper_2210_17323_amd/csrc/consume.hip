@@ -334,42 +334,110 @@ __global__ __launch_bounds__(256) void matvec_kernel(PackedArgs a, const XT* x, 
 // per segment.  The dot products accumulate sum (2^b + code) x in float32, and
 // sum (code - zero) x = that - (2^b + zero) sum x;  the offset is of the size of the codes themselves, so the
 // subtraction costs no accuracy worth naming.
-constexpr int MV2_ROWS = 8;
+constexpr int MV2_ROWS = 8;      // rows per step of a workgroup, read four at a time
+constexpr int MV2_HALF = 4;
 
+// The b words of this lane's 32 columns for four consecutive rows (rows past r repeat the last one).  n is a multiple
+// of 32 here, so a lane's words are all inside the row or all outside; `w0` is clamped by the caller for the latter,
+// whose vector entries are zero.
 template <int BITS>
-__global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __half* x, float* y) {
-    __shared__ float part[4][MV2_ROWS];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__device__ __forceinline__ void mv_load_rows(uint32_t (&w)[MV2_HALF][BITS + 1], const PackedArgs& a, int64_t rowbase, int64_t w0) {
+#pragma unroll
+    for (int rr = 0; rr < MV2_HALF; ++rr) {
+        const int64_t row = min(rowbase + rr, a.r - 1);
+        struct __attribute__((packed, aligned(4))) Words { uint32_t v[BITS]; };
+        const Words t = *reinterpret_cast<const Words*>(a.words + row * a.ldp + w0);      // one load of b words
+#pragma unroll
+        for (int i = 0; i < BITS; ++i) w[rr][i] = t.v[i];
+        w[rr][BITS] = 0u;
+    }
+}
+
+// The same two instructions as volatile statements: they keep their program order, so a pair of halves is consumed by
+// its dot product right after it is made.  Left to itself the scheduler makes all 64 pairs of four rows first and
+// holds them in registers, which costs a wavefront per SIMD.
+__device__ __forceinline__ uint32_t and_or_ordered(uint32_t a, uint32_t mask, uint32_t c) {
+    uint32_t v;
+    asm volatile("v_and_or_b32 %0, %1, %2, %3" : "=v"(v) : "v"(a), "s"(mask), "v"(c));
+    return v;
+}
+__device__ __forceinline__ void dot2_ordered(float& d, uint32_t pair, half2v xv) {
+    asm volatile("v_dot2_f32_f16 %0, %1, %2, %0" : "+v"(d) : "v"(pair), "v"(xv));
+}
+
+// acc[rr] += scale * (sum (2^b + code) x - (2^b + zero) sum x) over this lane's 32 columns, for four rows
+template <int BITS>
+__device__ __forceinline__ void mv_dot_rows(const uint32_t (&w)[MV2_HALF][BITS + 1], const half2v (&xq)[16], float sx, float* acc,
+                                            const PackedArgs& a, int64_t rowbase, int64_t g0) {
     constexpr int WANT = 10 - BITS;
     constexpr uint32_t M = (1u << BITS) - 1u;
     constexpr uint32_t MASK_LO = M << WANT, MASK_HI = M << (16 + WANT), MASK = MASK_LO | MASK_HI;
     const uint32_t magic = 0x3C003C00u + (uint32_t)BITS * 0x04000400u;       // (2^b, 2^b) as two halves
     const float offset = (float)(1 << BITS);
+#pragma unroll
+    for (int rr = 0; rr < MV2_HALF; ++rr) {
+        // two interleaved chains per row, so consecutive dot products do not wait for each other
+        float d0 = 0.f, d1 = 0.f;
+        uint32_t joined[3] = {0u, 0u, 0u};
+        if constexpr (BITS == 3) {
+            joined[0] = __builtin_amdgcn_perm(w[rr][1], w[rr][0], 0x07060100u);      // low half of w0, high half of w1
+            joined[1] = __builtin_amdgcn_perm(w[rr][0], w[rr][2], 0x07060100u);      // low half of w2, high half of w0
+            joined[2] = __builtin_amdgcn_perm(w[rr][2], w[rr][1], 0x07060100u);      // low half of w1, high half of w2
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const PairSpec sp = PairTable<BITS>::at(i);
+            uint32_t v;
+            if (sp.lo_word < 0) {
+                const uint32_t ta = stream_bits<BITS>(w[rr], BITS * sp.k_lo - WANT);
+                const uint32_t tb = stream_bits<BITS>(w[rr], BITS * sp.k_hi - (16 + WANT));
+                v = and_or_ordered(tb, MASK_HI, and_or_ordered(ta, MASK_LO, magic));
+            } else {
+                uint32_t m;
+                if (sp.lo_word == sp.hi_word) m = w[rr][sp.lo_word];
+                else m = joined[sp.lo_word == 0 ? 0 : (sp.lo_word == 2 ? 1 : 2)];
+                const uint32_t t = sp.rel >= WANT ? (m >> (sp.rel - WANT)) : (m << (WANT - sp.rel));
+                v = and_or_ordered(t, MASK, magic);
+            }
+            if (i & 1) dot2_ordered(d1, v, xq[i]);
+            else       dot2_ordered(d0, v, xq[i]);
+        }
+        const int64_t gi = min(rowbase + rr, a.r - 1) * a.ngroups + g0;
+        acc[rr] = fmaf(a.scales[gi], (d0 + d1) - (offset + (float)a.zeros[gi]) * sx, acc[rr]);
+    }
+}
+
+// The words of the next four rows are requested before the current four are multiplied (within a segment, and across to
+// the wavefront's next segment), so a wavefront always has loads in flight while it computes.
+template <int BITS>
+__global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __half* x, float* y) {
+    __shared__ float part[4][MV2_ROWS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t nseg = (a.n + MV_SEG - 1) / MV_SEG;
     const int64_t row_end = min(((int64_t)blockIdx.x + 1) * a.rows_per_wg, a.r);
     for (int64_t row0 = (int64_t)blockIdx.x * a.rows_per_wg; row0 < row_end; row0 += MV2_ROWS) {
     float acc[MV2_ROWS];
 #pragma unroll
     for (int rr = 0; rr < MV2_ROWS; ++rr) acc[rr] = 0.f;
+    uint32_t wa[MV2_HALF][BITS + 1], wb[MV2_HALF][BITS + 1];
+    const int64_t wlast = a.words_per_row - BITS;            // n is a multiple of 32 and at least 32
+    auto words_at = [&](int64_t seg) { return min(((seg * MV_SEG + (int64_t)lane * 32) >> 5) * BITS, wlast); };
+    if (wave < nseg) mv_load_rows<BITS>(wa, a, row0, words_at(wave));
+#pragma unroll 1
     for (int64_t s = wave; s < nseg; s += 4) {
-        const int64_t k0 = s * MV_SEG + (int64_t)lane * 32;
-        if (k0 >= a.n) continue;
+        const int64_t k0 = s * MV_SEG + (int64_t)lane * 32;      // lanes past the last column: any words, zero vector entries
+        mv_load_rows<BITS>(wb, a, row0 + MV2_HALF, words_at(s));
         uint32_t xp[16];                                     // the lane's 32 vector entries, two halves per register
-        if (k0 + 32 <= a.n && (reinterpret_cast<uintptr_t>(x + k0) & 15) == 0) {
+        {
+            const bool inside = k0 < a.n;
+            const __half* xsrc = x + min(k0, a.n - 32);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint4 u = reinterpret_cast<const uint4*>(x + k0)[q];
-                xp[4 * q] = u.x; xp[4 * q + 1] = u.y; xp[4 * q + 2] = u.z; xp[4 * q + 3] = u.w;
-            }
-        } else {
-            const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t lo = (k0 + 2 * i < a.n) ? xb[k0 + 2 * i] : 0u;
-                const uint32_t hi = (k0 + 2 * i + 1 < a.n) ? xb[k0 + 2 * i + 1] : 0u;
-                xp[i] = lo | (hi << 16);                     // columns past n contribute nothing
+                const uint4 u = reinterpret_cast<const uint4*>(xsrc)[q];
+                xp[4 * q] = inside ? u.x : 0u; xp[4 * q + 1] = inside ? u.y : 0u; xp[4 * q + 2] = inside ? u.z : 0u; xp[4 * q + 3] = inside ? u.w : 0u;
             }
         }
+        asm volatile("" ::: "memory");                       // the requests above stay above the arithmetic below
         float sx = 0.f;
         half2v xq[16];                                       // the same entries paired like the codes
 #pragma unroll
@@ -380,56 +448,13 @@ __global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __
             const uint32_t hi = (sp.k_hi & 1) ? (xp[sp.k_hi >> 1] & 0xFFFF0000u) : (xp[sp.k_hi >> 1] << 16);
             xq[i] = __builtin_bit_cast(half2v, lo | hi);
         }
-        const int64_t w0 = (k0 >> 5) * BITS;
-        const int64_t g0 = a.group ? k0 / a.group : 0;
-        uint32_t w[MV2_ROWS][BITS + 1];
-        int64_t gi[MV2_ROWS];
-#pragma unroll
-        for (int rr = 0; rr < MV2_ROWS; ++rr) {
-            const int64_t row = min(row0 + rr, a.r - 1);     // rows past r repeat the last one and are dropped below
-            const uint32_t* p = a.words + row * a.ldp + w0;
-            if (w0 + BITS <= a.words_per_row) {              // the usual case: one load of b words (4-byte aligned)
-                struct __attribute__((packed, aligned(4))) Words { uint32_t v[BITS]; };
-                const Words t = *reinterpret_cast<const Words*>(p);
-#pragma unroll
-                for (int i = 0; i < BITS; ++i) w[rr][i] = t.v[i];
-            } else {
-#pragma unroll
-                for (int i = 0; i < BITS; ++i) w[rr][i] = (w0 + i < a.words_per_row) ? p[i] : 0u;
-            }
-            w[rr][BITS] = 0u;
-            gi[rr] = row * a.ngroups + g0;
-        }
-#pragma unroll
-        for (int rr = 0; rr < MV2_ROWS; ++rr) {
-            // two interleaved chains per row, so consecutive dot products do not wait for each other
-            float d0 = 0.f, d1 = 0.f;
-            uint32_t joined[3] = {0u, 0u, 0u};
-            if constexpr (BITS == 3) {
-                joined[0] = __builtin_amdgcn_perm(w[rr][1], w[rr][0], 0x07060100u);      // low half of w0, high half of w1
-                joined[1] = __builtin_amdgcn_perm(w[rr][0], w[rr][2], 0x07060100u);      // low half of w2, high half of w0
-                joined[2] = __builtin_amdgcn_perm(w[rr][2], w[rr][1], 0x07060100u);      // low half of w1, high half of w2
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const PairSpec sp = PairTable<BITS>::at(i);
-                uint32_t v;
-                if (sp.lo_word < 0) {
-                    const uint32_t ta = stream_bits<BITS>(w[rr], BITS * sp.k_lo - WANT);
-                    const uint32_t tb = stream_bits<BITS>(w[rr], BITS * sp.k_hi - (16 + WANT));
-                    v = and_or(tb, MASK_HI, and_or(ta, MASK_LO, magic));
-                } else {
-                    uint32_t m;
-                    if (sp.lo_word == sp.hi_word) m = w[rr][sp.lo_word];
-                    else m = joined[sp.lo_word == 0 ? 0 : (sp.lo_word == 2 ? 1 : 2)];
-                    const uint32_t t = sp.rel >= WANT ? (m >> (sp.rel - WANT)) : (m << (WANT - sp.rel));
-                    v = and_or(t, MASK, magic);
-                }
-                if (i & 1) d1 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, v), xq[i], d1, false);
-                else       d0 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, v), xq[i], d0, false);
-            }
-            acc[rr] = fmaf(a.scales[gi[rr]], (d0 + d1) - (offset + (float)a.zeros[gi[rr]]) * sx, acc[rr]);
-        }
+        // column / group size without the 64-bit division (n < 2^31 is checked on the host)
+        const uint32_t kc = (uint32_t)min(k0, a.n - 32);
+        const int64_t g0 = a.group == 0 ? 0 : (int64_t)(a.gshift >= 0 ? kc >> a.gshift : kc / (uint32_t)a.group);
+        mv_dot_rows<BITS>(wa, xq, sx, acc, a, row0, g0);
+        if (s + 4 < nseg) mv_load_rows<BITS>(wa, a, row0, words_at(s + 4));
+        asm volatile("" ::: "memory");
+        mv_dot_rows<BITS>(wb, xq, sx, acc + MV2_HALF, a, row0 + MV2_HALF, g0);
     }
 #pragma unroll
     for (int rr = 0; rr < MV2_ROWS; ++rr) {
@@ -523,7 +548,8 @@ template <int BITS, typename XT>
 static void launch_matvec(PackedArgs a, const XT* x, float* y, hipStream_t s) {
     const int gsub = (a.group == 0 || a.group % 32 == 0) ? 1 : (int)(32 / a.group);
     if constexpr (sizeof(XT) == 2) {
-        if (gsub == 1) {
+        // the fast kernel wants whole lanes (32 columns each) and 16-byte loads of the vector
+        if (gsub == 1 && a.n % 32 == 0 && a.n >= 32 && a.n < 0x7fffffffLL && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
             a.rows_per_wg = rows_per_workgroup(a.r, MV2_ROWS);
             hipLaunchKernelGGL((matvec_dot2_kernel<BITS>), dim3((unsigned)ceil_div(a.r, a.rows_per_wg)), dim3(256), 0, s, a, x, y);
             return;

@@ -72,6 +72,12 @@ def test_consumers_match_oracle(bits, group, r, n, ternary):
         err = np.abs(y.double().cpu().numpy() - want)
         _say(f"  matvec {dt}: max err / bound = {(err / bound).max():.3f}")
         assert np.all(err <= bound)
+        if dt == torch.float16:             # a vector that does not start on a 16-byte boundary: same result
+            xo = torch.empty(n + 1, dtype=dt, device="cuda")[1:]
+            xo.copy_(x)
+            y2 = torch.full((r,), 5.0, dtype=torch.float32, device="cuda")
+            g.gptq_matvec_packed(wd, n, bits, sd, zd, group, xo, y2)
+            assert np.all(np.abs(y2.double().cpu().numpy() - want) <= bound)
 
 
 def test_consumers_after_the_solver():
