@@ -12,7 +12,8 @@ A column k > j that is still waiting holds w_k + delta_k with the deltas of colu
 same conditions, delta_k = (S_k - sum_{j<=i<k} delta_i R_ik) / R_kk with S_k = sum_{i<j} d_i R_ik: this is what a
 group grid taken "from the current weights" at column j sees (groups inside a block).
 The float64 emulation below follows that recurrence with lazy blocks and must give the oracle's codes, grids
-and errors."""
+and errors.  A second emulation follows the arrangement the GPU kernels use for groups inside a block (the whole
+block's weights rebuilt at once through the inverse of the block's diagonal part of R) to the same bar."""
 import numpy as np
 import pytest
 
@@ -67,4 +68,50 @@ def test_factor_form_equals_algorithm_1(bits, grid, group, n):
     got = factor_form_quantize(W, R, bits, grid, 128, group)
     assert np.array_equal(got["codes"], want["codes"])
     assert np.array_equal(got["zero"], want["zero"]) and np.allclose(got["scale"], want["scale"], rtol=1e-12)
+    assert np.allclose(got["E"], want["E"], rtol=1e-6, atol=1e-9 * np.abs(want["E"]).max())
+
+
+def block_form_quantize(W, R, bits, grid, group, block=128):
+    """The arrangement quant_block_hybrid_kernel uses for groups inside a block: at a block start the working weights
+    are w + s R_bb^-1 (the conditions (delta R)_k = 0 over the whole block), the block is then walked as Alg. 1 walks
+    it, on U's diagonal block R_bb^-1, and hands d = w - q to the accumulators of the later columns."""
+    W = np.asarray(W, dtype=np.float64)
+    r, n = W.shape
+    S = np.zeros((r, n))
+    maxq = O.grid_maxq(bits, grid)
+    codes = np.zeros((r, n), dtype=np.int64)
+    ng = n // group
+    scales, zeros = np.zeros((r, ng)), np.zeros((r, ng), dtype=np.int64)
+    E = np.zeros((r, n))
+    for i in range(0, n, block):
+        iend = min(i + block, n)
+        Ub = np.linalg.inv(R[i:iend, i:iend])
+        Wb = W[:, i:iend] + S[:, i:iend] @ Ub                # the block's weights as they stand now
+        D = np.zeros((r, iend - i))
+        for j in range(i, iend):
+            c = j - i
+            if j % group == 0:
+                scale, zero = O.grid_params(Wb[:, c:c + group], bits, grid)
+                scales[:, j // group], zeros[:, j // group] = scale, zero
+            codes[:, j] = O.quant_codes(Wb[:, c], scale, zero, maxq)
+            q = O.dequant(codes[:, j], scale, zero)
+            E[:, j] = (Wb[:, c] - q) / Ub[c, c]
+            Wb[:, c + 1:] -= np.outer(E[:, j], Ub[c, c + 1:])
+            D[:, c] = W[:, j] - q
+        S[:, iend:] += D @ R[i:iend, iend:]
+    return dict(codes=codes, scale=scales, zero=zeros, E=E)
+
+
+@pytest.mark.parametrize("bits,grid,group,n", [(4, "minmax", 32, 416), (2, "minmax", 128, 384), (2, "ternary", 64, 320)])
+def test_block_form_with_group_grids_equals_algorithm_1(bits, grid, group, n):
+    rng = np.random.default_rng(7 * n + bits)
+    X = rng.normal(size=(n, 6 * n)) * np.exp(0.5 * rng.normal(size=(n, 1))) + 0.4 * rng.normal(size=(1, 6 * n))
+    W = (rng.normal(size=(24, n)) * 0.02).astype(np.float16).astype(np.float64)
+    Hd = O.damp(O.hessian(X))
+    U = O.hinv_cholesky_upper(Hd)
+    R = np.linalg.cholesky(Hd[::-1, ::-1])[::-1, ::-1]
+    want = O.gptq_quantize(W, U, bits, grid, 128, group)
+    got = block_form_quantize(W, R, bits, grid, group)
+    assert np.array_equal(got["codes"], want["codes"])
+    assert np.array_equal(got["zero"], want["zero"]) and np.allclose(got["scale"], want["scale"], rtol=1e-10)
     assert np.allclose(got["E"], want["E"], rtol=1e-6, atol=1e-9 * np.abs(want["E"]).max())
