@@ -44,8 +44,8 @@ def parse():
                          "bloom176b_out_ternary_g128 | opt175b_q | tiny | opt175b_block (all six linears of a block)")
     ap.add_argument("--tokens", type=int, default=0, help="calibration tokens (default: the layer's own, 262144)")
     ap.add_argument("--chunk", type=int, default=0,
-                    help="tokens per gptq_hessian_accumulate call (default: 32768; all tokens at once for layers of up to "
-                         "6144 input channels, whose few tiles make the library split the token range of a call)")
+                    help="tokens per gptq_hessian_accumulate call (default: all of them in one call; the library splits the token "
+                         "range of matrices with few tiles and walks long calls on large matrices in slices of 32768)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--form", choices=["auto", "factor", "inverse"], default="auto",
                     help="steps 2 and 3.  factor: gptq_damp_cholesky + gptq_quantize_layer_from_factor (Alg. 1 driven by the Cholesky "
@@ -145,7 +145,7 @@ def bench_block(a):
                 W[r0:r0 + rows] = lay.weights(row0=r0, nrows=min(rows, lay.r - r0), device=dev)
             members.append((lay.name, W, lay))
         groups.append((X, members))
-    chunk = min(a.chunk or 32768, m)
+    chunk = min(a.chunk or m, m)
     form = "auto" if a.form == "auto" else a.form
     runs = {}
     for bits in (3, 4):
@@ -212,7 +212,8 @@ class LayerBench:
         self.pbits = 2 if lay.grid == "ternary" else lay.bits
         self.packed = torch.empty((r, g.packed_words_per_row(n, self.pbits)), dtype=torch.int32, device=dev)
         self.grid = g.GPTQ_GRID_TERNARY if lay.grid == "ternary" else g.GPTQ_GRID_MINMAX
-        self.chunk = min(chunk_arg or (m if n <= 6144 else 32768), m)
+        # one call over all tokens: the library splits short matrices' token range and walks long ones slice by slice
+        self.chunk = min(chunk_arg or m, m)
         self.chunks = [(c0, min(c0 + self.chunk, m)) for c0 in range(0, m, self.chunk)]
         h_bytes = g.gptq_hessian_accumulate_workspace_bytes(n, self.chunk, lay.x.dtype)
         self.h_ws = torch.empty(h_bytes, dtype=torch.uint8, device=dev) if h_bytes else None
@@ -312,9 +313,11 @@ def main():
     chunk = lb.chunk
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    syrk_ms = [e0.elapsed_time(e1) for (e0, e1, _) in lb.syrk_events]
-    syrk_avg_ms = sum(syrk_ms) / len(syrk_ms)
-    syrk_flops_per_launch = sum(float(n) * (n + 1) * t for (_, _, t) in lb.syrk_events) / len(lb.syrk_events)
+    # per launch of the SYRK kernel: a call's event time over the launches the library says the call makes
+    launches = sum(g.gptq_hessian_accumulate_launches(n, t, lay.x.dtype) for (_, _, t) in lb.syrk_events)
+    syrk_avg_ms = sum(e0.elapsed_time(e1) for (e0, e1, _) in lb.syrk_events) / launches
+    syrk_flops_per_launch = sum(float(n) * (n + 1) * t for (_, _, t) in lb.syrk_events) / launches
+    tokens_per_launch = int(round(sum(t for (_, _, t) in lb.syrk_events) / launches))
     achieved = syrk_flops_per_launch / (syrk_avg_ms * 1e-3) / 1e12
     if factor_form:
         flops = dict(flops, tri_inverse=0.0)            # this form has no triangular inverse: not counted
@@ -359,7 +362,7 @@ def main():
                 "traffic": None}
         del Wt, Et, Ut
 
-    traffic = MEASURED_SYRK_TRAFFIC.get((n, chunk)) if lay.x.dtype != torch.float32 else None
+    traffic = MEASURED_SYRK_TRAFFIC.get((n, tokens_per_launch)) if lay.x.dtype != torch.float32 else None
     out = {
         "metric": "gptq_layer_solve_tflops", "value": total_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -381,7 +384,9 @@ def main():
                              "matvec_frac_of_hbm_peak": mv_bytes / (mv_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                              "dequantize_f16_ms": dq_ms, "dequantize_GBps": dq_bytes / (dq_ms * 1e-3) / 1e9,
                              "dequantize_frac_of_hbm_peak": dq_bytes / (dq_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
-        "roofline": {"kernel": "syrk_f16_dma_kernel (one gptq_hessian_accumulate call; the events also span its ~1.4 ms repack_kernel)",
+        "roofline": {"kernel": "syrk_f16_dma_kernel (HIP events around a gptq_hessian_accumulate call, divided by the launches of the kernel "
+                               "the call makes; a launch repacks the next slice of the token range in its tail)",
+                     "launches_per_call": launches // len(lb.syrk_events), "tokens_per_launch": tokens_per_launch,
                      "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_F16_MFMA_TFLOPS,
                      "avg_launch_ms": syrk_avg_ms, "flops_per_launch": syrk_flops_per_launch,

@@ -70,12 +70,20 @@ GPTQ_API const char* gptq_last_error(void);
  *       parts whose partial tiles (held in the workspace) are added in a fixed order, so that all CUs have
  *       work -- pass such layers long chunks, whole calibration sets if they fit.  Without the workspace
  *       the kernels read X in place: the same sums up to float32 summation order, at lower speed.
+ *       Calls of more than 32768 tokens on layers whose H fills the chip without that split (from ~11000 channels
+ *       on) walk the token range in slices of 32768: the workspace then holds two repacked slices, and every slice
+ *       but the first is repacked inside the preceding slice's matrix-core kernel by the workgroups that have run
+ *       out of tiles, so the repack costs no pass of its own -- pass such layers whole calibration sets too.
+ *       gptq_hessian_accumulate_launches(n, t, xdtype) tells how many launches of the matrix-core kernel a call
+ *       makes (1 unless it is sliced).  The environment variable GPTQ_HESSIAN_SLICE_TOKENS (a multiple of 32), read
+ *       at every call, changes the slice length and makes every 16-bit call longer than a slice take this path.
  *       Repeating a call gives the same bits either way.  The size is 0 where the workspace is not used (ws is
  *       then ignored).  A non-NULL ws that is misaligned or smaller than that size is GPTQ_ERR_WORKSPACE.
  *   No normalisation by the token count is applied (the quantization result is invariant to the
  *   scale of H).  n == 0 or t == 0 is a valid no-op.
  */
 GPTQ_API size_t gptq_hessian_accumulate_workspace_bytes(int64_t n, int64_t t, int xdtype);
+GPTQ_API int64_t gptq_hessian_accumulate_launches(int64_t n, int64_t t, int xdtype);
 GPTQ_API int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int xdtype,
                             int64_t n, int64_t t, int64_t ldx, void* ws, size_t ws_bytes, void* stream);
 

@@ -48,6 +48,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_hessian_accumulate.argtypes = [vp, i64, vp, ci, i64, i64, i64, vp, sz, vp]
     L.gptq_hessian_accumulate_workspace_bytes.argtypes = [i64, i64, ci]
     L.gptq_hessian_accumulate_workspace_bytes.restype = sz
+    L.gptq_hessian_accumulate_launches.argtypes = [i64, i64, ci]
+    L.gptq_hessian_accumulate_launches.restype = i64
     L.gptq_hessian_symmetrize.argtypes = [vp, i64, i64, vp]
     L.gptq_hessian_accumulate_token_major.argtypes = [vp, i64, vp, ci, i64, i64, i64, vp, sz, vp]
     L.gptq_hessian_accumulate_token_major_workspace_bytes.argtypes = [i64, i64, ci]
@@ -121,6 +123,11 @@ def packed_words_per_row(n: int, bits: int) -> int:
 
 def gptq_hessian_accumulate_workspace_bytes(n: int, t: int, dtype: torch.dtype = torch.float16) -> int:
     return lib().gptq_hessian_accumulate_workspace_bytes(n, t, _DTYPE[dtype])
+
+
+def gptq_hessian_accumulate_launches(n: int, t: int, dtype: torch.dtype = torch.float16) -> int:
+    """Launches of the matrix-core kernel one gptq_hessian_accumulate call of t tokens makes (1 unless it is sliced)."""
+    return int(lib().gptq_hessian_accumulate_launches(n, t, _DTYPE[dtype]))
 
 
 def gptq_hessian_accumulate(H: torch.Tensor, X: torch.Tensor, ws: torch.Tensor | None = None) -> None:

@@ -70,6 +70,15 @@ struct SyrkArgs {
     int64_t spp;                // steps per split (a multiple of 5)
     int64_t items;              // total * splits
     float* P;                   // [items][256][256] partial tiles, or null
+    // Long calls go through the kernel in slices of the token range (launch_syrk_sliced): while the last of its
+    // workgroups still multiply, those that have run out of tiles repack the NEXT slice (next_items > 0), so only
+    // the first slice's repack is a pass of its own.
+    const uint16_t* next_X;     // first token of the next slice
+    int64_t next_t, next_nsteps;
+    unsigned char* next_Xb;     // the other half of the workspace
+    unsigned int* next_counter; // work counter of that repack, zero when the kernel starts
+    unsigned int next_items;    // groups of 16 rows x groups of 512 tokens
+    unsigned int next_tgroups;
 };
 
 template <bool IS_BF16>
@@ -276,6 +285,39 @@ constexpr int DK = 32;                                  // tokens per stage
 constexpr int DSTAGE = 2 * 256 * DK * 2;                // bytes per stage: A panel + B panel
 constexpr int DMA_TOKENS = 5 * DK;                      // tokens per trip of the 5-stage loop
 
+// The same repack by one wavefront: 16 rows x 512 tokens per work item (16 loads in flight per lane, then 16 stores),
+// items handed out by an atomic counter.  Every wavefront that calls this leaves when the counter has passed the last
+// item; nobody waits for anybody.
+__device__ __forceinline__ void repack_tail(const SyrkArgs& g, int lane) {
+    if (g.next_items == 0) return;
+    for (;;) {
+        unsigned int item = 0;
+        if (lane == 0) item = atomicAdd(g.next_counter, 1u);
+        item = (unsigned int)__builtin_amdgcn_readfirstlane((int)item);
+        if (item >= g.next_items) return;
+        const int64_t rg = item / g.next_tgroups, tg = item % g.next_tgroups;
+        const int64_t step = tg * 16 + (lane >> 2);
+        if (step < g.next_nsteps) {                          // else this lane's 32 tokens lie past the padded slice
+            const int64_t tok = step * 32 + (lane & 3) * 8;
+            uint4 v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int64_t row = rg * 16 + i;
+                v[i] = make_uint4(0, 0, 0, 0);
+                if (row < g.n) v[i] = load8h_guard(g.next_X + row * g.ldx + tok, g.next_t - tok);
+            }
+            // rows rg*16 .. rg*16+15 lie in one panel (16 divides 256)
+            unsigned char* base = g.next_Xb + (((rg * 16) >> 8) * g.next_nsteps + step) * 16384;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = (int)((rg * 16 + i) & 255);
+                const int pos = (lane & 3) ^ ((r >> 2) & 3);
+                *reinterpret_cast<uint4*>(base + r * 64 + pos * 16) = v[i];
+            }
+        }
+    }
+}
+
 template <bool IS_BF16, bool BLOCKED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void syrk_f16_dma_kernel(SyrkArgs g) {
     constexpr int BT = 256;
@@ -299,7 +341,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int64_t xcd = w % NXCD, slot_step = gridDim.x / NXCD;
     int64_t slot = w / NXCD;
     auto tile_at = [&](int64_t sl) { return ((sl / 32) * NXCD + xcd) * 32 + (sl % 32); };
-    if (tile_at(slot) >= g.items) return;
+    if (tile_at(slot) >= g.items) {
+        if (BLOCKED) repack_tail(g, threadIdx.x & 63);
+        return;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -486,6 +531,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
         if (!more) break;
     }
+    if (BLOCKED) repack_tail(g, lane);
 }
 
 // H tile += 2 * (P[0] + P[1] + ... + P[splits-1]), the partial tiles of one tile in the order of their token
@@ -578,6 +624,90 @@ static int launch_syrk_dma(SyrkArgs g, void* ws, hipStream_t s, bool token_major
     return GPTQ_OK;
 }
 
+// ---- long calls: the token range in slices, the repack of slice i + 1 inside the kernel of slice i ---------------
+// A call with more tokens than one slice goes through the direct-to-LDS kernel slice by slice (the workspace holds two
+// repacked slices).  Only the first slice is repacked by a kernel of its own; every later one is repacked by the
+// workgroups of the preceding slice's kernel as they run out of tiles (repack_tail), which otherwise sit idle until
+// the last workgroup of the launch is through -- 8 % of the launch at n = 12288 (1176 tiles on 256 CUs), about what
+// the repack costs.  Taken when one slice alone fills the chip without splitting its token range.
+constexpr int64_t SLICE_TOKENS = 32768;
+constexpr int MAX_SLICES = 64;
+
+static int64_t slice_tokens() {
+    // GPTQ_HESSIAN_SLICE_TOKENS: tokens per slice of a long call (a multiple of 32; default 32768).  Setting it also
+    // makes every 16-bit call that is longer than a slice take this path, whatever the matrix size.
+    // Read at every call (the workspace query and the call itself must see the same value).
+    const char* e = getenv("GPTQ_HESSIAN_SLICE_TOKENS");
+    const int64_t x = e ? atoll(e) : 0;
+    return (x >= 32 && x % 32 == 0) ? x : 0;
+}
+
+static bool syrk_sliced(int64_t n, int64_t t) {
+    const int64_t forced = slice_tokens();
+    const int64_t slice = forced ? forced : SLICE_TOKENS;
+    if (t <= slice || ceil_div(t, slice) > MAX_SLICES) return false;
+    return forced != 0 || (n > 6144 && syrk_plan(n, slice).splits == 1);
+}
+
+static int64_t padded_steps(int64_t tokens) { return ceil_div(ceil_div(tokens, DK), 5) * 5; }
+
+static size_t syrk_sliced_ws_bytes(int64_t n) {
+    const int64_t slice = slice_tokens() ? slice_tokens() : SLICE_TOKENS;
+    const size_t one = round_up((size_t)ceil_div(n, 256) * 256 * (size_t)padded_steps(slice) * DK * 2, 256);
+    return 2 * one + 256;
+}
+
+__global__ void zero_counters_kernel(unsigned int* c, int count) {
+    if ((int)threadIdx.x < count) c[threadIdx.x] = 0u;
+}
+
+template <bool IS_BF16>
+static int launch_syrk_sliced(SyrkArgs g, void* ws, hipStream_t s) {
+    const int64_t slice = slice_tokens() ? slice_tokens() : SLICE_TOKENS;
+    const int64_t nslices = ceil_div(g.t, slice);
+    syrk_schedule(g, 256);
+    const size_t one = round_up((size_t)g.nt * 256 * (size_t)padded_steps(slice) * DK * 2, 256);
+    unsigned char* buf[2] = {static_cast<unsigned char*>(ws), static_cast<unsigned char*>(ws) + one};
+    unsigned int* counters = reinterpret_cast<unsigned int*>(static_cast<unsigned char*>(ws) + 2 * one);
+    g.splits = 1; g.P = nullptr;
+    g.items = g.total;
+    g.per_xcd = ceil_div(ceil_div(g.items, 32), NXCD) * 32;
+    if (g.per_xcd * NXCD > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "hessian: too many tiles");
+    const int64_t blocks = std::min<int64_t>(g.per_xcd, 32) * NXCD;
+    const uint16_t* X0 = g.X;
+    const int64_t t_all = g.t;
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(MAX_SLICES), 0, s, counters, MAX_SLICES);
+    GPTQ_LAUNCH_CHECK();
+    {
+        const int64_t t0 = std::min<int64_t>(slice, t_all), ns0 = padded_steps(t0);
+        hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(g.nt * 16), (unsigned)ceil_div(ns0, 16)), dim3(256), 0, s, X0, g.ldx, g.n, t0, ns0, buf[0]);
+        GPTQ_LAUNCH_CHECK();
+    }
+    for (int64_t i = 0; i < nslices; ++i) {
+        const int64_t ti = std::min<int64_t>(slice, t_all - i * slice);
+        SyrkArgs a = g;
+        a.X = X0 + i * slice;
+        a.Xb = buf[i & 1];
+        a.nsteps = padded_steps(ti);
+        a.spp = a.nsteps;
+        a.t = a.nsteps * DK;
+        a.next_items = 0;
+        if (i + 1 < nslices) {
+            const int64_t tn = std::min<int64_t>(slice, t_all - (i + 1) * slice);
+            a.next_X = X0 + (i + 1) * slice;
+            a.next_t = tn;
+            a.next_nsteps = padded_steps(tn);
+            a.next_Xb = buf[(i + 1) & 1];
+            a.next_counter = counters + i;
+            a.next_tgroups = (unsigned int)ceil_div(a.next_nsteps, 16);
+            a.next_items = (unsigned int)(g.nt * 16) * a.next_tgroups;
+        }
+        hipLaunchKernelGGL((syrk_f16_dma_kernel<IS_BF16, true>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+        GPTQ_LAUNCH_CHECK();
+    }
+    return GPTQ_OK;
+}
+
 template <bool IS_BF16, int BT, int WM, int WN>
 static int launch_syrk(SyrkArgs g, hipStream_t s) {
     g.nt = (int)ceil_div(g.n, BT);
@@ -618,6 +748,7 @@ constexpr int64_t SYRK_DMA_MIN_N = 2048;        // below this even a split token
 
 static size_t syrk_ws_bytes(int64_t n, int64_t t, int xdtype) {
     if (xdtype == GPTQ_F32 || n < SYRK_DMA_MIN_N) return 0;
+    if (syrk_sliced(n, t)) return syrk_sliced_ws_bytes(n);
     const SyrkPlan p = syrk_plan(n, t);
     if (n <= 6144 && p.splits == 1) return 0;       // too few tokens to split: the 128-tile kernel does better
     return p.repack_bytes + p.partial_bytes;
@@ -626,6 +757,13 @@ static size_t syrk_ws_bytes(int64_t n, int64_t t, int xdtype) {
 extern "C" size_t gptq_hessian_accumulate_workspace_bytes(int64_t n, int64_t t, int xdtype) {
     if (n <= 0 || t <= 0) return 0;
     return syrk_ws_bytes(n, t, xdtype);
+}
+
+extern "C" int64_t gptq_hessian_accumulate_launches(int64_t n, int64_t t, int xdtype) {
+    if (n <= 0 || t <= 0) return 0;
+    if (xdtype == GPTQ_F32 || n < SYRK_DMA_MIN_N || !syrk_sliced(n, t)) return 1;
+    const int64_t slice = slice_tokens() ? slice_tokens() : SLICE_TOKENS;
+    return ceil_div(t, slice);
 }
 
 extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int xdtype,
@@ -659,6 +797,8 @@ extern "C" int gptq_hessian_accumulate(float* H, int64_t ldh, const void* X, int
     if (need && ws && (!aligned(ws, 256) || ws_bytes < need))
         return fail(GPTQ_ERR_WORKSPACE, "hessian_accumulate: workspace misaligned or smaller than the %zu bytes this call needs "
                                         "(pass NULL to read X in place)", need);
+    if (need && ws && syrk_sliced(n, t))
+        return bf ? launch_syrk_sliced<true>(g, ws, s) : launch_syrk_sliced<false>(g, ws, s);
     if (need && ws)
         return bf ? launch_syrk_dma<true>(g, ws, s) : launch_syrk_dma<false>(g, ws, s);
     if (n <= 6144)                  // 256-wide tiles only fill the chip when there are enough of them

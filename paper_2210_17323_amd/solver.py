@@ -80,7 +80,7 @@ def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", 
     return LayerResult(codes, scales, zeros, half, Wq, packed)
 
 
-def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bool = False, timings: dict | None = None,
+def solve_block(groups, bits: int | None = None, chunk: int | None = None, want_Wq: bool = False, timings: dict | None = None,
                 factors: dict | None = None, form: str = "auto", overlap: bool = False):
     """The layers of one block, quantized in sequence (Section 4, Setup: a block's inputs are collected, its
     layers quantized, then the next block).  `groups` is a list of (X, layers): X [n x m] are the input
@@ -91,9 +91,11 @@ def solve_block(groups, bits: int | None = None, chunk: int = 32768, want_Wq: bo
     (CUDA events; with overlap the phases of different groups run at the same time, so they do not add up to the
     wall time, which is returned under "total").  If `factors` is a dict it receives {group index: the factor
     each group's layers were quantized with} (otherwise it is freed as soon as the group is done).
+    chunk: tokens per gptq_hessian_accumulate call (None: a group's whole input in one call, which lets the library
+    split or slice the token range itself).
     form: "inverse" factors every group into U = Cholesky((H + lambda I)^-1)^T; "factor" into R with
-    H + lambda I = R R^T and runs Alg. 1 from R (no triangular inverse; per-row grids only); "auto" takes the
-    factor form for the groups whose layers all have per-row grids.
+    H + lambda I = R R^T and runs Alg. 1 from R (no triangular inverse; one grid per row or groups of 32, 64 or 128
+    columns); "auto" takes the factor form for the groups all of whose layers it is offered for.
     overlap: the Hessian of group k+1 is accumulated on a second stream while group k is factored and quantized
     (the factorisation's serial chains leave most of the chip idle)."""
     out = {}

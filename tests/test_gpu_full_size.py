@@ -72,7 +72,7 @@ def test_full_size_sampled_parity(which):
 
     # ---- step 1
     H = S.new_hessian(n)
-    S.accumulate(H, X, chunk=32768)
+    S.accumulate(H, X)                      # one call over all tokens, as bench.py makes it
     torch.cuda.synchronize()
     _say(f"hessian done at {time.time() - t0:.1f}s")
     nb = n // 128
@@ -275,7 +275,7 @@ def test_full_size_decoder_block_3_and_4_bits():
     U_host = {}
     for bits, form in ((3, "inverse"), (4, "factor")):      # 3 bits through U = Cholesky of the inverse, 4 bits through the factor R
         factors, timings = {}, {}
-        res = S.solve_block(groups, bits=bits, chunk=32768, timings=timings, factors=factors, form=form)
+        res = S.solve_block(groups, bits=bits, timings=timings, factors=factors, form=form)
         torch.cuda.synchronize()
         total = timings.pop("total")
         _say(f"{bits}-bit block ({form} form) solved at {time.time() - t0:.1f}s: {total:.0f} ms on the GPU; " +

@@ -89,6 +89,36 @@ def test_hessian_matches_oracle(case):
         assert torch.equal(H3, H2)
 
 
+@pytest.mark.parametrize("n,t,slice_tokens,dtype", [(2304, 4000, 1024, torch.float16), (2100, 3333, 320, torch.bfloat16), (2560, 2100, 2048, torch.float16)])
+def test_hessian_long_call_in_slices_matches_oracle(n, t, slice_tokens, dtype, monkeypatch):
+    # A call longer than one slice walks the token range slice by slice, and every slice but the first is repacked by
+    # the workgroups of the preceding slice's kernel.  The slice length is 32768 tokens and only large matrices take
+    # this path; GPTQ_HESSIAN_SLICE_TOKENS shortens it and opens the path to any size.
+    _say(f"hessian in slices n={n} t={t} slice={slice_tokens} {dtype}")
+    X = _padded(n, t, dtype, 8)                              # rows start on 16-byte boundaries
+    X.copy_(_layer(configs.config3()[1], n, 8, t).x.tile(device="cuda").to(dtype))
+    want = O.hessian(X.double().cpu().numpy())
+    plain = g.gptq_hessian_accumulate_workspace_bytes(n, t, dtype)
+    monkeypatch.setenv("GPTQ_HESSIAN_SLICE_TOKENS", str(slice_tokens))
+    nbytes = g.gptq_hessian_accumulate_workspace_bytes(n, t, dtype)
+    assert nbytes and nbytes != plain
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                          # NaN patterns: every byte that is read must have been written
+    out = []
+    for _ in range(2):                                      # twice: the work counters start at zero in every call
+        H = _padded(n, n, torch.float32, 4)
+        g.gptq_hessian_accumulate(H, X, ws)
+        g.gptq_hessian_symmetrize(H)
+        torch.cuda.synchronize()
+        out.append(H)
+    err = _rel_fro(out[0].double().cpu().numpy(), want)
+    _say(f"  rel_fro={err:.3e}")
+    assert err <= 1e-5
+    assert torch.equal(out[0], out[1])
+    monkeypatch.delenv("GPTQ_HESSIAN_SLICE_TOKENS")
+    assert g.gptq_hessian_accumulate_workspace_bytes(n, t, dtype) == plain
+
+
 @pytest.mark.parametrize("n,t,dtype", [(6416, 2056, torch.float16), (2300, 4000, torch.float16), (320, 1000, torch.float16), (200, 264, torch.bfloat16), (1, 1, torch.float16)])
 def test_hessian_token_major_matches_oracle(n, t, dtype):
     # activations given as [tokens x channels], the layout of a layer input
