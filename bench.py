@@ -28,11 +28,12 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 around the process).  From rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same counter reads
 # for a plain 1 GiB copy kernel (factors 2.000 and 1.000): profiles/layer_solve_opt175b_fc2_pmc_counters.txt.  The fetch
 # reading varies from one collection to the next; the entry is the one tabulated there, the note gives the range seen.
-# Keyed by (n, tokens per call); other shapes: not collected.
-MEASURED_SYRK_TRAFFIC = {(49152, 32768): {"bytes": (6.2966e7 * 2.0 + 6.0244e6 * 1.0) * 1024,
+# Keyed by (n, tokens per launch); other shapes: not collected.
+MEASURED_SYRK_TRAFFIC = {(49152, 32768): {"bytes": (6.4375e7 * 2.0 + 9.1801e6 * 1.0) * 1024,
                                           "note": "stored rocprofv3 reading (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000), not collected in "
-                                                  "this run; seven collections of this launch gave 135-283 GB against 12.9 GB algorithmic "
-                                                  "(X chunk read once, upper triangle of H read and written once)"}}
+                                                  "this run; nine collections of this launch gave 135-283 GB against 12.9 GB algorithmic "
+                                                  "(X slice read once, upper triangle of H read and written once) plus the 6.4 GB of the "
+                                                  "next slice's repack, which the launch does in its tail"}}
 
 
 def parse():
