@@ -341,12 +341,15 @@ constexpr int MV2_HALF = 4;
 // of 32 here, so a lane's words are all inside the row or all outside; `w0` is clamped by the caller for the latter,
 // whose vector entries are zero.
 template <int BITS>
-__device__ __forceinline__ void mv_load_rows(uint32_t (&w)[MV2_HALF][BITS + 1], const PackedArgs& a, int64_t rowbase, int64_t w0) {
+__device__ __forceinline__ void mv_load_rows(uint32_t (&w)[MV2_HALF][BITS + 1], const PackedArgs& a, int rowbase, uint32_t w0) {
 #pragma unroll
     for (int rr = 0; rr < MV2_HALF; ++rr) {
-        const int64_t row = min(rowbase + rr, a.r - 1);
+        // the row is the same for the whole wavefront: its address stays in scalar registers and the load takes the
+        // lane's word offset as a 32-bit index (r and the words of a row fit 31 bits, checked on the host)
+        const int row = __builtin_amdgcn_readfirstlane(min(rowbase + rr, (int)a.r - 1));
+        const uint32_t* prow = a.words + (int64_t)row * a.ldp;
         struct __attribute__((packed, aligned(4))) Words { uint32_t v[BITS]; };
-        const Words t = *reinterpret_cast<const Words*>(a.words + row * a.ldp + w0);      // one load of b words
+        const Words t = *reinterpret_cast<const Words*>(reinterpret_cast<const char*>(prow) + w0 * 4u);      // one load of b words
 #pragma unroll
         for (int i = 0; i < BITS; ++i) w[rr][i] = t.v[i];
         w[rr][BITS] = 0u;
@@ -368,7 +371,7 @@ __device__ __forceinline__ void dot2_ordered(float& d, uint32_t pair, half2v xv)
 // acc[rr] += scale * (sum (2^b + code) x - (2^b + zero) sum x) over this lane's 32 columns, for four rows
 template <int BITS>
 __device__ __forceinline__ void mv_dot_rows(const uint32_t (&w)[MV2_HALF][BITS + 1], const half2v (&xq)[16], float sx, float* acc,
-                                            const PackedArgs& a, int64_t rowbase, int64_t g0) {
+                                            const PackedArgs& a, int rowbase, uint32_t g0) {
     constexpr int WANT = 10 - BITS;
     constexpr uint32_t M = (1u << BITS) - 1u;
     constexpr uint32_t MASK_LO = M << WANT, MASK_HI = M << (16 + WANT), MASK = MASK_LO | MASK_HI;
@@ -402,8 +405,11 @@ __device__ __forceinline__ void mv_dot_rows(const uint32_t (&w)[MV2_HALF][BITS +
             if (i & 1) dot2_ordered(d1, v, xq[i]);
             else       dot2_ordered(d0, v, xq[i]);
         }
-        const int64_t gi = min(rowbase + rr, a.r - 1) * a.ngroups + g0;
-        acc[rr] = fmaf(a.scales[gi], (d0 + d1) - (offset + (float)a.zeros[gi]) * sx, acc[rr]);
+        const int row = __builtin_amdgcn_readfirstlane(min(rowbase + rr, (int)a.r - 1));
+        const int64_t gbase = (int64_t)row * a.ngroups;      // scalar; the lane's group is a 32-bit index on top
+        const float sc = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.scales + gbase) + g0 * 4u);
+        const int zr = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(a.zeros + gbase) + g0 * 4u);
+        acc[rr] = fmaf(sc, (d0 + d1) - (offset + (float)zr) * sx, acc[rr]);
     }
 }
 
@@ -420,13 +426,14 @@ __global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __
 #pragma unroll
     for (int rr = 0; rr < MV2_ROWS; ++rr) acc[rr] = 0.f;
     uint32_t wa[MV2_HALF][BITS + 1], wb[MV2_HALF][BITS + 1];
-    const int64_t wlast = a.words_per_row - BITS;            // n is a multiple of 32 and at least 32
-    auto words_at = [&](int64_t seg) { return min(((seg * MV_SEG + (int64_t)lane * 32) >> 5) * BITS, wlast); };
-    if (wave < nseg) mv_load_rows<BITS>(wa, a, row0, words_at(wave));
+    const uint32_t wlast = (uint32_t)(a.words_per_row - BITS);      // n is a multiple of 32 and at least 32
+    auto words_at = [&](int64_t seg) { return min((uint32_t)(((seg * MV_SEG) >> 5) + lane) * BITS, wlast); };
+    const int row0i = (int)row0;
+    if (wave < nseg) mv_load_rows<BITS>(wa, a, row0i, words_at(wave));
 #pragma unroll 1
     for (int64_t s = wave; s < nseg; s += 4) {
         const int64_t k0 = s * MV_SEG + (int64_t)lane * 32;      // lanes past the last column: any words, zero vector entries
-        mv_load_rows<BITS>(wb, a, row0 + MV2_HALF, words_at(s));
+        mv_load_rows<BITS>(wb, a, row0i + MV2_HALF, words_at(s));
         uint32_t xp[16];                                     // the lane's 32 vector entries, two halves per register
         {
             const bool inside = k0 < a.n;
@@ -450,11 +457,11 @@ __global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __
         }
         // column / group size without the 64-bit division (n < 2^31 is checked on the host)
         const uint32_t kc = (uint32_t)min(k0, a.n - 32);
-        const int64_t g0 = a.group == 0 ? 0 : (int64_t)(a.gshift >= 0 ? kc >> a.gshift : kc / (uint32_t)a.group);
-        mv_dot_rows<BITS>(wa, xq, sx, acc, a, row0, g0);
-        if (s + 4 < nseg) mv_load_rows<BITS>(wa, a, row0, words_at(s + 4));
+        const uint32_t g0 = a.group == 0 ? 0u : (a.gshift >= 0 ? kc >> a.gshift : kc / (uint32_t)a.group);
+        mv_dot_rows<BITS>(wa, xq, sx, acc, a, row0i, g0);
+        if (s + 4 < nseg) mv_load_rows<BITS>(wa, a, row0i, words_at(s + 4));
         asm volatile("" ::: "memory");
-        mv_dot_rows<BITS>(wb, xq, sx, acc + MV2_HALF, a, row0 + MV2_HALF, g0);
+        mv_dot_rows<BITS>(wb, xq, sx, acc + MV2_HALF, a, row0i + MV2_HALF, g0);
     }
 #pragma unroll
     for (int rr = 0; rr < MV2_ROWS; ++rr) {
@@ -549,7 +556,8 @@ static void launch_matvec(PackedArgs a, const XT* x, float* y, hipStream_t s) {
     const int gsub = (a.group == 0 || a.group % 32 == 0) ? 1 : (int)(32 / a.group);
     if constexpr (sizeof(XT) == 2) {
         // the fast kernel wants whole lanes (32 columns each) and 16-byte loads of the vector
-        if (gsub == 1 && a.n % 32 == 0 && a.n >= 32 && a.n < 0x7fffffffLL && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+        if (gsub == 1 && a.n % 32 == 0 && a.n >= 32 && a.n < 0x7fffffffLL && a.r < 0x7fffffffLL && a.words_per_row < 0x3fffffffLL &&
+            a.ngroups < 0x3fffffffLL && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
             a.rows_per_wg = rows_per_workgroup(a.r, MV2_ROWS);
             hipLaunchKernelGGL((matvec_dot2_kernel<BITS>), dim3((unsigned)ceil_div(a.r, a.rows_per_wg)), dim3(256), 0, s, a, x, y);
             return;
