@@ -201,7 +201,9 @@ GPTQ_API int gptq_quantize_layer(const void* W, int wdtype, int64_t ldw, int64_t
  *   its first column (Section 4, "Additional Tricks"), which this form does not hold: at the start of every block
  *   of 128 columns they are rebuilt as w + s R_bb^-1 from the block's accumulators s and the inverse of the block's own
  *   128 x 128 diagonal block of R (the corrections of the waiting columns satisfy delta R_bb = s), and inside the
- *   block Alg. 1 runs on that inverse, which is the diagonal block of U.
+ *   block Alg. 1 runs on that inverse, which is the diagonal block of U.  For these group sizes the workspace also
+ *   holds a copy of R with every column block scaled by that inverse (n x n floats; gptq_quantize_layer_workspace_bytes
+ *   counts it whenever `group` is 32, 64 or 128).
  *   W is read in its own type at every block (it is not copied); the workspace
  *   (gptq_quantize_layer_workspace_bytes) holds the float32 accumulators instead.  All other arguments, outputs
  *   (codes, scales, zeros, Wq, half_E2_rows) and error behaviour as for gptq_quantize_layer.

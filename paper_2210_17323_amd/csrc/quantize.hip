@@ -408,16 +408,17 @@ static bool factor_form_group_supported(int64_t group) { return group == 0 || gr
 
 constexpr int QOB = 1024;   // outer block: trailing updates beyond it are deferred and applied as one rank-1024 GEMM
 
-struct QuantWs { size_t wk, e, cs, t, ub, total; int64_t ldk; };
-static QuantWs quant_ws_layout(int64_t r, int64_t n) {
+struct QuantWs { size_t wk, e, cs, ub, rt, total; int64_t ldk; };
+static QuantWs quant_ws_layout(int64_t r, int64_t n, int64_t group) {
     QuantWs l;
     l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
     l.wk = 0;
     size_t off = round_up((size_t)std::max<int64_t>(r, 1) * l.ldk * sizeof(float), 256);
     l.e = off; off += 2 * round_up((size_t)std::max<int64_t>(r, 1) * QOB * sizeof(float), 256);   // two error panels (look-ahead)
     l.cs = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QB, 256);                        // codes of a block that cannot be stored in place
-    l.t = off; off += round_up((size_t)std::max<int64_t>(r, 1) * QB * sizeof(float), 256);         // factor form with groups: S[:, block] U_bb
-    l.ub = off; off += round_up((size_t)ceil_div(std::max<int64_t>(n, 1), QB) * QB * QB * sizeof(float), 256);   // ... and every U_bb
+    l.ub = off; off += round_up((size_t)ceil_div(std::max<int64_t>(n, 1), QB) * QB * QB * sizeof(float), 256);   // factor form with groups: every U_bb
+    l.rt = off;                                                                                       // ... and R with its column blocks scaled by them
+    if (group != 0 && factor_form_group_supported(group)) off += round_up((size_t)std::max<int64_t>(n, 1) * l.ldk * sizeof(float), 256);
     l.total = off + 256;
     return l;
 }
@@ -441,9 +442,9 @@ extern "C" int gptq_trailing_update(float* W, int64_t ldw, const float* E, int64
 }
 
 extern "C" size_t gptq_quantize_layer_workspace_bytes(int64_t r, int64_t n, int block, int64_t group) {
-    (void)block; (void)group;
+    (void)block;
     if (r < 0 || n < 0) return 0;
-    return quant_ws_layout(r, n).total;
+    return quant_ws_layout(r, n, group).total;
 }
 
 // Both forms of Alg. 1 share validation, blocking and look-ahead.  rf = false: `U` is Cholesky((H + lambda I)^-1)^T,
@@ -473,7 +474,7 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
     if (!W || !U || !codes || !scales || !zeros) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: null pointer");
     if (ldw < n || ldu < n || ldc < n || (Wq && ldq < n)) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: leading dimension smaller than n");
     if (!aligned(U, 16) || ldu % 4) return fail(GPTQ_ERR_INVALID_ARG, "quantize_layer: U must be 16-byte aligned with ldu %% 4 == 0");
-    const QuantWs lay = quant_ws_layout(r, n);
+    const QuantWs lay = quant_ws_layout(r, n, group);
     if (!ws || !aligned(ws, 256) || ws_bytes < lay.total) return fail(GPTQ_ERR_WORKSPACE, "quantize_layer: workspace missing, misaligned or too small");
     if (r > 0x7fffffffLL) return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer: too many rows");
 
@@ -510,10 +511,16 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
     }
     GPTQ_LAUNCH_CHECK();
     const bool hybrid = rf && group != 0;
-    float* Tblk = reinterpret_cast<float*>(base + lay.t);
     float* Ub = reinterpret_cast<float*>(base + lay.ub);
+    // The matrix the deferred updates multiply with: U, R, or -- factor form with groups -- Rt = R with every column block
+    // scaled by the inverse of its diagonal block (made here, once), so that the accumulators of a block hold s R_bb^-1.
+    const float* Bm = U;
+    int64_t ldb = ldu;
     if (hybrid) {
+        float* Rt = reinterpret_cast<float*>(base + lay.rt);
         if (int rc = launch_invert_diag_blocks(U, ldu, n, Ub, s)) return rc;
+        if (int rc = launch_scale_column_blocks(U, ldu, n, Ub, Rt, lay.ldk, s)) return rc;
+        Bm = Rt; ldb = lay.ldk;
     }
 
     const unsigned qblocks = (unsigned)ceil_div(r, 256);
@@ -547,13 +554,8 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
                 GPTQ_LAUNCH_CHECK();
             }
             if (hybrid) {
-                // T = S[:, block] U_bb (U_bb upper triangular: a tile's K range ends at its last column), then the block
-                GemmF32 g{};
-                g.A = Wk + j0; g.lda = lay.ldk; g.B = Ub + (j0 / QB) * QB * QB; g.ldb = QB; g.C = Tblk; g.ldc = QB;
-                g.M = r; g.N = nbk; g.K = nbk; g.alpha = 1.f; g.b_is_nk = false; g.overwrite = true; g.b_upper_tri = true;
-                if (int rc = launch_gemm_f32(g, s)) return rc;
                 HybridArgs h{};
-                h.W = W; h.ldw = ldw; h.T = Tblk; h.Ub = Ub + (j0 / QB) * QB * QB; h.r = r; h.n = n; h.j0 = j0; h.nbk = nbk;
+                h.W = W; h.ldw = ldw; h.T = Wk + j0; h.ldt = lay.ldk; h.Ub = Ub + (j0 / QB) * QB * QB; h.r = r; h.n = n; h.j0 = j0; h.nbk = nbk;
                 h.grid = grid; h.maxq = maxq; h.scales = scales; h.zeros = zeros; h.ngroups = ngroups;
                 h.codes = codes; h.ldc = ldc; h.cstage = reinterpret_cast<uint8_t*>(base + lay.cs);
                 h.D = E + (j0 - o0); h.ldd = QOB; h.half_e2 = half_E2_rows; h.first_block = (j0 == 0);
@@ -587,7 +589,7 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
             GPTQ_LAUNCH_CHECK();
             if (j1 < o1) {
                 GemmF32 g{};
-                g.A = E + (j0 - o0); g.lda = QOB; g.B = U + j0 * ldu + j1; g.ldb = ldu; g.C = Wk + j1; g.ldc = lay.ldk;
+                g.A = E + (j0 - o0); g.lda = QOB; g.B = Bm + j0 * ldb + j1; g.ldb = ldb; g.C = Wk + j1; g.ldc = lay.ldk;
                 g.M = r; g.N = o1 - j1; g.K = nbk; g.alpha = rf ? 1.f : -1.f; g.b_is_nk = false; g.overwrite = false;
                 const int rc = launch_gemm_f32(g, s);
                 if (rc) return rc;
@@ -599,14 +601,14 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
             if (int rc = ts.mark(s, &quantized)) return rc;
             if (int rc = ts.wait(s, rest_done)) return rc;      // it wrote the columns from o1 on
             GemmF32 g{};
-            g.A = E; g.lda = QOB; g.B = U + o0 * ldu + o1; g.ldb = ldu; g.C = Wk + o1; g.ldc = lay.ldk;
+            g.A = E; g.lda = QOB; g.B = Bm + o0 * ldb + o1; g.ldb = ldb; g.C = Wk + o1; g.ldc = lay.ldk;
             g.M = r; g.N = o2 - o1; g.K = o1 - o0; g.alpha = rf ? 1.f : -1.f; g.b_is_nk = false; g.overwrite = false;
             int rc = launch_gemm_f32(g, s);
             if (rc) return rc;
             rest_done = nullptr;
             if (o2 < n) {
                 if ((rc = ts.wait(s2, quantized))) return rc;
-                g.B = U + o0 * ldu + o2; g.C = Wk + o2; g.N = n - o2;
+                g.B = Bm + o0 * ldb + o2; g.C = Wk + o2; g.N = n - o2;
                 rc = launch_gemm_f32(g, s2);
                 if (rc) return rc;
                 if ((rc = ts.mark(s2, &rest_done))) return rc;

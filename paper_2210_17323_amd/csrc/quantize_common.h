@@ -162,7 +162,7 @@ __device__ __forceinline__ void stage_diag_block(float* ubs, const float* M, int
 // ---- the factor form with grids taken inside a block: arguments and launchers (quantize_groups.hip) ----
 struct HybridArgs {
     const void* W; int64_t ldw;     // original weights, type WT
-    const float* T;                 // [r x 128]: S[:, block] U_bb
+    const float* T; int64_t ldt;    // this block's 128 columns of the accumulators, which hold S[:, block] U_bb
     const float* Ub;                // U_bb, dense 128 x 128 (identity outside a short last block)
     int64_t r, n, j0; int nbk;
     int grid; int maxq;
@@ -178,5 +178,8 @@ struct HybridArgs {
 int launch_quant_block_hybrid(int64_t group, int wdtype, unsigned workgroups, const HybridArgs& h, hipStream_t s);
 // Ub[b] = R_bb^-1 for every 128 x 128 diagonal block of R (dense, identity outside a short last block).
 int launch_invert_diag_blocks(const float* R, int64_t ldr, int64_t n, float* Ub, hipStream_t s);
+// Rt[0:j0, block] = R[0:j0, block] U_bb for every column block (the part above the diagonal blocks; the rest of Rt is
+// not written).
+int launch_scale_column_blocks(const float* R, int64_t ldr, int64_t n, const float* Ub, float* Rt, int64_t ldt, hipStream_t s);
 
 }  // namespace gptq

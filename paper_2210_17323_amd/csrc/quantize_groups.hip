@@ -12,9 +12,11 @@ namespace gptq {
 // inverse of the block's own 128 x 128 diagonal block of R: the corrections delta of the block's waiting columns
 // satisfy delta R_bb = s (the relation of the per-row form, written for every column of the block with the block's
 // earlier columns left at their working values), and inside the block Alg. 1 runs on U's diagonal block, which is
-// that same R_bb^-1 because U = R^-1 is block upper triangular.  The host computes T = S[:, block] U_bb on the
-// matrix cores; this kernel adds the original weights, walks the block like quant_block_kernel on U_bb, and leaves
-// d_j = w_j - q_j (original weight minus grid value) for the deferred updates S[:, later] += D R[block, later].
+// that same R_bb^-1 because U = R^-1 is block upper triangular.  The product s U_bb costs nothing per block: the
+// deferred updates run on Rt = R with every column block scaled by its U_bb (scale_column_blocks_kernel, once per call),
+// so the accumulators hold  sum_i d_i Rt[i][block] = s U_bb  already.  This kernel adds the original weights, walks the
+// block like quant_block_kernel on U_bb, and leaves d_j = w_j - q_j (original weight minus grid value) for the deferred
+// updates S[:, later] += D Rt[block, later].
 template <typename WT>
 struct HybridState {
     WeightRegs<WT> worig;               // original weights of the block
@@ -86,12 +88,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int64_t rr = active ? row : a.r - 1;
     HybridState<WT> st;
     {
-        const float* src = a.T + rr * QB;
+        const float* src = a.T + rr * a.ldt;
         const WT* wsrc = static_cast<const WT*>(a.W) + rr * a.ldw + a.j0;
+        if (a.nbk == QB) {
 #pragma unroll
-        for (int k = 0; k < QB; k += 4) {
-            const float4 v = *reinterpret_cast<const float4*>(src + k);
-            st.w[k] = v.x; st.w[k + 1] = v.y; st.w[k + 2] = v.z; st.w[k + 3] = v.w;
+            for (int k = 0; k < QB; k += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(src + k);
+                st.w[k] = v.x; st.w[k + 1] = v.y; st.w[k + 2] = v.z; st.w[k + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < QB; ++k) st.w[k] = (k < a.nbk) ? src[k] : 0.f;
         }
         if constexpr (sizeof(WT) == 2) {
             if (a.nbk == QB && (reinterpret_cast<uintptr_t>(wsrc) & 15) == 0) {
@@ -166,6 +173,57 @@ __global__ __launch_bounds__(128) void invert_diag_blocks_kernel(const float* R,
     for (int q = threadIdx.x; q < QB * QB; q += 128) dst[q] = xs[(q / QB) * (QB + 1) + (q % QB)];
 }
 
+// Rt[rows above the block, block] = R[those rows, block] U_bb, one workgroup per 128 x 128 tile above the diagonal
+// blocks (tile number t of the strict upper triangle of blocks, column block by column block).  Both operands sit in
+// LDS; a thread makes 8 x 4 outputs: its 8 values of a column of A are the same for the 32 threads that share its
+// rows (broadcast reads), its 4 values of a row of U_bb one 16-byte read.
+__global__ __launch_bounds__(512) void scale_column_blocks_kernel(const float* R, int64_t ldr, int64_t n, const float* Ub, float* Rt, int64_t ldt) {
+    int jb = 1, ib = (int)blockIdx.x;                    // tile t -> (ib, jb), ib < jb: column block jb has jb tiles
+    while (ib >= jb) { ib -= jb; ++jb; }
+    extern __shared__ __align__(16) float scale_sm[];
+    constexpr int PA = 133, P = 132;          // pitches: the rows a wavefront reads of A at a time fall on different banks
+    float* As = scale_sm;                     // [i][k]
+    float* Us = scale_sm + QB * PA;           // [k][c]; 128 * 133 floats is a multiple of 16 bytes
+    const int64_t i0 = (int64_t)ib * QB, j0 = (int64_t)jb * QB;
+    const float* ub = Ub + (int64_t)jb * QB * QB;
+    for (int q = threadIdx.x; q < QB * QB; q += 512) {
+        const int i = q / QB, k = q % QB;
+        const int64_t gk = j0 + k;
+        As[i * PA + k] = (gk < n) ? R[(i0 + i) * ldr + gk] : 0.f;       // rows i0 + i < j0 <= n are inside the matrix
+        Us[i * P + k] = ub[q];                                         // row i of U_bb, column k
+    }
+    __syncthreads();
+    const int ty = threadIdx.x >> 5, tx = threadIdx.x & 31;            // rows ty*8 .. +7, columns tx*4 .. +3
+    float acc[8][4];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
+#pragma unroll 4
+    for (int k = 0; k < QB; ++k) {
+        float av[8];
+#pragma unroll
+        for (int a = 0; a < 8; ++a) av[a] = As[(ty * 8 + a) * PA + k];
+        const float4 b0 = *reinterpret_cast<const float4*>(Us + k * P + tx * 4);
+        const float bv[4] = {b0.x, b0.y, b0.z, b0.w};
+#pragma unroll
+        for (int a = 0; a < 8; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[a][b] = fmaf(av[a], bv[b], acc[a][b]);
+    }
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+        float* dst = Rt + (i0 + ty * 8 + a) * ldt + j0 + tx * 4;
+        if (j0 + tx * 4 + 4 <= n) {
+            *reinterpret_cast<float4*>(dst) = make_float4(acc[a][0], acc[a][1], acc[a][2], acc[a][3]);
+        } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                if (j0 + tx * 4 + b < n) dst[b] = acc[a][b];
+        }
+    }
+}
+
 int launch_quant_block_hybrid(int64_t group, int wdtype, unsigned workgroups, const HybridArgs& h, hipStream_t s) {
 #define GPTQ_HYB(G)                                                                                                                \
     switch (wdtype) {                                                                                                              \
@@ -184,6 +242,18 @@ int launch_invert_diag_blocks(const float* R, int64_t ldr, int64_t n, float* Ub,
     constexpr size_t inv_lds = 2 * QB * (QB + 1) * sizeof(float);
     GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(invert_diag_blocks_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)inv_lds));
     hipLaunchKernelGGL(invert_diag_blocks_kernel, dim3((unsigned)ceil_div(n, QB)), dim3(128), inv_lds, s, R, ldr, n, Ub);
+    GPTQ_LAUNCH_CHECK();
+    return GPTQ_OK;
+}
+
+int launch_scale_column_blocks(const float* R, int64_t ldr, int64_t n, const float* Ub, float* Rt, int64_t ldt, hipStream_t s) {
+    const int64_t nblk = ceil_div(n, QB);
+    if (nblk < 2) return GPTQ_OK;
+    if (nblk > 65535) return fail(GPTQ_ERR_UNSUPPORTED, "quantize_layer_from_factor: too many column blocks");
+    const int64_t tiles = nblk * (nblk - 1) / 2;
+    constexpr size_t lds = (QB * 133 + QB * 132) * sizeof(float);
+    GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(scale_column_blocks_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(scale_column_blocks_kernel, dim3((unsigned)tiles), dim3(512), lds, s, R, ldr, n, Ub, Rt, ldt);
     GPTQ_LAUNCH_CHECK();
     return GPTQ_OK;
 }
