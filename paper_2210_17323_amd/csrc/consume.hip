@@ -477,6 +477,145 @@ __global__ __launch_bounds__(256) void matvec_dot2_kernel(PackedArgs a, const __
     }
 }
 
+// ---- one grid per row: the dot products on the matrix cores --------------------------------------------------------
+// Same loads, same pairs of halves, but the pairs are not multiplied by v_dot2: two pair registers (4 weights) are the A
+// operand and the two matching registers of the vector the B operand of one v_mfma_f32_16x16x16_f16.  The instruction
+// computes D[i][j] += sum over the four lanes kb of <weights of lane (i, kb), vector entries of lane (j, kb)>
+// (lane = i + 16 kb on the A side, j + 16 kb on the B side), so its DIAGONAL accumulates exactly the dot products the
+// lanes want -- every lane's weights with its own vector entries, summed over four lanes at a time -- and the other 240
+// entries (one lane's weights with another lane's entries) are never read.  That takes a third of the vector
+// instructions off the path that bounds the kernel, at 8 matrix-core instructions per row and segment, which run beside
+// the unpacking of other wavefronts.  With one grid per row the scale, the zero point and the 2^b offset come in at the
+// very end:  y = scale (sum (2^b + code) x - (2^b + zero) sum x).
+typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+
+// codes_as_half_pairs with the and-or written in C: what feeds a matrix-core instruction must be an instruction the
+// compiler knows, so that it can keep the wait states the hardware wants between a vector write and the matrix read of
+// the same register (an inline-assembly statement hides its instruction from that check).
+template <int BITS>
+__device__ __forceinline__ void codes_as_half_pairs_plain(const uint32_t (&w)[BITS + 1], uint32_t (&pr)[16]) {
+    constexpr int WANT = 10 - BITS;
+    constexpr uint32_t M = (1u << BITS) - 1u;
+    constexpr uint32_t MASK_LO = M << WANT, MASK_HI = M << (16 + WANT), MASK = MASK_LO | MASK_HI;
+    uint32_t magic = 0x3C003C00u + (uint32_t)BITS * 0x04000400u;             // (2^b, 2^b) as two halves
+    // the constants in registers whose contents the compiler does not know: v_and_or_b32 takes no literals here, and with
+    // known constants the compiler prefers an and and an or with one literal each
+    uint32_t mask = MASK, mask_lo = MASK_LO, mask_hi = MASK_HI;
+    asm volatile("" : "+s"(mask), "+s"(mask_lo), "+s"(mask_hi), "+v"(magic));
+    uint32_t joined[3] = {0u, 0u, 0u};
+    if constexpr (BITS == 3) {
+        joined[0] = __builtin_amdgcn_perm(w[1], w[0], 0x07060100u);      // low half of w0, high half of w1
+        joined[1] = __builtin_amdgcn_perm(w[0], w[2], 0x07060100u);      // low half of w2, high half of w0
+        joined[2] = __builtin_amdgcn_perm(w[2], w[1], 0x07060100u);      // low half of w1, high half of w2
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const PairSpec sp = PairTable<BITS>::at(i);
+        if (sp.lo_word < 0) {
+            const uint32_t ta = stream_bits<BITS>(w, BITS * sp.k_lo - WANT);
+            const uint32_t tb = stream_bits<BITS>(w, BITS * sp.k_hi - (16 + WANT));
+            pr[i] = (tb & mask_hi) | ((ta & mask_lo) | magic);
+        } else {
+            uint32_t m;
+            if (sp.lo_word == sp.hi_word) m = w[sp.lo_word];
+            else m = joined[sp.lo_word == 0 ? 0 : (sp.lo_word == 2 ? 1 : 2)];
+            const uint32_t t = sp.rel >= WANT ? (m >> (sp.rel - WANT)) : (m << (WANT - sp.rel));
+            pr[i] = (t & mask) | magic;
+        }
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void mv_mfma_rows(const uint32_t (&w)[MV2_HALF][BITS + 1], const half2v (&xq)[16], float4v* acc) {
+#pragma unroll
+    for (int rr = 0; rr < MV2_HALF; ++rr) {
+        uint32_t pr[16];
+        codes_as_half_pairs_plain<BITS>(w[rr], pr);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const u32x2v av = {pr[2 * t], pr[2 * t + 1]};
+            const u32x2v bv = {__builtin_bit_cast(uint32_t, xq[2 * t]), __builtin_bit_cast(uint32_t, xq[2 * t + 1])};
+            acc[rr] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4v, av), __builtin_bit_cast(half4v, bv), acc[rr], 0, 0, 0);
+        }
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void matvec_mfma_kernel(PackedArgs a, const __half* x, float* y) {
+    __shared__ float part[4][MV2_ROWS + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t nseg = (a.n + MV_SEG - 1) / MV_SEG;
+    const int64_t row_end = min(((int64_t)blockIdx.x + 1) * a.rows_per_wg, a.r);
+    // this lane's element of the diagonal of D: lane = j + 16 ib holds D[4 ib + e][j], e = 0 .. 3
+    const int dj = lane & 15, dib = lane >> 4;
+    const bool on_diag = (dj >> 2) == dib;
+    const int de = dj & 3;
+    for (int64_t row0 = (int64_t)blockIdx.x * a.rows_per_wg; row0 < row_end; row0 += MV2_ROWS) {
+    float4v acc[MV2_ROWS];
+#pragma unroll
+    for (int rr = 0; rr < MV2_ROWS; ++rr) acc[rr] = float4v{0.f, 0.f, 0.f, 0.f};
+    float sx = 0.f;                                          // sum of this lane's vector entries over its segments
+    uint32_t wa[MV2_HALF][BITS + 1], wb[MV2_HALF][BITS + 1];
+    const uint32_t wlast = (uint32_t)(a.words_per_row - BITS);      // n is a multiple of 32 and at least 32
+    auto words_at = [&](int64_t seg) { return min((uint32_t)(((seg * MV_SEG) >> 5) + lane) * BITS, wlast); };
+    const int row0i = (int)row0;
+    if (wave < nseg) mv_load_rows<BITS>(wa, a, row0i, words_at(wave));
+#pragma unroll 1
+    for (int64_t s = wave; s < nseg; s += 4) {
+        const int64_t k0 = s * MV_SEG + (int64_t)lane * 32;      // lanes past the last column: any words, zero vector entries
+        mv_load_rows<BITS>(wb, a, row0i + MV2_HALF, words_at(s));
+        uint32_t xp[16];
+        {
+            const bool inside = k0 < a.n;
+            const __half* xsrc = x + min(k0, a.n - 32);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint4 u = reinterpret_cast<const uint4*>(xsrc)[q];
+                xp[4 * q] = inside ? u.x : 0u; xp[4 * q + 1] = inside ? u.y : 0u; xp[4 * q + 2] = inside ? u.z : 0u; xp[4 * q + 3] = inside ? u.w : 0u;
+            }
+        }
+        asm volatile("" ::: "memory");                       // the requests above stay above the arithmetic below
+        half2v xq[16];                                       // the same entries paired like the codes
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            sx = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, xp[i]), __builtin_bit_cast(half2v, 0x3C003C00u), sx, false);
+            const PairSpec sp = PairTable<BITS>::at(i);
+            const uint32_t lo = (xp[sp.k_lo >> 1] >> (16 * (sp.k_lo & 1))) & 0xFFFFu;
+            const uint32_t hi = (sp.k_hi & 1) ? (xp[sp.k_hi >> 1] & 0xFFFF0000u) : (xp[sp.k_hi >> 1] << 16);
+            xq[i] = __builtin_bit_cast(half2v, lo | hi);
+        }
+        mv_mfma_rows<BITS>(wa, xq, acc);
+        if (s + 4 < nseg) mv_load_rows<BITS>(wa, a, row0i, words_at(s + 4));
+        asm volatile("" ::: "memory");
+        mv_mfma_rows<BITS>(wb, xq, acc + MV2_HALF);
+    }
+#pragma unroll
+    for (int rr = 0; rr <= MV2_ROWS; ++rr) {
+        float v;
+        if (rr < MV2_ROWS) {
+            const float4v c = acc[rr < MV2_ROWS ? rr : 0];
+            const float e = de == 0 ? c.x : (de == 1 ? c.y : (de == 2 ? c.z : c.w));
+            v = on_diag ? e : 0.f;
+        } else {
+            v = sx;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (lane == 0) part[wave][rr] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < MV2_ROWS && row0 + threadIdx.x < a.r) {
+        const int64_t row = row0 + threadIdx.x;
+        const float dots = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+        const float sxs = (part[0][MV2_ROWS] + part[1][MV2_ROWS]) + (part[2][MV2_ROWS] + part[3][MV2_ROWS]);
+        y[row] = a.scales[row * a.ngroups] * (dots - ((float)(1 << BITS) + (float)a.zeros[row * a.ngroups]) * sxs);
+    }
+    __syncthreads();
+    }
+}
+
 __global__ void zero_vector_kernel(float* y, int64_t r) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < r) y[i] = 0.f;
@@ -559,7 +698,10 @@ static void launch_matvec(PackedArgs a, const XT* x, float* y, hipStream_t s) {
         if (gsub == 1 && a.n % 32 == 0 && a.n >= 32 && a.n < 0x7fffffffLL && a.r < 0x7fffffffLL && a.words_per_row < 0x3fffffffLL &&
             a.ngroups < 0x3fffffffLL && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
             a.rows_per_wg = rows_per_workgroup(a.r, MV2_ROWS);
-            hipLaunchKernelGGL((matvec_dot2_kernel<BITS>), dim3((unsigned)ceil_div(a.r, a.rows_per_wg)), dim3(256), 0, s, a, x, y);
+            if (a.group == 0)
+                hipLaunchKernelGGL((matvec_mfma_kernel<BITS>), dim3((unsigned)ceil_div(a.r, a.rows_per_wg)), dim3(256), 0, s, a, x, y);
+            else
+                hipLaunchKernelGGL((matvec_dot2_kernel<BITS>), dim3((unsigned)ceil_div(a.r, a.rows_per_wg)), dim3(256), 0, s, a, x, y);
             return;
         }
     }
