@@ -81,7 +81,7 @@ def quantize(W: torch.Tensor, U: torch.Tensor, bits: int, grid: str = "minmax", 
 
 
 def solve_block(groups, bits: int | None = None, chunk: int | None = None, want_Wq: bool = False, timings: dict | None = None,
-                factors: dict | None = None, form: str = "auto", overlap: bool = False):
+                factors: dict | None = None, form: str = "auto", overlap: bool = False, stack: bool = True):
     """The layers of one block, quantized in sequence (Section 4, Setup: a block's inputs are collected, its
     layers quantized, then the next block).  `groups` is a list of (X, layers): X [n x m] are the input
     activations shared by `layers`, a list of (name, W, settings) with settings an object carrying
@@ -97,7 +97,9 @@ def solve_block(groups, bits: int | None = None, chunk: int | None = None, want_
     H + lambda I = R R^T and runs Alg. 1 from R (no triangular inverse; one grid per row or groups of 32, 64 or 128
     columns); "auto" takes the factor form for the groups all of whose layers it is offered for.
     overlap: the Hessian of group k+1 is accumulated on a second stream while group k is factored and quantized
-    (the factorisation's serial chains leave most of the chip idle)."""
+    (the factorisation's serial chains leave most of the chip idle).
+    stack: layers of a group with the same bits, grid, block, group size and weight type are quantized as one matrix of
+    stacked rows (their results are row slices of the stack's; their time is reported under "a+b+c:quantize_pack")."""
     out = {}
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
@@ -133,16 +135,37 @@ def solve_block(groups, bits: int | None = None, chunk: int | None = None, want_
         e[1].record()
         marks.append((f"group{gi}:damp_cholesky_inverse", e[0], e[1]))
         ws = None
+        # Rows are independent in Alg. 1 (Section 2: the objective is a sum over rows), so layers that share the factor and
+        # the grid settings go through it as ONE matrix of stacked rows: one pass over the columns instead of one per
+        # layer, with three times the rows per kernel for q, k, v.
+        stacks = []
         for name, W, lay in layers:
-            b = lay.bits if bits is None else bits
-            need = B.gptq_quantize_layer_workspace_bytes(W.shape[0], n, lay.block, lay.group)
+            key = (lay.bits if bits is None else bits, lay.grid, lay.block, lay.group, W.dtype)
+            for st in stacks:
+                if stack and st[0] == key:
+                    st[1].append((name, W, lay))
+                    break
+            else:
+                stacks.append((key, [(name, W, lay)]))
+        for (b, grid, block, group, _), members in stacks:
+            Ws = members[0][1] if len(members) == 1 else torch.cat([W for _, W, _ in members], dim=0)
+            need = B.gptq_quantize_layer_workspace_bytes(Ws.shape[0], n, block, group)
             if ws is None or ws.numel() < need:
+                ws = None
                 ws = torch.empty(need, dtype=torch.uint8, device=X.device)
             q0, q1 = ev(), ev()
             q0.record()
-            out[name] = quantize(W, U, b, lay.grid, lay.block, lay.group, want_Wq=want_Wq, pack=True, ws=ws, from_factor=from_factor)
+            res = quantize(Ws, U, b, grid, block, group, want_Wq=want_Wq, pack=True, ws=ws, from_factor=from_factor)
             q1.record()
-            marks.append((f"{name}:quantize_pack", q0, q1))
+            r0 = 0
+            for name, W, _ in members:
+                r1 = r0 + W.shape[0]
+                out[name] = res if len(members) == 1 else LayerResult(
+                    res.codes[r0:r1], res.scales[r0:r1], res.zeros[r0:r1], res.half_E2_rows[r0:r1],
+                    None if res.Wq is None else res.Wq[r0:r1], None if res.packed is None else res.packed[r0:r1])
+                r0 = r1
+            marks.append(("+".join(name for name, _, _ in members) + ":quantize_pack", q0, q1))
+            del Ws, res
         if factors is not None:
             factors[gi] = U
         if overlap:

@@ -344,7 +344,15 @@ def test_block_driver_shares_hessians_and_matches_oracle(form):
     timings = {}
     res = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, timings=timings, form=form)
     assert set(res) == {"q", "k", "v", "out"}
-    assert {"group0:hessian", "group0:damp_cholesky_inverse", "group1:hessian", "q:quantize_pack", "out:quantize_pack", "total"} <= set(timings)
+    assert {"group0:hessian", "group0:damp_cholesky_inverse", "group1:hessian", "q+k+v:quantize_pack", "out:quantize_pack", "total"} <= set(timings)
+    # q, k, v went through Alg. 1 as one matrix of stacked rows; layer by layer gives the same bits (rows are independent)
+    res1 = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, form=form, stack=False)
+    torch.cuda.synchronize()
+    for name in res:
+        assert res[name].codes.shape == res1[name].codes.shape
+        assert torch.equal(res[name].codes, res1[name].codes) and torch.equal(res[name].scales, res1[name].scales)
+        assert torch.equal(res[name].zeros, res1[name].zeros) and torch.equal(res[name].packed, res1[name].packed)
+        assert torch.equal(res[name].Wq, res1[name].Wq) and torch.equal(res[name].half_E2_rows, res1[name].half_E2_rows)
     # the same block with the next group's Hessian accumulated on a second stream meanwhile: the same bits
     res2 = S.solve_block(groups, bits=4, chunk=4096, want_Wq=True, form=form, overlap=True)
     torch.cuda.synchronize()
