@@ -30,6 +30,21 @@ def test_workspace_sizes():
     assert g.gptq_hessian_accumulate_workspace_bytes(4096, 256) == 0         # too few tokens to split
 
 
+def test_long_hessian_calls_are_sliced_only_on_large_matrices():
+    import torch
+    # one launch of the matrix-core kernel per 32768 tokens where one slice fills the chip; the workspace holds two slices
+    assert g.gptq_hessian_accumulate_launches(49152, 262144, torch.float16) == 8
+    assert g.gptq_hessian_accumulate_launches(12288, 262144, torch.float16) == 8
+    assert g.gptq_hessian_accumulate_launches(12288, 32768, torch.float16) == 1
+    assert g.gptq_hessian_accumulate_launches(12288, 40000, torch.bfloat16) == 2
+    assert g.gptq_hessian_accumulate_launches(4096, 262144, torch.float16) == 1       # few tiles: one launch, split token range
+    assert g.gptq_hessian_accumulate_launches(49152, 262144, torch.float32) == 1      # float32 activations: the float32 GEMM
+    assert g.gptq_hessian_accumulate_launches(0, 100, torch.float16) == 0
+    two_slices = 2 * 49152 * 32800 * 2 + 256
+    assert g.gptq_hessian_accumulate_workspace_bytes(49152, 262144) == two_slices
+    assert g.gptq_hessian_accumulate_workspace_bytes(49152, 65536) == two_slices
+
+
 def _err():
     return g.lib().gptq_last_error().decode()
 
