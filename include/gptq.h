@@ -233,6 +233,36 @@ GPTQ_API int gptq_trailing_update(float* W, int64_t ldw, const float* E, int64_t
                          int64_t r, int64_t ncols, int64_t k, void* stream);
 
 /*
+ * The two deferred rank-1024 updates through split float32 products on the bf16 matrix cores -- the form
+ * gptq_damp_cholesky* and gptq_quantize_layer* use for their large updates (Section 3, Steps 2 and 3; Alg. 1, last
+ * statement of the outer loop).  Every float32 operand element is the exact sum of three bfloat16 pieces
+ * (8 + 8 + 8 significant bits); of the nine piece products of a * b the six with i + j <= 4 are accumulated in
+ * float32, smallest first; the three left out are below 2^-23 |a b|, the size of a float32 rounding.
+ *
+ * gptq_trailing_update_split:   W[r x ncols] -= E[r x k] * U[k x ncols]       (arguments as gptq_trailing_update)
+ * gptq_symmetric_update_split:  H[n x n] -= P[n x k] * P^T on the 256 x 256 tiles that touch the upper triangle
+ *                               (diagonal tiles whole; tiles below the diagonal are not written)
+ *   k must be 1024 and r, ncols, n multiples of 256 (else GPTQ_ERR_UNSUPPORTED, nothing enqueued); all matrices
+ *   row-major float32, 16-byte aligned, leading dimensions multiples of 4 elements.  ws: device workspace of at
+ *   least *_workspace_bytes, 256-byte aligned, holds the split operands; its contents need not be initialised.
+ *   Operand elements must be finite and below 2^127 in magnitude.
+ */
+/*
+ * Which launches take the split products is decided per launch from its count of 256 x 256 tiles: at least 205, and at
+ * least 80 % of the workgroup slots of its last round of 256 taken.  gptq_set_split_min_tiles(t) with t > 0 replaces
+ * that rule by "at least t tiles" for every later call of the process (t <= 0 restores it) and returns the previous
+ * setting: a tuning and test knob -- the results of a call depend on it only through rounding.  Not meant to be
+ * changed while another thread is inside a library call.
+ */
+GPTQ_API int gptq_set_split_min_tiles(int tiles);
+GPTQ_API size_t gptq_trailing_update_split_workspace_bytes(int64_t r, int64_t ncols);
+GPTQ_API int gptq_trailing_update_split(float* W, int64_t ldw, const float* E, int64_t lde, const float* U, int64_t ldu,
+                               int64_t r, int64_t ncols, int64_t k, void* ws, size_t ws_bytes, void* stream);
+GPTQ_API size_t gptq_symmetric_update_split_workspace_bytes(int64_t n);
+GPTQ_API int gptq_symmetric_update_split(float* H, int64_t ldh, const float* P, int64_t ldp, int64_t n, int64_t k,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Step 4 -- bit packing (the paper stores 3-bit weights densely, Section 4 "Practical Speedups",
  * but prints no layout; this one is ours).
  *

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     gptq_damp_cholesky_inverse_noalloc, gptq_noalloc_max_n,
     gptq_damp_cholesky, gptq_damp_cholesky_workspace_bytes, gptq_quantize_layer_from_factor, gptq_quantize_layer_from_factor_supports,
     gptq_quantize_layer, gptq_quantize_layer_workspace_bytes, gptq_trailing_update,
+    gptq_trailing_update_split, gptq_trailing_update_split_workspace_bytes,
+    gptq_symmetric_update_split, gptq_symmetric_update_split_workspace_bytes, gptq_set_split_min_tiles,
     gptq_pack, gptq_unpack, packed_words_per_row, gptq_dequantize_packed, gptq_matvec_packed,
     GPTQ_GRID_MINMAX, GPTQ_GRID_TERNARY,
 )

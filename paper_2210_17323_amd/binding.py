@@ -70,13 +70,22 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.gptq_quantize_layer_from_factor_supports.argtypes = [i64]
     L.gptq_quantize_layer_from_factor_supports.restype = ci
     L.gptq_trailing_update.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i64, vp]
+    L.gptq_trailing_update_split.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i64, vp, sz, vp]
+    L.gptq_trailing_update_split_workspace_bytes.argtypes = [i64, i64]
+    L.gptq_trailing_update_split_workspace_bytes.restype = sz
+    L.gptq_symmetric_update_split.argtypes = [vp, i64, vp, i64, i64, i64, vp, sz, vp]
+    L.gptq_symmetric_update_split_workspace_bytes.argtypes = [i64]
+    L.gptq_symmetric_update_split_workspace_bytes.restype = sz
+    L.gptq_set_split_min_tiles.argtypes = [ci]
+    L.gptq_set_split_min_tiles.restype = ci
     L.gptq_pack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     L.gptq_unpack.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp]
     L.gptq_dequantize_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, i64, vp]
     L.gptq_matvec_packed.argtypes = [vp, i64, i64, i64, ci, vp, vp, i64, vp, ci, vp, vp]
     for name in ("gptq_hessian_accumulate", "gptq_hessian_symmetrize", "gptq_damp_cholesky_inverse", "gptq_check_info",
                  "gptq_quantize_layer", "gptq_pack", "gptq_unpack", "gptq_damp_cholesky_inverse_noalloc",
-                 "gptq_hessian_accumulate_token_major", "gptq_dequantize_packed", "gptq_matvec_packed"):
+                 "gptq_hessian_accumulate_token_major", "gptq_dequantize_packed", "gptq_matvec_packed",
+                 "gptq_trailing_update_split", "gptq_symmetric_update_split"):
         getattr(L, name).restype = ci
     if path == LIB_PATH:
         _lib = L
@@ -258,6 +267,42 @@ def gptq_trailing_update(W: torch.Tensor, E: torch.Tensor, U: torch.Tensor) -> N
     if E.shape[0] != r or U.shape != (k, ncols):
         raise ValueError("need E [r x k] and U [k x ncols] for W [r x ncols]")
     _check(lib().gptq_trailing_update(_ptr(W), _ld(W), _ptr(E), _ld(E), _ptr(U), _ld(U), r, ncols, k, _stream()))
+
+
+def gptq_trailing_update_split_workspace_bytes(r: int, ncols: int) -> int:
+    return int(lib().gptq_trailing_update_split_workspace_bytes(int(r), int(ncols)))
+
+
+def gptq_trailing_update_split(W: torch.Tensor, E: torch.Tensor, U: torch.Tensor, ws: torch.Tensor) -> None:
+    """W[r x ncols] -= E[r x 1024] @ U[1024 x ncols] through split float32 products on the bf16 matrix cores."""
+    for t, nm in ((W, "W"), (E, "E"), (U, "U")):
+        _dev2d(t, nm, (torch.float32,))
+    r, ncols = W.shape
+    k = E.shape[1]
+    if E.shape[0] != r or U.shape != (k, ncols):
+        raise ValueError("need E [r x k] and U [k x ncols] for W [r x ncols]")
+    _check(lib().gptq_trailing_update_split(_ptr(W), _ld(W), _ptr(E), _ld(E), _ptr(U), _ld(U), r, ncols, k,
+                                            _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def gptq_set_split_min_tiles(tiles: int) -> int:
+    """Launches of at least `tiles` 256 x 256 tiles take the split products (0: the library's own rule); returns the previous setting."""
+    return int(lib().gptq_set_split_min_tiles(int(tiles)))
+
+
+def gptq_symmetric_update_split_workspace_bytes(n: int) -> int:
+    return int(lib().gptq_symmetric_update_split_workspace_bytes(int(n)))
+
+
+def gptq_symmetric_update_split(H: torch.Tensor, P: torch.Tensor, ws: torch.Tensor) -> None:
+    """H[n x n] -= P[n x 1024] @ P^T on the 256 x 256 tiles that touch the upper triangle (split float32 products)."""
+    _dev2d(H, "H", (torch.float32,))
+    _dev2d(P, "P", (torch.float32,))
+    n = H.shape[0]
+    if H.shape[1] != n or P.shape[0] != n:
+        raise ValueError("need a square H [n x n] and P [n x k]")
+    _check(lib().gptq_symmetric_update_split(_ptr(H), _ld(H), _ptr(P), _ld(P), n, P.shape[1],
+                                             _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def gptq_pack(codes: torch.Tensor, bits: int, out: torch.Tensor) -> None:

@@ -273,9 +273,12 @@ using namespace gptq;
 
 namespace {
 constexpr int OB = 1024;     // outer block: rank-1024 updates keep the big GEMMs compute-bound and their tiles long
+static_assert(OB == SPLIT_K, "the split products take exactly one outer block as K");
+// A rank-1024 update goes through the split-operand kernel (bf16 matrix cores, 256 x 256 tiles) when its tiles fill the
+// chip well (split_pays): the strip of the next outer block has 4 tile columns, the square rest t (t + 1) / 2 tiles.
 
-struct CholWs { float* dinv; float* T; float* T2; int64_t ld2; float* Uoo; float* tmp; size_t total; };
-CholWs chol_ws_layout(void* ws, int64_t n) {
+struct CholWs { float* dinv; float* T; float* T2; int64_t ld2; float* Uoo; float* tmp; unsigned char* planes; size_t total; };
+CholWs chol_ws_layout(void* ws, int64_t n, bool with_split = true) {
     const size_t n1 = (size_t)std::max<int64_t>(n, 1);
     const size_t nblk = (size_t)ceil_div((int64_t)n1, NB), nouter = (size_t)ceil_div((int64_t)n1, OB);
     size_t off = 0;
@@ -287,6 +290,9 @@ CholWs chol_ws_layout(void* ws, int64_t n) {
     l.T2 = reinterpret_cast<float*>(base + off);    off += round_up((size_t)OB * l.ld2 * sizeof(float), 256);   // a row panel [1024 x n]
     l.Uoo = reinterpret_cast<float*>(base + off);   off += round_up(nouter * OB * OB * sizeof(float), 256);     // U_oo of every outer block, dense
     l.tmp = reinterpret_cast<float*>(base + off);   off += round_up((size_t)NB * OB * sizeof(float), 256);      // one row block of a product
+    l.planes = reinterpret_cast<unsigned char*>(base + off);                                                    // bf16 pieces of a column panel (split products)
+    if (with_split && (int64_t)n1 >= 2 * OB) off += round_up(split_planes_bytes((int64_t)n1), 256);
+    else l.planes = nullptr;
     l.total = off + 256;
     return l;
 }
@@ -316,8 +322,8 @@ static int chol_check_args(const float* H, int64_t ld, int64_t n, float percdamp
 // (the host code below enqueues in an order that respects every dependence, so one stream is always valid).
 // want_inverse = false stops after the factorisation: H holds R (upper triangular, zeros below) with H + lambda I = R R^T.
 static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, int* info_dev, hipStream_t s, bool lookahead,
-                    bool want_inverse = true) {
-    const CholWs w = chol_ws_layout(ws, n);
+                    bool want_inverse = true, bool with_split = true) {
+    const CholWs w = chol_ws_layout(ws, n, with_split);
     float* dinv = w.dinv;
     constexpr size_t diag_lds = (2 * NB * DP + 32 * 64) * sizeof(float);
     GPTQ_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(diag_block_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)diag_lds));
@@ -416,13 +422,40 @@ static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, i
             hipEvent_t factored = nullptr;
             if (int rc = ts.mark(s, &factored)) return rc;
             if (int rc = ts.wait(s, rest_done)) return rc;
-            Opt co; co.nk = true; co.upper = true; co.ccol0 = p0;
-            if (int rc = gemm_on(s, H + o0, ld, H + p0 * ld + o0, ld, H + p0, ld, o0, o0 - p0, ow, -1.f, co)) return rc;
             rest_done = nullptr;
+            // Large updates multiply the bf16 pieces of the panel R[0:o0, o] (gemm_split.hip): one split of the panel serves
+            // both parts, as row operand and as column operand.  The plane buffer is free here: its last reader, the
+            // previous outer block's rest update, is what the wait above was for.
+            const bool split_strip = w.planes && ow == OB && split_pays((o0 / 256) * (OB / 256));
+            const bool split_rest = w.planes && ow == OB && p0 > 0 && split_pays((p0 / 256) * (p0 / 256 + 1) / 2);
+            if (split_strip || split_rest) {
+                if (int rc = launch_split_rows(H + o0, ld, o0, w.planes, s)) return rc;
+                if (int rc = ts.mark(s, &factored)) return rc;
+            }
+            SplitGemm sg{};
+            sg.A_planes = sg.B_planes = w.planes;
+            sg.A_zero = sg.B_zero = w.planes ? split_zero_block(w.planes, o0) : nullptr;
+            sg.ldc = ld; sg.alpha = -1.f;
+            if (split_strip) {
+                sg.a_panel0 = 0; sg.b_panel0 = (int)(p0 / 256); sg.C = H + p0;
+                sg.tiles_m = (int)(o0 / 256); sg.tiles_n = (int)(OB / 256);
+                sg.skip_lower = true; sg.crow0 = 0; sg.ccol0 = p0;
+                if (int rc = launch_gemm_split(sg, s)) return rc;
+            } else {
+                Opt co; co.nk = true; co.upper = true; co.ccol0 = p0;
+                if (int rc = gemm_on(s, H + o0, ld, H + p0 * ld + o0, ld, H + p0, ld, o0, o0 - p0, ow, -1.f, co)) return rc;
+            }
             if (p0 > 0) {
                 if (int rc = ts.wait(s2, factored)) return rc;
-                Opt ro; ro.nk = true; ro.upper = true;
-                if (int rc = gemm_on(s2, H + o0, ld, H + o0, ld, H, ld, p0, p0, ow, -1.f, ro)) return rc;
+                if (split_rest) {
+                    sg.a_panel0 = sg.b_panel0 = 0; sg.C = H;
+                    sg.tiles_m = sg.tiles_n = (int)(p0 / 256);
+                    sg.upper_square = true; sg.skip_lower = false;
+                    if (int rc = launch_gemm_split(sg, s2)) return rc;
+                } else {
+                    Opt ro; ro.nk = true; ro.upper = true;
+                    if (int rc = gemm_on(s2, H + o0, ld, H + o0, ld, H, ld, p0, p0, ow, -1.f, ro)) return rc;
+                }
                 if (int rc = ts.mark(s2, &rest_done)) return rc;
             }
         }
@@ -534,10 +567,10 @@ extern "C" int gptq_damp_cholesky_inverse_noalloc(float* H, int64_t ld, int64_t 
                                           "array holds; use gptq_damp_cholesky_inverse with a caller workspace",
                     (long long)n, (long long)NOALLOC_MAX_N);
     static_assert(NOALLOC_MAX_N % OB == 0, "layout below assumes whole outer blocks");
-    if (chol_ws_layout(nullptr, n).total > NOALLOC_BYTES) return fail(GPTQ_ERR_UNSUPPORTED, "damp_cholesky_inverse_noalloc: scratch layout exceeds the static array");
+    if (chol_ws_layout(nullptr, n, false).total > NOALLOC_BYTES) return fail(GPTQ_ERR_UNSUPPORTED, "damp_cholesky_inverse_noalloc: scratch layout exceeds the static array");
     void* ws = nullptr;
     if ((rc = scratch_for_current_device(&ws))) return rc;
-    return chol_run(H, ld, n, percdamp, ws, info_dev, static_cast<hipStream_t>(stream), false);
+    return chol_run(H, ld, n, percdamp, ws, info_dev, static_cast<hipStream_t>(stream), false, true, false);
 }
 
 extern "C" int gptq_check_info(const int* info_dev, int* host_info, void* stream) {

@@ -128,4 +128,33 @@ struct GemmF32 {
 };
 int launch_gemm_f32(const GemmF32& g, hipStream_t s);
 
+// ---- float32 products of rank 1024 on the bf16 matrix cores (gemm_split.hip) -----------------
+// C[256 tiles_m x 256 tiles_n] += alpha * A * B^T over K = SPLIT_K, with both operands given as "planes": the three
+// bfloat16 pieces of every float32 element in the blocked layout the kernel copies straight into LDS.
+//   launch_split_rows: A [rows x SPLIT_K] float32, K contiguous        -> planes of ceil(rows / 256) panels
+//   launch_split_cols: B [SPLIT_K x cols] float32, columns contiguous  -> planes of ceil(cols / 256) panels (of B^T)
+// Both write split_planes_bytes(rows) bytes, the last 16 KB of which are zeros (split_zero_block); rows past the
+// operand's end are zeros.  A launch reads panels a_panel0 .. and b_panel0 .. of the two plane buffers.
+//   upper_square: C is square and only the tiles of its upper triangle are computed (diagonal tiles whole).
+//   skip_lower:   rectangular C at (crow0, ccol0) of a parent matrix: tiles entirely below the parent's diagonal are left out.
+// The six piece products kept leave a relative error of at most 2^-23 per product of two elements.
+constexpr int SPLIT_K = 1024;
+struct SplitGemm {
+    const unsigned char* A_planes; int a_panel0;
+    const unsigned char* B_planes; int b_panel0;
+    const unsigned char* A_zero;        // each operand's block of zeros: split_zero_block(planes, rows given to its split)
+    const unsigned char* B_zero;
+    float* C; int64_t ldc;
+    float alpha;
+    int tiles_m, tiles_n;
+    bool upper_square;
+    bool skip_lower; int64_t crow0, ccol0;
+};
+size_t split_planes_bytes(int64_t rows);
+bool split_pays(int64_t tiles);         // whether a launch of that many 256 x 256 tiles should take the split kernel
+inline const unsigned char* split_zero_block(const unsigned char* planes, int64_t rows) { return planes + split_planes_bytes(rows) - 16384; }
+int launch_split_rows(const float* A, int64_t lda, int64_t rows, unsigned char* planes, hipStream_t s);
+int launch_split_cols(const float* B, int64_t ldb, int64_t cols, unsigned char* planes, hipStream_t s);
+int launch_gemm_split(const SplitGemm& g, hipStream_t s);
+
 }  // namespace gptq

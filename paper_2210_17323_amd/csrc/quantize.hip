@@ -407,8 +407,13 @@ static bool group_supported(int64_t group) {
 static bool factor_form_group_supported(int64_t group) { return group == 0 || group == 32 || group == 64 || group == 128; }
 
 constexpr int QOB = 1024;   // outer block: trailing updates beyond it are deferred and applied as one rank-1024 GEMM
+static_assert(QOB == SPLIT_K, "the split products take exactly one outer block as K");
 
-struct QuantWs { size_t wk, e, cs, ub, rt, total; int64_t ldk; };
+// The deferred rank-1024 updates go through the split-operand kernel (bf16 matrix cores, 256 x 256 tiles, one per
+// workgroup) when rows and columns come in whole tiles and the launch fills the chip well (split_pays).
+static bool split_shapes_ok(int64_t r, int64_t n) { return r >= 256 && r % 256 == 0 && n % 256 == 0 && n >= 2 * QOB; }
+
+struct QuantWs { size_t wk, e, cs, ub, rt, pa, pb, pr, total; int64_t ldk; bool split; };
 static QuantWs quant_ws_layout(int64_t r, int64_t n, int64_t group) {
     QuantWs l;
     l.ldk = (int64_t)round_up((size_t)std::max<int64_t>(n, 1), 4);
@@ -419,6 +424,14 @@ static QuantWs quant_ws_layout(int64_t r, int64_t n, int64_t group) {
     l.ub = off; off += round_up((size_t)ceil_div(std::max<int64_t>(n, 1), QB) * QB * QB * sizeof(float), 256);   // factor form with groups: every U_bb
     l.rt = off;                                                                                       // ... and R with its column blocks scaled by them
     if (group != 0 && factor_form_group_supported(group)) off += round_up((size_t)std::max<int64_t>(n, 1) * l.ldk * sizeof(float), 256);
+    // split products (gemm_split.hip): the bf16 pieces of an error panel, of the next outer block's rows of U and of all rows beyond
+    l.split = split_shapes_ok(r, n);
+    l.pa = l.pb = l.pr = off;
+    if (l.split) {
+        l.pa = off; off += round_up(split_planes_bytes(r), 256);
+        l.pb = off; off += round_up(split_planes_bytes(QOB), 256);
+        l.pr = off; off += round_up(split_planes_bytes(n), 256);
+    }
     l.total = off + 256;
     return l;
 }
@@ -523,6 +536,9 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
         Bm = Rt; ldb = lay.ldk;
     }
 
+    unsigned char* Pa = reinterpret_cast<unsigned char*>(base + lay.pa);
+    unsigned char* Pb = reinterpret_cast<unsigned char*>(base + lay.pb);
+    unsigned char* Pr = reinterpret_cast<unsigned char*>(base + lay.pr);
     const unsigned qblocks = (unsigned)ceil_div(r, 256);
     // Lazy batching at two levels (Section 3, Step 2 applied twice): inside an outer block of 1024 columns
     // each 128-column block updates only the rest of the outer block (rank 128); the columns beyond it
@@ -600,18 +616,46 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
             hipEvent_t quantized = nullptr;
             if (int rc = ts.mark(s, &quantized)) return rc;
             if (int rc = ts.wait(s, rest_done)) return rc;      // it wrote the columns from o1 on
+            rest_done = nullptr;
+            const float alpha = rf ? 1.f : -1.f;
+            const bool full = lay.split && ob == QOB && o1 - o0 == QOB;
+            const bool split_strip = full && o2 - o1 == QOB && split_pays((r / 256) * (QOB / 256));
+            const bool split_rest = full && o2 < n && split_pays((r / 256) * ((n - o2) / 256));
+            SplitGemm sg{};
+            sg.A_planes = Pa; sg.A_zero = split_zero_block(Pa, r); sg.a_panel0 = 0;
+            sg.ldc = lay.ldk; sg.alpha = alpha; sg.tiles_m = (int)(r / 256);
             GemmF32 g{};
             g.A = E; g.lda = QOB; g.B = Bm + o0 * ldb + o1; g.ldb = ldb; g.C = Wk + o1; g.ldc = lay.ldk;
-            g.M = r; g.N = o2 - o1; g.K = o1 - o0; g.alpha = rf ? 1.f : -1.f; g.b_is_nk = false; g.overwrite = false;
-            int rc = launch_gemm_f32(g, s);
-            if (rc) return rc;
-            rest_done = nullptr;
+            g.M = r; g.N = o2 - o1; g.K = o1 - o0; g.alpha = alpha; g.b_is_nk = false; g.overwrite = false;
+            if (split_strip) {
+                // the pieces of the error panel are made here, for both parts (the helper stream's last reader of the
+                // buffer is what the wait above was for); those of U's rows for the next outer block's columns as well
+                if (int rc = launch_split_rows(E, QOB, r, Pa, s)) return rc;
+                if (int rc = launch_split_cols(Bm + o0 * ldb + o1, ldb, QOB, Pb, s)) return rc;
+                if (int rc = ts.mark(s, &quantized)) return rc;
+                sg.B_planes = Pb; sg.B_zero = split_zero_block(Pb, QOB); sg.b_panel0 = 0;
+                sg.C = Wk + o1; sg.tiles_n = QOB / 256;
+                if (int rc = launch_gemm_split(sg, s)) return rc;
+            } else {
+                if (int rc = launch_gemm_f32(g, s)) return rc;
+            }
             if (o2 < n) {
-                if ((rc = ts.wait(s2, quantized))) return rc;
-                g.B = Bm + o0 * ldb + o2; g.C = Wk + o2; g.N = n - o2;
-                rc = launch_gemm_f32(g, s2);
-                if (rc) return rc;
-                if ((rc = ts.mark(s2, &rest_done))) return rc;
+                if (split_rest) {
+                    // U's rows for all columns beyond depend on nothing of this outer block: they are split before the helper
+                    // stream waits for it (the buffer's last reader, the previous rest update, precedes this on the stream)
+                    if (int rc = launch_split_cols(Bm + o0 * ldb + o2, ldb, n - o2, Pr, s2)) return rc;
+                }
+                if (int rc = ts.wait(s2, quantized)) return rc;
+                if (split_rest) {
+                    if (!split_strip) { if (int rc = launch_split_rows(E, QOB, r, Pa, s2)) return rc; }
+                    sg.B_planes = Pr; sg.B_zero = split_zero_block(Pr, n - o2); sg.b_panel0 = 0;
+                    sg.C = Wk + o2; sg.tiles_n = (int)((n - o2) / 256);
+                    if (int rc = launch_gemm_split(sg, s2)) return rc;
+                } else {
+                    g.B = Bm + o0 * ldb + o2; g.C = Wk + o2; g.N = n - o2;
+                    if (int rc = launch_gemm_f32(g, s2)) return rc;
+                }
+                if (int rc = ts.mark(s2, &rest_done)) return rc;
             }
         }
     }

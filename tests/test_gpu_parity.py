@@ -398,6 +398,74 @@ def test_trailing_update_matches_oracle(r, ncols, k):
     assert err <= 1e-6              # float32 accumulation of k terms: about sqrt(k) * 6e-8
 
 
+def _split_operand(rng, rows, cols, scale):
+    # values of mixed magnitude and sign with full 24-bit significands, some exact zeros and some tiny entries
+    a = rng.normal(size=(rows, cols)) * np.exp(rng.normal(size=(rows, cols)) * 2.0) * scale
+    a[rng.random(size=a.shape) < 0.05] = 0.0
+    a[rng.random(size=a.shape) < 0.01] *= 1e-20
+    return a.astype(np.float32)
+
+
+@pytest.mark.parametrize("r,ncols", [(256, 256), (512, 2304), (1280, 768)])
+def test_trailing_update_split_matches_oracle(r, ncols):
+    # the same update through split float32 products (three bfloat16 pieces per element, six piece products):
+    # against the float64 product of the same float32 inputs, and no worse than the float32 matrix-core product
+    k = 1024
+    _say(f"trailing update, split products r={r} ncols={ncols}")
+    rng = np.random.default_rng(7 * r + ncols)
+    W0 = rng.normal(size=(r, ncols)).astype(np.float32)
+    E = _split_operand(rng, r, k, 1.0)
+    U = _split_operand(rng, k, ncols, 1.0 / np.sqrt(k))
+    Wd = _padded(r, ncols, torch.float32, 4); Wd.copy_(torch.from_numpy(W0))
+    Ed = _padded(r, k, torch.float32, 4); Ed.copy_(torch.from_numpy(E))
+    Ud = _padded(k, ncols, torch.float32, 4); Ud.copy_(torch.from_numpy(U))
+    ws = torch.empty(g.gptq_trailing_update_split_workspace_bytes(r, ncols), dtype=torch.uint8, device="cuda")
+    ws.fill_(0x7f)                   # nothing in the workspace has to be initialised
+    g.gptq_trailing_update_split(Wd, Ed, Ud, ws)
+    prod = E.astype(np.float64) @ U.astype(np.float64)
+    want = W0.astype(np.float64) - prod
+    got = Wd.double().cpu().numpy()
+    W32 = _padded(r, ncols, torch.float32, 4); W32.copy_(torch.from_numpy(W0))
+    g.gptq_trailing_update(W32, Ed, Ud)
+    err, err32 = _rel_fro(got - W0, -prod), _rel_fro(W32.double().cpu().numpy() - W0, -prod)
+    # element by element against what the arithmetic allows: each of the k products is off by at most 2^-23 of its
+    # size (the piece products left out), and each of the 384 float32 additions of a 16-term group by 2^-24 of the
+    # partial sum, which a dominant term can bring close to the sum of magnitudes (a random walk of 384 such steps, the
+    # worst of a million elements): 2^-18 of that sum bounds both.  A piece product left out by mistake is what the
+    # Frobenius figure catches: 2^-17 of the typical product, i.e. about 4e-6 there.
+    bound = 2.0 ** -18 * (np.abs(E).astype(np.float64) @ np.abs(U).astype(np.float64)) + 2.0 ** -22 * np.abs(W0)
+    worst = float(np.max(np.abs(got - want) / bound))
+    _say(f"  rel_fro of the product: split {err:.3e}, float32 kernel {err32:.3e}; worst element / bound {worst:.3f}")
+    assert err <= 5e-7 and err <= 1.5 * err32 + 1e-8
+    assert worst <= 1.0
+
+
+@pytest.mark.parametrize("n", [256, 768, 2560])
+def test_symmetric_update_split_matches_oracle(n):
+    # H -= P P^T on the tiles that touch the upper triangle (the factorisation's deferred rank-1024 update)
+    k = 1024
+    _say(f"symmetric update, split products n={n}")
+    rng = np.random.default_rng(n)
+    H0 = rng.normal(size=(n, n)).astype(np.float32)
+    P = _split_operand(rng, n, k, 1.0 / np.sqrt(k))
+    Hd = _padded(n, n, torch.float32, 4); Hd.copy_(torch.from_numpy(H0))
+    Pd = _padded(n, k, torch.float32, 4); Pd.copy_(torch.from_numpy(P))
+    ws = torch.empty(g.gptq_symmetric_update_split_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    ws.fill_(0x7f)
+    g.gptq_symmetric_update_split(Hd, Pd, ws)
+    got = Hd.double().cpu().numpy()
+    P64 = P.astype(np.float64)
+    want = H0.astype(np.float64) - P64 @ P64.T
+    bound = 2.0 ** -18 * (np.abs(P64) @ np.abs(P64).T) + 2.0 ** -22 * np.abs(H0)
+    tile_r, tile_c = np.arange(n)[:, None] // 256, np.arange(n)[None, :] // 256
+    touched = tile_r <= tile_c
+    worst = float(np.max((np.abs(got - want) / bound)[touched]))
+    err = _rel_fro((got - H0)[touched], (want - H0)[touched])
+    _say(f"  rel_fro of the product {err:.3e}; worst element / bound {worst:.3f}")
+    assert worst <= 1.0 and err <= 5e-7
+    assert np.array_equal(got[~touched], H0.astype(np.float64)[~touched])      # tiles below the diagonal are left alone
+
+
 # ------------------------------------------------------------------ steps 2 and 3 without the inverse
 
 def _upper_factor(Hd):
@@ -494,3 +562,71 @@ def test_quantize_from_factor_with_unaligned_weight_rows():
     res = S.quantize(Wd, Rd, bits, "minmax", 128, 0, want_Wq=True, from_factor=True)
     torch.cuda.synchronize()
     _compare_quant(res, W.double().numpy(), U, Hd, bits, "minmax", 0, n, "factor form, unaligned rows", tie_tol=2e-3)
+
+
+# ------------------------------------------------------------------ the solvers with their deferred updates on the split products
+# On matrices this small the library's own rule keeps every update on the float32 kernel; with the rule replaced by
+# "every launch of whole tiles" the same calls run their rank-1024 updates through the split kernel and must still give
+# what the oracle gives, to the same bars.
+
+@pytest.fixture
+def forced_split():
+    prev = g.gptq_set_split_min_tiles(1)
+    yield
+    g.gptq_set_split_min_tiles(prev)
+
+
+@pytest.mark.parametrize("n,kind,form", [(3072, "relu", "inverse"), (3072, "lognormal", "factor"), (4352, "lognormal", "factor")])
+def test_cholesky_with_split_updates_matches_oracle(n, kind, form, forced_split):
+    _say(f"cholesky, split updates, n={n} kind={kind} form={form}")
+    base = configs.config2()[0] if kind == "lognormal" else configs.config3()[1]
+    X = _layer(base, n, 8, 4 * n).x.tile().double().numpy()
+    H32 = O.hessian(X).astype(np.float32)
+    Hd = O.damp(H32.astype(np.float64), 0.01)
+    H = _padded(n, n, torch.float32, 4)
+    H.copy_(torch.from_numpy(np.triu(H32) + np.tril(np.full_like(H32, 7.0), -1)))
+    if form == "inverse":
+        want = O.hinv_cholesky_upper(Hd)
+        S.cholesky_inverse(H, 0.01)
+    else:
+        want = _upper_factor(Hd)
+        S.cholesky_factor(H, 0.01)
+    got = H.double().cpu().numpy()
+    err = _rel_fro(got, want)
+    _say(f"  rel_fro={err:.3e}")
+    assert np.array_equal(np.tril(got, -1), np.zeros_like(got))
+    assert err <= 2e-5
+    if form == "factor":
+        assert float(np.abs(got @ got.T - Hd).max() / np.abs(Hd).max()) <= 1e-5
+
+
+SPLIT_QUANT_CASES = [
+    # bits, grid, group, dtype, r, n, from_factor
+    (3, "minmax", 0, torch.float16, 512, 3072, False),
+    (2, "minmax", 128, torch.float16, 256, 4096, False),
+    (3, "minmax", 0, torch.float16, 512, 3072, True),
+    (2, "ternary", 128, torch.float16, 256, 3072, True),
+    (4, "minmax", 0, torch.float32, 256, 2304, True),
+]
+
+
+@pytest.mark.parametrize("bits,grid,group,dtype,r,n,from_factor", SPLIT_QUANT_CASES)
+def test_quantize_with_split_updates_matches_oracle(bits, grid, group, dtype, r, n, from_factor, forced_split):
+    _say(f"quantize, split updates, bits={bits} grid={grid} group={group} dtype={dtype} r={r} n={n} from_factor={from_factor}")
+    lay = _layer(configs.config3()[1], n, r, 8 * n, shift=bits)
+    W = lay.weights().to(dtype)
+    X = lay.x.tile().double().numpy()
+    Hd = O.damp(O.hessian(X))
+    U = O.hinv_cholesky_upper(Hd)
+    F32 = (_upper_factor(Hd) if from_factor else U).astype(np.float32)
+    Wd = _padded(r, n, dtype, 8)
+    Wd.copy_(W)
+    Fd = _padded(n, n, torch.float32, 4)
+    Fd.copy_(torch.from_numpy(F32))
+    res = S.quantize(Wd, Fd, bits, grid, 128, group, want_Wq=True, from_factor=from_factor)
+    torch.cuda.synchronize()
+    if from_factor:
+        _compare_quant(res, W.double().numpy(), U, Hd, bits, grid, group, n, "factor form, split updates", tie_tol=2e-3)
+    else:
+        _compare_quant(res, W.double().numpy(), F32.astype(np.float64), Hd, bits, grid, group, n, "split updates")
+    assert int(res.codes.max()) <= O.grid_maxq(bits, grid)

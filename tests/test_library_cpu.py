@@ -21,7 +21,8 @@ def test_library_loads_and_exports_every_declared_symbol():
 def test_workspace_sizes():
     assert g.gptq_damp_cholesky_inverse_workspace_bytes(256) >= 2 * 128 * 128 * 4 + 256 * 128 * 4
     big = g.gptq_quantize_layer_workspace_bytes(12288, 49152)
-    assert 12288 * 49152 * 4 < big < 12288 * 49152 * 4 * 1.05 + (1 << 24)      # W copy + two r x 1024 error panels
+    planes = (12288 + 1024 + 49152) * 6144 + 3 * 16384      # bf16 pieces of an error panel, of 1024 and of all columns of U's rows
+    assert 12288 * 49152 * 4 + planes < big < 12288 * 49152 * 4 * 1.05 + planes + (1 << 24)      # W copy + two r x 1024 error panels
     assert g.gptq_quantize_layer_workspace_bytes(0, 0) > 0
     assert g.gptq_hessian_accumulate_workspace_bytes(49152, 32768) == 49152 * 32800 * 2
     # few tiles (136 for 256 CUs): the token range is split in 5, repacked chunk + 5 partial tiles per tile
@@ -97,6 +98,20 @@ def test_argument_validation_happens_on_the_host():
     assert tu(one, 60, one, 8, one, 64, 4, 64, 8, None) == INVALID          # ldw < ncols
     assert tu(None, 64, one, 8, one, 64, 4, 64, 8, None) == INVALID
     assert tu(one, 64, one, 8, one, 64, 0, 64, 8, None) == OK and tu(one, 64, one, 8, one, 64, 4, 64, 0, None) == OK
+    tus = L.gptq_trailing_update_split
+    assert tus(one, 256, one, 1024, one, 256, 256, 256, 512, one, 1 << 30, None) == UNSUPPORTED and "1024" in _err()   # k
+    assert tus(one, 256, one, 1024, one, 256, 200, 256, 1024, one, 1 << 30, None) == UNSUPPORTED                      # r % 256
+    assert tus(one, 256, one, 1024, one, 256, 256, 256, 1024, one, 1024, None) == WORKSPACE
+    assert tus(one, 256, one, 1024, one, 256, 256, 256, 1024, None, 0, None) == WORKSPACE
+    assert tus(one, 128, one, 1024, one, 256, 256, 256, 1024, one, 1 << 30, None) == INVALID                           # ldw < ncols
+    assert tus(one, 256, one, 1024, one, 256, 0, 256, 1024, one, 1 << 30, None) == OK
+    assert g.gptq_trailing_update_split_workspace_bytes(256, 512) == 3 * (3 * 32 * 16384) + 2 * 16384 + 256
+    sus = L.gptq_symmetric_update_split
+    assert sus(one, 256, one, 1024, 256, 128, one, 1 << 30, None) == UNSUPPORTED
+    assert sus(one, 256, one, 1024, 300, 1024, one, 1 << 30, None) == UNSUPPORTED
+    assert sus(one, 256, one, 1024, 256, 1024, one, 64, None) == WORKSPACE
+    assert sus(one, 256, one, 1000, 256, 1024, one, 1 << 30, None) == INVALID                                           # ldp < k
+    assert sus(one, 256, one, 1024, 0, 1024, None, 0, None) == OK
     assert L.gptq_pack(one, 64, 2, 64, 5, one, 8, None) == INVALID
     assert L.gptq_pack(one, 64, 2, 64, 3, one, 5, None) == INVALID      # 64*3/32 = 6 words needed
     assert L.gptq_pack(one, 32, 2, 64, 3, one, 6, None) == INVALID      # ldc < n
