@@ -173,7 +173,8 @@ def bench_block(a):
     out = {
         "metric": "gptq_block_solve_ms", "value": total3, "unit": "ms", "n_gpus": 1, "steps": 1, "warmup": 1,
         "ms_per_step": total3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1); u8 codes", "data": "synthetic",
+        "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1: the large rank-1024 updates as products of three "
+                 "bf16 pieces per f32 element, exact piece products accumulated in f32); u8 codes", "data": "synthetic",
         "config": {"workload": f"one OPT-175B-shaped decoder block: q, k, v, out 12288x12288, fc1 49152x12288, fc2 12288x49152, "
                                f"{m} tokens, per-row grids, B=128; q/k/v share one Hessian, one factor and one pass of Alg. 1 (stacked rows)",
                    "steps_2_and_3": form, "tokens_per_accumulate_call": chunk},
@@ -347,10 +348,11 @@ def main():
     dq_bytes = packed.numel() * 4 + grid_bytes + r * n * 2
     del Wd
 
-    # The float32 matrix-core GEMM that carries the larger share of the step (rank-1024 updates of the factorisation,
-    # of the inverse and of Alg. 1), timed alone through gptq_trailing_update at the shape of Alg. 1's median deferred
-    # update of this layer: W[r x n/2] -= E[r x 1024] U[1024 x n/2], operands taken from the buffers of the solve.
-    gemm = None
+    # The deferred rank-1024 update that carries the larger share of the step (factorisation and Alg. 1), timed alone at the
+    # shape of Alg. 1's median deferred update of this layer, W[r x n/2] -= E[r x 1024] U[1024 x n/2], operands taken
+    # from the buffers of the solve: through the split products the solvers use at this size (bf16 matrix cores, six piece
+    # products per float32 product; the time includes splitting both operands) and through the float32 kernel.
+    gemm = split_gemm = None
     kk, nc = min(1024, n), (n // 2) // 256 * 256
     if nc >= 256 and r >= 256:
         Wt = torch.zeros((r, nc), dtype=torch.float32, device=dev)
@@ -362,6 +364,19 @@ def main():
                 "achieved": g_flops / (g_ms * 1e-3) / 1e12, "peak": PEAK_F32_TFLOPS, "unit": "TFLOP/s",
                 "frac": g_flops / (g_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS, "avg_launch_ms": g_ms, "flops_per_launch": g_flops,
                 "traffic": None}
+        if kk == 1024 and r % 256 == 0:
+            sws = torch.empty(g.gptq_trailing_update_split_workspace_bytes(r, nc), dtype=torch.uint8, device=dev)
+            s_ms = timed(lambda: g.gptq_trailing_update_split(Wt, Et, Ut, sws), 10)
+            split_gemm = {"kernel": f"gemm_split_kernel + split_rows_kernel + split_cols_kernel (gptq_trailing_update_split, same shape)",
+                          "bound": "mfma", "achieved": 6 * g_flops / (s_ms * 1e-3) / 1e12, "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                          "frac": 6 * g_flops / (s_ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, "avg_launch_ms": s_ms,
+                          "flops_per_launch": 6 * g_flops,
+                          "float32_equivalent_tflops": g_flops / (s_ms * 1e-3) / 1e12,
+                          "float32_equivalent_of_fp32_peak": g_flops / (s_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS,
+                          "note": "bf16 matrix-core flops: six piece products per float32 product, priced against the bf16 peak; "
+                                  "float32_equivalent counts the float32 product's own flops",
+                          "traffic": None}
+            del sws
         del Wt, Et, Ut
 
     traffic = MEASURED_SYRK_TRAFFIC.get((n, tokens_per_launch)) if lay.x.dtype != torch.float32 else None
@@ -369,7 +384,8 @@ def main():
         "metric": "gptq_layer_solve_tflops", "value": total_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1); u8 codes",
+        "dtype": "f16 inputs, f32 accumulate (Hessian); f32 (Cholesky, Alg. 1: the large rank-1024 updates as products of three "
+                 "bf16 pieces per f32 element, exact piece products accumulated in f32); u8 codes",
         "data": "synthetic",
         "value_note": "all algorithmic flops of the solve (fp16 SYRK + fp32 factorisation, inverse and Alg. 1) over the step "
                       "time: a throughput of the whole job, comparable with no single peak; see phase_frac_of_peak",
@@ -380,6 +396,8 @@ def main():
         "phases_ms": {k: round(v, 3) for k, v in phases.items()},
         "phase_tflops": tf,
         "phase_frac_of_peak": frac,
+        "phase_frac_note": "Cholesky and Alg. 1: the float32 flops of the phase against the float32 matrix-core peak; their large updates "
+                           "run as split products on the bf16 matrix cores (roofline_split_gemm), which is how a phase can pass 1",
         "pack_GBps": (r * n + packed.numel() * 4) / (phases["pack"] * 1e-3) / 1e9,
         "algorithmic_flops": flops,
         "packed_consumers": {"matvec_us": mv_ms * 1e3, "matvec_GBps": mv_bytes / (mv_ms * 1e-3) / 1e9,
@@ -396,6 +414,7 @@ def main():
                      "traffic_unit": "bytes per launch",
                      "traffic_note": traffic["note"] if traffic else "not collected for this shape"},
         "roofline_f32_gemm": gemm,
+        "roofline_split_gemm": split_gemm,
     }
     # The other workload shapes, one short run each (1 warm-up + 2 timed steps): per-layer time and per-phase fraction of peak
     if a.layer == "opt175b_fc2" and not a.no_other_layers:

@@ -277,7 +277,7 @@ static_assert(OB == SPLIT_K, "the split products take exactly one outer block as
 // A rank-1024 update goes through the split-operand kernel (bf16 matrix cores, 256 x 256 tiles) when its tiles fill the
 // chip well (split_pays): the strip of the next outer block has 4 tile columns, the square rest t (t + 1) / 2 tiles.
 
-struct CholWs { float* dinv; float* T; float* T2; int64_t ld2; float* Uoo; float* tmp; unsigned char* planes; size_t total; };
+struct CholWs { float* dinv; float* T; float* T2; int64_t ld2; float* Uoo; float* tmp; unsigned char* planes; unsigned char* planes2; size_t total; };
 CholWs chol_ws_layout(void* ws, int64_t n, bool with_split = true) {
     const size_t n1 = (size_t)std::max<int64_t>(n, 1);
     const size_t nblk = (size_t)ceil_div((int64_t)n1, NB), nouter = (size_t)ceil_div((int64_t)n1, OB);
@@ -291,8 +291,14 @@ CholWs chol_ws_layout(void* ws, int64_t n, bool with_split = true) {
     l.Uoo = reinterpret_cast<float*>(base + off);   off += round_up(nouter * OB * OB * sizeof(float), 256);     // U_oo of every outer block, dense
     l.tmp = reinterpret_cast<float*>(base + off);   off += round_up((size_t)NB * OB * sizeof(float), 256);      // one row block of a product
     l.planes = reinterpret_cast<unsigned char*>(base + off);                                                    // bf16 pieces of a column panel (split products)
-    if (with_split && (int64_t)n1 >= 2 * OB) off += round_up(split_planes_bytes((int64_t)n1), 256);
-    else l.planes = nullptr;
+    l.planes2 = nullptr;                                                                                        // ... and of a row block (the inverse)
+    if (with_split && (int64_t)n1 >= 2 * OB) {
+        off += round_up(split_planes_bytes((int64_t)n1), 256);
+        l.planes2 = reinterpret_cast<unsigned char*>(base + off);
+        off += round_up(split_planes_bytes((int64_t)n1), 256);
+    } else {
+        l.planes = nullptr;
+    }
     l.total = off + 256;
     return l;
 }
@@ -479,13 +485,27 @@ static int chol_run(float* H, int64_t ld, int64_t n, float percdamp, void* ws, i
         const int64_t k0 = k * OB, k1 = std::min<int64_t>(k0 + OB, n), kw = k1 - k0;
         const float* Ukk = w.Uoo + k * (int64_t)OB * OB;
         hipEvent_t read_done = nullptr;  // s: the column block above k has been read by this step's update
+        bool marked = false;
         if (k1 < n && k0 > 0) {
             // U[0:k0, k1:n] += U[0:k0, k] (-U_kk R[k, k1:n])   (U[0:k0, k] not yet multiplied by U_kk; the second factor is
             // what the factorisation left in the row block)
-            Opt u;
-            if (int rc = gemm_on(s, H + k0, ld, H + k0 * ld + k1, ld, H + k1, ld, k0, n - k1, kw, 1.f, u)) return rc;
+            if (w.planes && kw == OB && (n - k1) % 256 == 0 && split_pays((k0 / 256) * ((n - k1) / 256))) {
+                // through the split products; the column block has been read once its pieces are made
+                if (int rc = launch_split_rows(H + k0, ld, k0, w.planes, s)) return rc;
+                if (int rc = ts.mark(s, &read_done)) return rc;
+                marked = true;
+                if (int rc = launch_split_cols(H + k0 * ld + k1, ld, n - k1, w.planes2, s)) return rc;
+                SplitGemm sg{};
+                sg.A_planes = w.planes; sg.A_zero = split_zero_block(w.planes, k0);
+                sg.B_planes = w.planes2; sg.B_zero = split_zero_block(w.planes2, n - k1);
+                sg.C = H + k1; sg.ldc = ld; sg.alpha = 1.f; sg.tiles_m = (int)(k0 / 256); sg.tiles_n = (int)((n - k1) / 256);
+                if (int rc = launch_gemm_split(sg, s)) return rc;
+            } else {
+                Opt u;
+                if (int rc = gemm_on(s, H + k0, ld, H + k0 * ld + k1, ld, H + k1, ld, k0, n - k1, kw, 1.f, u)) return rc;
+            }
         }
-        if (int rc = ts.mark(s, &read_done)) return rc;
+        if (!marked) { if (int rc = ts.mark(s, &read_done)) return rc; }
         // On the other stream: U[0:k0, k] <- U[0:k0, k] U_kk through T, and the diagonal block.  Nothing later reads them.
         // The last column block has no update after it: it stays on the caller's stream, with the row-panel buffer (free
         // by now) for its product, beside the last but one on the other stream.

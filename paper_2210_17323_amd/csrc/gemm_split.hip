@@ -28,8 +28,6 @@ namespace gptq {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-namespace {
-
 constexpr int SK = SPLIT_K;                      // K of a split product
 constexpr int PSTEPS = SK / 32;                  // 32-element steps per plane
 constexpr int PASSES = 6;
@@ -290,8 +288,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int i = 0; i < 16; ++i) unsafeAtomicAdd(cb + (int64_t)(8 * (i >> 2) + (i & 3)) * g.ldc, alpha * acc[s][u][i]);
         }
 }
-
-}  // namespace
 
 // A launch of the split kernel pays when it fills the chip's 256 CUs well: one 256 x 256 tile per workgroup, one workgroup
 // per CU, ~200 us per tile -- so at least 80 % of the slots of its last round of workgroups should be taken.
