@@ -248,11 +248,10 @@ GPTQ_API int gptq_trailing_update(float* W, int64_t ldw, const float* E, int64_t
  *   Operand elements must be finite and below 2^127 in magnitude.
  */
 /*
- * Which launches take the split products is decided per launch from its count of 256 x 256 tiles: at least 205, and at
- * least 80 % of the workgroup slots of its last round of 256 taken.  gptq_set_split_min_tiles(t) with t > 0 replaces
- * that rule by "at least t tiles" for every later call of the process (t <= 0 restores it) and returns the previous
- * setting: a tuning and test knob -- the results of a call depend on it only through rounding.  Not meant to be
- * changed while another thread is inside a library call.
+ * Which launches take the split products is decided per launch from its count of 256 x 256 tiles: at least 144.
+ * gptq_set_split_min_tiles(t) with t > 0 replaces that minimum for every later call of the process (t <= 0 restores
+ * it) and returns the previous setting: a tuning and test knob -- the results of a call depend on it only through
+ * rounding.  Not meant to be changed while another thread is inside a library call.
  */
 GPTQ_API int gptq_set_split_min_tiles(int tiles);
 GPTQ_API size_t gptq_trailing_update_split_workspace_bytes(int64_t r, int64_t ncols);

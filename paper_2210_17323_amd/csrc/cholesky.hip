@@ -283,21 +283,18 @@ CholWs chol_ws_layout(void* ws, int64_t n, bool with_split = true) {
     const size_t nblk = (size_t)ceil_div((int64_t)n1, NB), nouter = (size_t)ceil_div((int64_t)n1, OB);
     size_t off = 0;
     CholWs l{};
-    char* base = static_cast<char*>(ws);
+    // with ws == nullptr only the total is wanted: no pointer is formed (arithmetic on a null pointer is undefined)
+    uintptr_t base = reinterpret_cast<uintptr_t>(ws);
+    auto at = [&](size_t bytes) { const size_t o = off; off += round_up(bytes, 256); return ws ? reinterpret_cast<void*>(base + o) : nullptr; };
     l.ld2 = (int64_t)round_up(n1, 4);
-    l.dinv = reinterpret_cast<float*>(base + off);  off += round_up(nblk * NB * NB * sizeof(float), 256);       // R_bb^-1, dense
-    l.T = reinterpret_cast<float*>(base + off);     off += round_up(n1 * OB * sizeof(float), 256);              // a column panel [n x 1024]
-    l.T2 = reinterpret_cast<float*>(base + off);    off += round_up((size_t)OB * l.ld2 * sizeof(float), 256);   // a row panel [1024 x n]
-    l.Uoo = reinterpret_cast<float*>(base + off);   off += round_up(nouter * OB * OB * sizeof(float), 256);     // U_oo of every outer block, dense
-    l.tmp = reinterpret_cast<float*>(base + off);   off += round_up((size_t)NB * OB * sizeof(float), 256);      // one row block of a product
-    l.planes = reinterpret_cast<unsigned char*>(base + off);                                                    // bf16 pieces of a column panel (split products)
-    l.planes2 = nullptr;                                                                                        // ... and of a row block (the inverse)
-    if (with_split && (int64_t)n1 >= 2 * OB) {
-        off += round_up(split_planes_bytes((int64_t)n1), 256);
-        l.planes2 = reinterpret_cast<unsigned char*>(base + off);
-        off += round_up(split_planes_bytes((int64_t)n1), 256);
-    } else {
-        l.planes = nullptr;
+    l.dinv = static_cast<float*>(at(nblk * NB * NB * sizeof(float)));        // R_bb^-1, dense
+    l.T = static_cast<float*>(at(n1 * OB * sizeof(float)));                  // a column panel [n x 1024]
+    l.T2 = static_cast<float*>(at((size_t)OB * l.ld2 * sizeof(float)));      // a row panel [1024 x n]
+    l.Uoo = static_cast<float*>(at(nouter * OB * OB * sizeof(float)));       // U_oo of every outer block, dense
+    l.tmp = static_cast<float*>(at((size_t)NB * OB * sizeof(float)));        // one row block of a product
+    if (with_split && (int64_t)n1 >= 2 * OB) {                               // split products: bf16 pieces of a column panel
+        l.planes = static_cast<unsigned char*>(at(split_planes_bytes((int64_t)n1)));
+        l.planes2 = static_cast<unsigned char*>(at(split_planes_bytes((int64_t)n1)));      // ... and of a row block (the inverse)
     }
     l.total = off + 256;
     return l;

@@ -289,16 +289,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
 }
 
-// A launch of the split kernel pays when it fills the chip's 256 CUs well: one 256 x 256 tile per workgroup, one workgroup
-// per CU, ~200 us per tile -- so at least 80 % of the slots of its last round of workgroups should be taken.
-// gptq_set_split_min_tiles replaces the rule by a plain minimum (tests force the split products onto small matrices).
+// A launch takes the split kernel from 144 tiles of 256 x 256 on (one tile per workgroup, one workgroup per CU, ~200 us
+// per tile): measured on the 12288-, 14336- and 4096-column layers, a plain minimum anywhere from 96 to 192 tiles gives
+// the same times within noise, below that the float32 kernel's smaller tiles fill the chip better.
+// gptq_set_split_min_tiles replaces the minimum (tests force the split products onto small matrices).
+constexpr int SPLIT_MIN_TILES = 144;
 static std::atomic<int> g_split_min_tiles{0};
 bool split_pays(int64_t tiles) {
     const int forced = g_split_min_tiles.load(std::memory_order_relaxed);
-    if (forced > 0) return tiles >= forced;
-    if (tiles < 205) return false;
-    const int64_t rounds = ceil_div(tiles, 256);
-    return tiles * 5 >= rounds * 256 * 4;
+    return tiles >= (forced > 0 ? forced : SPLIT_MIN_TILES);
 }
 
 size_t split_planes_bytes(int64_t rows) {
