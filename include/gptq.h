@@ -116,7 +116,10 @@ GPTQ_API int gptq_hessian_symmetrize(float* H, int64_t ldh, int64_t n, void* str
  *             gptq_check_info.  percdamp < 0 is invalid; percdamp == 0 is allowed.
  *   Computed as a Cholesky factorisation taken from the last column backwards, H + lambda I = R R^T with R
  *   upper triangular, followed by the triangular inverse U = R^-1 (the same matrix, by uniqueness of
- *   the Cholesky factor), all in float32.
+ *   the Cholesky factor), all in float32; the rank-1024 updates that carry most of the flops multiply three-piece
+ *   bfloat16 splits of their float32 operands on the bf16 matrix cores when they are large (see
+ *   gptq_symmetric_update_split below: the error of a float32 multiply-add), which is also what the second half of
+ *   the workspace is for.
  *   Part of the work is enqueued on helper streams owned by the library (created once per host thread and
  *   device, default priority) and joined back with events: when the call returns, everything it enqueued
  *   is ordered on `stream`, and nothing of it starts before the work already on `stream`.
@@ -129,7 +132,7 @@ GPTQ_API int gptq_damp_cholesky_inverse(float* H_U, int64_t ld, int64_t n, float
  * Step 2 for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc) and therefore cannot bring a workspace: the same kernels and the same
  * result as gptq_damp_cholesky_inverse, with the scratch space in a fixed device array that is part of the
- * library image (about 51 MiB, resident on every GPU the library runs on until the process ends).
+ * library image (float32 kernels only; about 51 MiB, resident on every GPU the library runs on until the process ends).
  *
  *   n <= GPTQ_NOALLOC_MAX_N (gptq_noalloc_max_n() returns it); a larger n is GPTQ_ERR_UNSUPPORTED and nothing is
  *   enqueued.  H_U, ld, percdamp, info_dev and the result are as for gptq_damp_cholesky_inverse.
@@ -173,6 +176,9 @@ GPTQ_API int gptq_check_info(const int* info_dev, int* host_info, void* stream);
  *            E[:, j] = (W[:, j] - Q[:, j]) / U[j][j] at the time column j is quantized (Alg. 1).  Its
  *            sum over rows equals (1/2) tr((W-Q)(H + lambda I)(W-Q)^T).  May be NULL.
  *   ws       at least gptq_quantize_layer_workspace_bytes(r, n, block, group) bytes, 256-byte aligned.
+ *   The update of column j's block and the rank-128 updates inside an outer block of 1024 columns are float32; the
+ *   deferred rank-1024 updates beyond it are float32 matrix-core products or, when large, the split products of
+ *   gptq_trailing_update_split below.
  *   r == 0 or n == 0 is a valid no-op.  Like step 2, the call puts part of its work on the library's helper
  *   stream and joins it back before returning.
  */
