@@ -304,3 +304,61 @@ def test_full_size_decoder_block_3_and_4_bits():
                 _say(f"  {bits}-bit {name}: rows {rows.tolist()} ok at {time.time() - t0:.1f}s")
         del factors, res
     _say(f"full-size block done in {time.time() - t0:.1f}s")
+
+
+def _sampled_products(A, B_rows, idx_r, idx_c):
+    """float64 dot products A[i, :] . B_rows[:, j] for the sampled (i, j), and the same with magnitudes."""
+    a = A[idx_r].double().cpu().numpy()                       # [s x k]
+    b = B_rows[:, idx_c].double().cpu().numpy().T             # [s x k]
+    return np.einsum("sk,sk->s", a, b), np.einsum("sk,sk->s", np.abs(a), np.abs(b))
+
+
+def test_split_products_at_bench_size_on_sampled_outputs():
+    # The deferred rank-1024 updates in the launch configuration bench.py times (roofline_split_gemm: W[12288 x 24576]
+    # -= E U, and the factorisation's symmetric update of 47104 rows), on sampled outputs against float64 dot products
+    # of the same float32 operands; the float32 kernel on the same samples beside it.
+    import paper_2210_17323_amd as g
+    g.lib()
+    k = 1024
+    gen = torch.Generator(device="cuda").manual_seed(17323)
+    rnd = lambda *shape: torch.randn(*shape, device="cuda", generator=gen)
+    rng = np.random.default_rng(17323)
+    r, nc = 12288, 24576
+    _say(f"split trailing update {r} x {nc}")
+    E = rnd(r, k) * torch.exp(rnd(r, k))
+    U = rnd(k, nc) / 32
+    W0 = rnd(r, nc)
+    W = W0.clone()
+    ws = torch.empty(g.gptq_trailing_update_split_workspace_bytes(r, nc), dtype=torch.uint8, device="cuda")
+    g.gptq_trailing_update_split(W, E, U, ws)
+    W32 = W0.clone()
+    g.gptq_trailing_update(W32, E, U)
+    torch.cuda.synchronize()
+    ir, ic = rng.integers(0, r, 8192), rng.integers(0, nc, 8192)
+    prod, mag = _sampled_products(E, U, ir, ic)
+    w0 = W0[ir, ic].double().cpu().numpy()
+    err = np.abs(W[ir, ic].double().cpu().numpy() - (w0 - prod))
+    err32 = np.abs(W32[ir, ic].double().cpu().numpy() - (w0 - prod))
+    bound = 2.0 ** -18 * mag + 2.0 ** -22 * np.abs(w0)
+    rel = float(np.linalg.norm(err) / np.linalg.norm(prod))
+    rel32 = float(np.linalg.norm(err32) / np.linalg.norm(prod))
+    _say(f"  sampled products: split rel. error {rel:.3e} (worst / bound {float((err / bound).max()):.3f}), float32 kernel {rel32:.3e}")
+    assert np.all(err <= bound) and rel <= 5e-7 and rel <= 1.5 * rel32 + 1e-8
+    del E, U, W0, W, W32, ws
+
+    n = 47104
+    _say(f"split symmetric update n = {n}")
+    P = rnd(n, k) / 32
+    H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
+    ws = torch.empty(g.gptq_symmetric_update_split_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    g.gptq_symmetric_update_split(H, P, ws)
+    torch.cuda.synchronize()
+    ir, ic = rng.integers(0, n, 8192), rng.integers(0, n, 8192)
+    lo, hi = np.minimum(ir, ic), np.maximum(ir, ic)               # upper triangle
+    prod, mag = _sampled_products(P, P.T, lo, hi)
+    err = np.abs(H[lo, hi].double().cpu().numpy() + prod)
+    rel = float(np.linalg.norm(err) / np.linalg.norm(prod))
+    _say(f"  sampled products: rel. error {rel:.3e} (worst / bound {float((err / (2.0 ** -18 * mag)).max()):.3f})")
+    assert np.all(err <= 2.0 ** -18 * mag) and rel <= 5e-7
+    below = (ir // 256) > (ic // 256)                             # tiles entirely below the diagonal stay untouched
+    assert float(H[ir[below], ic[below]].abs().max()) == 0.0
