@@ -106,6 +106,8 @@ def test_argument_validation_happens_on_the_host():
     assert tus(one, 128, one, 1024, one, 256, 256, 256, 1024, one, 1 << 30, None) == INVALID                           # ldw < ncols
     assert tus(one, 256, one, 1024, one, 256, 0, 256, 1024, one, 1 << 30, None) == OK
     assert g.gptq_trailing_update_split_workspace_bytes(256, 512) == 3 * (3 * 32 * 16384) + 2 * 16384 + 256
+    prev = g.gptq_set_split_min_tiles(9)
+    assert g.gptq_set_split_min_tiles(-3) == 9 and g.gptq_set_split_min_tiles(prev) == 0      # a value <= 0 is the library's own rule
     sus = L.gptq_symmetric_update_split
     assert sus(one, 256, one, 1024, 256, 128, one, 1 << 30, None) == UNSUPPORTED
     assert sus(one, 256, one, 1024, 300, 1024, one, 1 << 30, None) == UNSUPPORTED
