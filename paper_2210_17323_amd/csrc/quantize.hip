@@ -604,9 +604,26 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
             }
             GPTQ_LAUNCH_CHECK();
             if (j1 < o1) {
+                // Inside the outer block the updates are batched once more, in pairs of blocks: after the first block of a
+                // pair only the second block's columns are brought up to date (rank 128, 128 columns wide); after the second,
+                // everything beyond the pair gets both blocks' contributions in one rank-256 product.  Same sums, associated
+                // differently: 16 instead of 28 block columns of the accumulators are read and written per outer block, and
+                // the wide products have twice the K.  Where the layer has many rows these products are what the step costs
+                // (Alg. 1 on a 49152 x 12288 layer 52.5 -> 50.6 ms; neutral at 12288 rows; the same batching in the
+                // factorisation made its chain slower, 11.6 -> 11.8 ms at n = 12288, and is not used there).
+                // A group grid that starts at the second block of a pair and reaches beyond it (a group of 384 columns) would
+                // see columns that still lack the first block's contribution: such layers keep one update per block.
+                const bool pairs = group <= QB || group % (2 * QB) == 0;
+                const int64_t idx = (j0 - o0) / QB;
                 GemmF32 g{};
-                g.A = E + (j0 - o0); g.lda = QOB; g.B = Bm + j0 * ldb + j1; g.ldb = ldb; g.C = Wk + j1; g.ldc = lay.ldk;
-                g.M = r; g.N = o1 - j1; g.K = nbk; g.alpha = rf ? 1.f : -1.f; g.b_is_nk = false; g.overwrite = false;
+                g.lda = QOB; g.ldb = ldb; g.ldc = lay.ldk; g.M = r; g.alpha = rf ? 1.f : -1.f; g.b_is_nk = false; g.overwrite = false;
+                if (!pairs) {
+                    g.A = E + (j0 - o0); g.B = Bm + j0 * ldb + j1; g.C = Wk + j1; g.N = o1 - j1; g.K = nbk;
+                } else if (idx % 2 == 0) {
+                    g.A = E + (j0 - o0); g.B = Bm + j0 * ldb + j1; g.C = Wk + j1; g.N = std::min<int64_t>(QB, o1 - j1); g.K = nbk;
+                } else {
+                    g.A = E + (j0 - QB - o0); g.B = Bm + (j0 - QB) * ldb + j1; g.C = Wk + j1; g.N = o1 - j1; g.K = QB + nbk;
+                }
                 const int rc = launch_gemm_f32(g, s);
                 if (rc) return rc;
             }
