@@ -610,7 +610,9 @@ static int alg1_run(bool rf, const void* W, int wdtype, int64_t ldw, int64_t r, 
                 // differently: 16 instead of 28 block columns of the accumulators are read and written per outer block, and
                 // the wide products have twice the K.  Where the layer has many rows these products are what the step costs
                 // (Alg. 1 on a 49152 x 12288 layer 52.5 -> 50.6 ms; neutral at 12288 rows; the same batching in the
-                // factorisation made its chain slower, 11.6 -> 11.8 ms at n = 12288, and is not used there).
+                // factorisation made its chain slower, 11.6 -> 11.8 ms at n = 12288, and is not used there; a full binary
+                // tree of batches -- rank 512 after the fourth block -- gained 0.4 ms more at 49152 rows and lost 1.7 ms on
+                // the 12288 x 49152 layer, whose chain then waits for longer products).
                 // A group grid that starts at the second block of a pair and reaches beyond it (a group of 384 columns) would
                 // see columns that still lack the first block's contribution: such layers keep one update per block.
                 const bool pairs = group <= QB || group % (2 * QB) == 0;
