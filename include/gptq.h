@@ -53,6 +53,18 @@ GPTQ_API int gptq_version(void);
 GPTQ_API const char* gptq_last_error(void);
 
 /*
+ * The only state the library keeps between calls: three helper streams (default priority, non-blocking) and 32 events per
+ * host thread and device, created by the first call of gptq_damp_cholesky* / gptq_quantize_layer* on that thread and
+ * device and used by the later ones (two caller streams of one thread therefore share them: their calls are correct
+ * but do not overlap each other's helper work).  gptq_release_thread_resources waits for the calling thread's helper
+ * streams on the current device and destroys them and their events; the next call that needs them creates new ones.
+ * It must not be called while a HIP graph capture that includes a library call is in progress on this thread, and
+ * graphs captured earlier stay valid (a graph does not refer to the streams it was captured on).  GPTQ_OK also when
+ * there was nothing to release.
+ */
+GPTQ_API int gptq_release_thread_resources(void);
+
+/*
  * Step 1 -- Hessian of the layer-wise objective, H = 2 X X^T (Section 2, text before Eq. 2; Alg. 1 caption).
  *
  *   H   [n x n] float32, ldh >= n.  Accumulated in place: H += 2 X X^T.  The caller zero-fills H

@@ -4,7 +4,7 @@ All arithmetic runs in the hand-written HIP kernels under csrc/; PyTorch only pr
 memory and streams.  There is no CPU fallback: loading fails loudly if the library is missing.
 """
 from .binding import (  # noqa: F401
-    GptqError, lib, load_library, version, exported_symbols,
+    GptqError, lib, load_library, version, exported_symbols, gptq_release_thread_resources,
     gptq_hessian_accumulate, gptq_hessian_accumulate_workspace_bytes, gptq_hessian_accumulate_launches, gptq_hessian_symmetrize,
     gptq_hessian_accumulate_token_major, gptq_hessian_accumulate_token_major_workspace_bytes,
     gptq_damp_cholesky_inverse, gptq_damp_cholesky_inverse_workspace_bytes, gptq_check_info,

@@ -85,7 +85,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     for name in ("gptq_hessian_accumulate", "gptq_hessian_symmetrize", "gptq_damp_cholesky_inverse", "gptq_check_info",
                  "gptq_quantize_layer", "gptq_pack", "gptq_unpack", "gptq_damp_cholesky_inverse_noalloc",
                  "gptq_hessian_accumulate_token_major", "gptq_dequantize_packed", "gptq_matvec_packed",
-                 "gptq_trailing_update_split", "gptq_symmetric_update_split"):
+                 "gptq_trailing_update_split", "gptq_symmetric_update_split", "gptq_release_thread_resources"):
         getattr(L, name).restype = ci
     if path == LIB_PATH:
         _lib = L
@@ -98,6 +98,11 @@ def lib() -> ctypes.CDLL:
 
 def version() -> int:
     return lib().gptq_version()
+
+
+def gptq_release_thread_resources() -> None:
+    """Destroys the calling thread's helper streams and events on the current device (the next call recreates them)."""
+    _check(lib().gptq_release_thread_resources())
 
 
 def _check(rc: int):

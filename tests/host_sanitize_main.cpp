@@ -23,6 +23,7 @@ int main() {
     const size_t big = (size_t)1 << 40;
 
     EXPECT(gptq_version() >= 100);
+    EXPECT(gptq_release_thread_resources() == GPTQ_OK);
     // sizes over the whole range of shapes, including the largest workload and degenerate ones
     for (int64_t n : {(int64_t)0, (int64_t)1, (int64_t)127, (int64_t)4096, (int64_t)14336, (int64_t)49152, (int64_t)1 << 20}) {
         (void)gptq_damp_cholesky_inverse_workspace_bytes(n);

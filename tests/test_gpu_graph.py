@@ -84,3 +84,24 @@ def test_layer_solve_replays_from_a_graph(forced_split):
                 assert torch.equal(a, w), f"replay {rep} (inputs {k}): {name} differs from the eager result"
     finally:
         g.gptq_set_split_min_tiles(prev)
+
+
+def test_helper_streams_can_be_released_and_come_back():
+    # the library's only state between calls: released, the next call recreates it and gives the same bits
+    import paper_2210_17323_amd as g
+    g.lib()
+    r, n, t, bits = 256, 2304, 3000, 4
+    lay = configs.scaled_twin(configs.config3()[1], n, r=r, m=t)
+    b = _Buffers(g, r, n, t, torch.float16, bits)
+    b.X.copy_(lay.x.tile().cuda()); b.W.copy_(lay.weights().cuda())
+    b.solve(g)
+    torch.cuda.synchronize()
+    want = b.results()
+    g.gptq_release_thread_resources()
+    g.gptq_release_thread_resources()              # a second release finds nothing and is a no-op
+    for out in (b.codes, b.packed):
+        out.fill_(0)
+    b.solve(g)
+    torch.cuda.synchronize()
+    for name, a, w in zip(("R", "codes", "scales", "zeros", "half_E2", "packed", "info"), b.results(), want):
+        assert torch.equal(a, w), name

@@ -98,6 +98,7 @@ def test_argument_validation_happens_on_the_host():
     assert tu(one, 60, one, 8, one, 64, 4, 64, 8, None) == INVALID          # ldw < ncols
     assert tu(None, 64, one, 8, one, 64, 4, 64, 8, None) == INVALID
     assert tu(one, 64, one, 8, one, 64, 0, 64, 8, None) == OK and tu(one, 64, one, 8, one, 64, 4, 64, 0, None) == OK
+    assert L.gptq_release_thread_resources() == OK          # nothing created on this thread: a no-op
     tus = L.gptq_trailing_update_split
     assert tus(one, 256, one, 1024, one, 256, 256, 256, 512, one, 1 << 30, None) == UNSUPPORTED and "1024" in _err()   # k
     assert tus(one, 256, one, 1024, one, 256, 200, 256, 1024, one, 1 << 30, None) == UNSUPPORTED                      # r % 256
